@@ -1,0 +1,177 @@
+/*
+ * saw.h -- C ABI of the SAW-INT4 KV-cache hot path for AMD MI355X (gfx950).
+ *
+ * Two stages (paper Sec. 3 and Sec. 4.1):
+ *   1. saw_rotate_quant_store: block-diagonal Hadamard rotation, token-wise asymmetric
+ *      INT4 quantisation and paged store of new K/V tokens, fused in one kernel;
+ *   2. saw_paged_decode_attn: one decode step o = softmax(q K^T / sqrt(d)) V read
+ *      straight from the INT4 pages, with q rotated instead of un-rotating K and the
+ *      output rotated back once for V.
+ * plus saw_dequant_pages (read-back / flatten), and a 16-bit-KV paged decode
+ * (saw_kv16_*) that serves as the same-run unquantised comparison.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or keeps them.  `saw_cache_t` itself is a host struct.
+ *   - Calls only validate arguments on the host and enqueue kernels on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream); they never
+ *     synchronise.  Return 0 on success, a negative SAW_E* code otherwise; on error
+ *     nothing was launched.
+ *   - Cache layout (one layer):
+ *       codes  [num_pages][n_kv_heads][page_size][head_dim/2]  uint8
+ *              byte j of a vector = code(2j) | code(2j+1) << 4          (App. A.1)
+ *       meta   [num_pages][n_kv_heads][page_size][2]            float32 (scale, zero)
+ *     separately for K and V.  A vector is dequantised as scale * (code - zero)
+ *     (App. A.1) and lives in the rotated space when its rotate_mask bit is set.
+ *   - page_table is [n_seqs][max_pages_per_seq] int32: logical page i of sequence b
+ *     is physical page page_table[b][i]; logical position p sits in logical page
+ *     p / page_size at slot p % page_size.
+ *   - Query head j reads kv head j / (n_q_heads / n_kv_heads).
+ *   - Supported: page_size 16; head_dim 64 or 128; had_block 1 (no rotation), 16, 32,
+ *     64 or 128 with had_block <= head_dim; n_q_heads / n_kv_heads in {1, 2, 4, 8}.
+ */
+#ifndef SAW_H_
+#define SAW_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAW_VERSION 100
+
+/* element types */
+#define SAW_F16  1
+#define SAW_BF16 2
+#define SAW_F32  3
+
+/* rotate_mask bits (Sec. 3: K~ = quant(K H), V~ = quant(V H); the K-only variant clears bit 1) */
+#define SAW_ROT_K 1
+#define SAW_ROT_V 2
+
+/* error codes */
+#define SAW_OK          0
+#define SAW_EINVAL     -1   /* unsupported shape, block size, dtype, stride or alignment */
+#define SAW_ENULL      -2   /* a required pointer is NULL                               */
+#define SAW_EWORKSPACE -3   /* workspace smaller than saw_decode_workspace_bytes(...)   */
+#define SAW_ELAUNCH    -4   /* the HIP runtime refused the launch                       */
+
+typedef void* saw_stream_t;
+
+typedef struct saw_cache {
+  uint8_t* k_codes;     /* device, layout above */
+  uint8_t* v_codes;
+  float*   k_meta;
+  float*   v_meta;
+  int32_t  num_pages;
+  int32_t  n_kv_heads;
+  int32_t  page_size;   /* 16 */
+  int32_t  head_dim;    /* 64 | 128 */
+  int32_t  had_block;   /* h of BDR-h (Sec. 3 eq. 2-3): 1 | 16 | 32 | 64 | 128 */
+  int32_t  rotate_mask; /* SAW_ROT_K | SAW_ROT_V */
+} saw_cache_t;
+
+int saw_version(void);
+const char* saw_strerror(int code);
+
+/*
+ * Fused rotate -> quantise -> pack -> paged store (Sec. 3 eqs. 1-3, App. A.1, App. A.4).
+ *
+ * For each new token t < T and kv head g: y = x H_blk (H_blk = diag of orthonormal
+ * order-h Sylvester Hadamard blocks; skipped when h == 1 or the tensor's rotate_mask
+ * bit is clear), then s = (max y - min y)/15, z = round(-min y / s),
+ * c_i = clip(round(y_i/s) + z, 0, 15) over all head_dim channels (one (s, z) per
+ * token and head), round = half to even.  A constant vector stores s = |y_0|
+ * (1 if zero), z = -sign(y_0), codes 0.  Arithmetic is fp32 on exactly widened inputs.
+ *
+ *   K, V        device, [T][n_kv_heads][head_dim] of in_dtype (SAW_F16 | SAW_BF16); the
+ *               distance between tokens is token_stride_elems (>= n_kv_heads*head_dim,
+ *               multiple of 8); base pointers 16-byte aligned.
+ *   page_table  device, [n_seqs][max_pages_per_seq].
+ *   slots       device, [T][2] int32 = (sequence index, logical position).  Slots must be
+ *               unique within a call.  A token whose sequence index, position or page id
+ *               is out of range (seq outside [0, n_seqs), position outside
+ *               [0, max_pages_per_seq*page_size), page outside [0, num_pages)) is skipped.
+ * T == 0 is a no-op.
+ */
+int saw_rotate_quant_store(const saw_cache_t* cache, const void* K, const void* V,
+                           int32_t in_dtype, int64_t T, int64_t token_stride_elems,
+                           const int32_t* page_table, int32_t n_seqs, int32_t max_pages_per_seq,
+                           const int32_t* slots, saw_stream_t stream);
+
+/*
+ * Bytes of scratch saw_paged_decode_attn needs for these arguments (split-KV partial
+ * results: [B][n_q_heads][splits][head_dim + 2] float32).  max_seq_len and num_splits
+ * have the meaning below; returns 0 on invalid arguments.
+ */
+size_t saw_decode_workspace_bytes(const saw_cache_t* cache, int32_t B, int32_t n_q_heads,
+                                  int32_t max_seq_len, int32_t num_splits);
+
+/*
+ * The split-KV geometry the decode calls will use for these arguments (host-side helper for
+ * reporting): partitions per sequence and tokens per partition.  Either output may be NULL.
+ */
+int saw_decode_plan(const saw_cache_t* cache, int32_t B, int32_t max_seq_len, int32_t num_splits,
+                    int32_t* splits_out, int32_t* chunk_tokens_out);
+
+/*
+ * One decode step over the INT4 cache (Sec. 2: o = softmax(q K^T/sqrt(d)) V; Sec. 4.1 and
+ * App. A.4: logits (q H_blk) dequant(K~)^T, output Score dequant(V~) H_blk).
+ *
+ *   q           device, [B][n_q_heads][head_dim] of q_dtype (SAW_F16 | SAW_BF16 | SAW_F32), dense.
+ *   seq_lens    device, [B] int32: tokens of sequence b to attend to, positions [0, len).
+ *               Lengths are clamped to the bound below.  len == 0 gives a zero output row.
+ *   max_seq_len host-side upper bound on seq_lens (sizes the split grid); <= 0 means
+ *               max_pages_per_seq * page_size.  Must not exceed that product.
+ *   sm_scale    logit scale; <= 0 selects 1/sqrt(head_dim).
+ *   out         device, [B][n_q_heads][head_dim] of out_dtype (SAW_F32 | SAW_F16 | SAW_BF16).
+ *   workspace   device scratch of at least saw_decode_workspace_bytes(...) bytes, 16-byte
+ *               aligned; contents are overwritten; concurrent calls need separate workspaces.
+ *   num_splits  split-KV factor (partitions of the context per sequence, merged by
+ *               log-sum-exp); 0 picks one from the shape.  Max 1024.
+ */
+int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dtype,
+                          int32_t B, int32_t n_q_heads,
+                          const int32_t* page_table, int32_t max_pages_per_seq,
+                          const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                          void* out, int32_t out_dtype,
+                          void* workspace, size_t workspace_bytes, int32_t num_splits,
+                          saw_stream_t stream);
+
+/*
+ * Dequantise positions [pos_begin, pos_end) of sequence `seq` into dense fp32
+ * [pos_end - pos_begin][n_kv_heads][head_dim] buffers: x^ = s (c - z) (App. A.1).  With
+ * unrotate != 0 the rotated tensors are multiplied by H_blk once more, which returns them
+ * to the original space (H is symmetric and orthonormal, App. A.4).  Either output may be
+ * NULL to skip it.  The caller guarantees the positions are backed by valid pages.
+ */
+int saw_dequant_pages(const saw_cache_t* cache, const int32_t* page_table,
+                      int32_t max_pages_per_seq, int32_t seq, int32_t pos_begin, int32_t pos_end,
+                      int32_t unrotate, float* k_out, float* v_out, saw_stream_t stream);
+
+/*
+ * 16-bit-KV comparison path (the unquantised cache the paper measures INT4 against):
+ * pages are [num_pages][n_kv_heads][page_size][head_dim] of `dtype` (SAW_F16 | SAW_BF16),
+ * no rotation, no metadata.  Same argument meaning as the INT4 calls; `cache` supplies
+ * only the shape fields (pointers and had_block / rotate_mask are ignored).
+ */
+int saw_kv16_store(const saw_cache_t* shape, void* k_pages, void* v_pages, int32_t dtype,
+                   const void* K, const void* V, int64_t T, int64_t token_stride_elems,
+                   const int32_t* page_table, int32_t n_seqs, int32_t max_pages_per_seq,
+                   const int32_t* slots, saw_stream_t stream);
+
+int saw_kv16_paged_decode_attn(const saw_cache_t* shape, const void* k_pages, const void* v_pages,
+                               int32_t dtype, const void* q, int32_t q_dtype,
+                               int32_t B, int32_t n_q_heads,
+                               const int32_t* page_table, int32_t max_pages_per_seq,
+                               const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                               void* out, int32_t out_dtype,
+                               void* workspace, size_t workspace_bytes, int32_t num_splits,
+                               saw_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAW_H_ */

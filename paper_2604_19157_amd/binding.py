@@ -1,0 +1,198 @@
+"""ctypes binding of the C ABI declared in ``include/saw.h``.
+
+Argument marshalling only: torch supplies device memory and the current stream, every
+step of the path runs in the HIP kernels of ``libsaw.so``.  There is no CPU fallback: if
+the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsaw.so")
+
+SAW_F16, SAW_BF16, SAW_F32 = 1, 2, 3
+ROT_K, ROT_V = 1, 2
+_DT = {torch.float16: SAW_F16, torch.bfloat16: SAW_BF16, torch.float32: SAW_F32}
+
+
+class SawCacheStruct(ctypes.Structure):
+    _fields_ = [("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+                ("k_meta", ctypes.c_void_p), ("v_meta", ctypes.c_void_p),
+                ("num_pages", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("page_size", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("had_block", ctypes.c_int32), ("rotate_mask", ctypes.c_int32)]
+
+
+class SawError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib().saw_strerror(code).decode()} ({code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libsaw.so`` (built by ``__graft_entry__.build()``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+        cp = ctypes.POINTER(SawCacheStruct)
+        L.saw_version.restype = ctypes.c_int
+        L.saw_strerror.restype = ctypes.c_char_p
+        L.saw_strerror.argtypes = [ctypes.c_int]
+        L.saw_rotate_quant_store.argtypes = [cp, vp, vp, i32, i64, i64, vp, i32, i32, vp, vp]
+        L.saw_decode_workspace_bytes.restype = sz
+        L.saw_decode_workspace_bytes.argtypes = [cp, i32, i32, i32, i32]
+        L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
+        L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.saw_kv16_store.argtypes = [cp, vp, vp, i32, vp, vp, i64, i64, vp, i32, i32, vp, vp]
+        L.saw_kv16_paged_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32,
+                                                 vp, i32, vp, sz, i32, vp]
+        _lib = L
+    return _lib
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise SawError(code, where)
+
+
+class Cache:
+    """One layer's INT4 paged cache: device tensors plus the shape/rotation descriptor."""
+
+    def __init__(self, num_pages, n_kv_heads, head_dim, had_block, rotate_mask=ROT_K | ROT_V,
+                 page_size=16, device="cuda", zero=True):
+        alloc = torch.zeros if zero else torch.empty
+        self.k_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
+        self.v_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
+        self.k_meta = alloc((num_pages, n_kv_heads, page_size, 2), dtype=torch.float32, device=device)
+        self.v_meta = alloc((num_pages, n_kv_heads, page_size, 2), dtype=torch.float32, device=device)
+        self.num_pages, self.n_kv_heads, self.page_size = num_pages, n_kv_heads, page_size
+        self.head_dim, self.had_block, self.rotate_mask = head_dim, had_block, rotate_mask
+
+    def struct(self) -> SawCacheStruct:
+        return SawCacheStruct(self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_meta.data_ptr(),
+                              self.v_meta.data_ptr(), self.num_pages, self.n_kv_heads, self.page_size,
+                              self.head_dim, self.had_block, self.rotate_mask)
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in (self.k_codes, self.v_codes, self.k_meta, self.v_meta))
+
+
+def rotate_quant_store(cache: Cache, K, V, page_table, slots):
+    """saw_rotate_quant_store: K, V ``[T][Hkv][d]`` fp16/bf16, page_table ``[n_seqs][max_pages]`` int32,
+    slots ``[T][2]`` int32, all on the device."""
+    T = K.shape[0]
+    assert K.dtype == V.dtype and K.shape == V.shape and K.stride(2) == 1 and K.stride(1) == cache.head_dim
+    assert V.stride() == K.stride() and page_table.dtype == torch.int32 and slots.dtype == torch.int32
+    assert page_table.is_contiguous() and slots.is_contiguous() and slots.shape == (T, 2)
+    st = cache.struct()
+    _check(lib().saw_rotate_quant_store(ctypes.byref(st), _ptr(K), _ptr(V), _DT[K.dtype], T,
+                                        K.stride(0) if T > 1 else cache.n_kv_heads * cache.head_dim,
+                                        _ptr(page_table), page_table.shape[0], page_table.shape[1],
+                                        _ptr(slots), _stream()), "saw_rotate_quant_store")
+
+
+def decode_workspace_bytes(cache: Cache, B, n_q_heads, max_seq_len, num_splits=0) -> int:
+    st = cache.struct()
+    return int(lib().saw_decode_workspace_bytes(ctypes.byref(st), B, n_q_heads, max_seq_len, num_splits))
+
+
+def decode_plan(cache: Cache, B, max_seq_len, num_splits=0):
+    st = cache.struct()
+    s, c = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().saw_decode_plan(ctypes.byref(st), B, max_seq_len, num_splits, ctypes.byref(s), ctypes.byref(c)),
+           "saw_decode_plan")
+    return s.value, c.value
+
+
+def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,
+                      out_dtype=torch.float32, workspace=None, num_splits=0):
+    """saw_paged_decode_attn: q ``[B][Hq][d]``; returns ``out [B][Hq][d]``."""
+    B, Hq, d = q.shape
+    assert q.is_contiguous() and page_table.is_contiguous() and seq_lens.dtype == torch.int32
+    bound = max_seq_len if max_seq_len > 0 else page_table.shape[1] * cache.page_size
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=out_dtype, device=q.device)
+    need = decode_workspace_bytes(cache, B, Hq, bound, num_splits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = cache.struct()
+    _check(lib().saw_paged_decode_attn(ctypes.byref(st), _ptr(q), _DT[q.dtype], B, Hq, _ptr(page_table),
+                                       page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
+                                       _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
+                                       num_splits, _stream()), "saw_paged_decode_attn")
+    return out
+
+
+def dequant_pages(cache: Cache, page_table, seq, pos_begin, pos_end, unrotate=False, want_k=True, want_v=True):
+    """saw_dequant_pages: returns fp32 ``(K^, V^)`` each ``[n][Hkv][d]`` (None if not requested)."""
+    n = pos_end - pos_begin
+    dev = cache.k_codes.device
+    k = torch.empty((n, cache.n_kv_heads, cache.head_dim), dtype=torch.float32, device=dev) if want_k else None
+    v = torch.empty((n, cache.n_kv_heads, cache.head_dim), dtype=torch.float32, device=dev) if want_v else None
+    st = cache.struct()
+    _check(lib().saw_dequant_pages(ctypes.byref(st), _ptr(page_table), page_table.shape[1], seq, pos_begin,
+                                   pos_end, int(bool(unrotate)), _ptr(k), _ptr(v), _stream()), "saw_dequant_pages")
+    return k, v
+
+
+class Kv16Cache:
+    """The 16-bit comparison cache: pages ``[num_pages][Hkv][16][d]`` of fp16/bf16."""
+
+    def __init__(self, num_pages, n_kv_heads, head_dim, dtype, page_size=16, device="cuda"):
+        self.k_pages = torch.zeros((num_pages, n_kv_heads, page_size, head_dim), dtype=dtype, device=device)
+        self.v_pages = torch.zeros((num_pages, n_kv_heads, page_size, head_dim), dtype=dtype, device=device)
+        self.num_pages, self.n_kv_heads, self.page_size, self.head_dim = num_pages, n_kv_heads, page_size, head_dim
+        self.dtype = dtype
+
+    def struct(self) -> SawCacheStruct:
+        return SawCacheStruct(0, 0, 0, 0, self.num_pages, self.n_kv_heads, self.page_size, self.head_dim, 1, 0)
+
+    def nbytes(self) -> int:
+        return 2 * self.k_pages.numel() * self.k_pages.element_size()
+
+
+def kv16_store(cache: Kv16Cache, K, V, page_table, slots):
+    T = K.shape[0]
+    assert K.dtype == cache.dtype and V.dtype == cache.dtype and K.stride() == V.stride()
+    st = cache.struct()
+    _check(lib().saw_kv16_store(ctypes.byref(st), _ptr(cache.k_pages), _ptr(cache.v_pages), _DT[cache.dtype],
+                                _ptr(K), _ptr(V), T, K.stride(0) if T > 1 else cache.n_kv_heads * cache.head_dim,
+                                _ptr(page_table), page_table.shape[0], page_table.shape[1], _ptr(slots),
+                                _stream()), "saw_kv16_store")
+
+
+def kv16_paged_decode_attn(cache: Kv16Cache, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,
+                           out_dtype=torch.float32, workspace=None, num_splits=0):
+    B, Hq, d = q.shape
+    bound = max_seq_len if max_seq_len > 0 else page_table.shape[1] * cache.page_size
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=out_dtype, device=q.device)
+    st = cache.struct()
+    need = int(lib().saw_decode_workspace_bytes(ctypes.byref(st), B, Hq, bound, num_splits))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib().saw_kv16_paged_decode_attn(ctypes.byref(st), _ptr(cache.k_pages), _ptr(cache.v_pages),
+                                            _DT[cache.dtype], _ptr(q), _DT[q.dtype], B, Hq, _ptr(page_table),
+                                            page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
+                                            _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
+                                            num_splits, _stream()), "saw_kv16_paged_decode_attn")
+    return out

@@ -1,0 +1,211 @@
+// C ABI entry points: argument validation on the host, then kernel launches on the
+// caller's stream.  No allocation, no synchronisation, no global state.
+#include <math.h>
+
+#include "saw_common.h"
+
+namespace saw {
+
+struct DecodeParams;  // defined in saw_decode.hip (kept opaque here)
+
+int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
+                 int32_t, int32_t, const int32_t*, hipStream_t);
+int launch_dequant(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t,
+                   float*, float*, hipStream_t);
+int launch_kv16_store(const saw_cache_t*, void*, void*, const void*, const void*, int64_t, int64_t,
+                      const int32_t*, int32_t, int32_t, const int32_t*, hipStream_t);
+int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void* v_pages, int kv_dtype,
+               const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
+               const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
+               const SplitPlan& plan, hipStream_t st);
+
+static bool shape_ok(const saw_cache_t* c) {
+  if (c->page_size != 16) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->n_kv_heads < 1 || c->num_pages < 1) return false;
+  return true;
+}
+
+static bool block_ok(const saw_cache_t* c) {
+  const int h = c->had_block;
+  if (!(h == 1 || h == 16 || h == 32 || h == 64 || h == 128)) return false;
+  if (h > c->head_dim) return false;
+  if (c->rotate_mask & ~(SAW_ROT_K | SAW_ROT_V)) return false;
+  return true;
+}
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// Split-KV plan.  Partitions are whole multiples of 64 tokens so every wavefront pass
+// starts on a page boundary.  The automatic choice aims at a few thousand work items so
+// that ragged batches balance over 256 compute units, with partitions of 256..1024 tokens.
+static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_len, int num_splits,
+                      SplitPlan* plan) {
+  const int64_t cap = (int64_t)max_pages * c->page_size;
+  if (cap <= 0 || cap > 0x7fffffffLL) return false;
+  int bound = (max_seq_len <= 0) ? (int)cap : max_seq_len;
+  if (bound > cap) return false;
+  if (num_splits < 0 || num_splits > 1024) return false;
+  const int units = (bound + 63) / 64;                    // 64-token units
+  int S = num_splits;
+  if (S == 0) {
+    const int64_t items = (int64_t)B * c->n_kv_heads;
+    int64_t want = (4096 + items - 1) / items;             // enough items to fill the chip
+    int64_t max_by_min_chunk = (units + 3) / 4;            // partitions of >= 256 tokens
+    int64_t min_by_max_chunk = (units + 15) / 16;          // partitions of <= 1024 tokens
+    int64_t s = want;
+    if (s > max_by_min_chunk) s = max_by_min_chunk;
+    if (s < min_by_max_chunk) s = min_by_max_chunk;
+    if (s < 1) s = 1;
+    if (s > 1024) s = 1024;
+    S = (int)s;
+  }
+  if (S > units) S = units;
+  if (S < 1) S = 1;
+  const int chunk_units = (units + S - 1) / S;
+  plan->chunk_tokens = chunk_units * 64;
+  plan->num_splits = (units + chunk_units - 1) / chunk_units;
+  plan->bound = bound;
+  return true;
+}
+
+}  // namespace saw
+
+using namespace saw;
+
+extern "C" {
+
+int saw_version(void) { return SAW_VERSION; }
+
+const char* saw_strerror(int code) {
+  switch (code) {
+    case SAW_OK: return "ok";
+    case SAW_EINVAL: return "invalid argument (shape, Hadamard block, dtype, stride or alignment)";
+    case SAW_ENULL: return "null pointer";
+    case SAW_EWORKSPACE: return "workspace too small";
+    case SAW_ELAUNCH: return "kernel launch failed";
+    default: return "unknown error";
+  }
+}
+
+int saw_rotate_quant_store(const saw_cache_t* c, const void* K, const void* V, int32_t in_dtype,
+                           int64_t T, int64_t token_stride_elems, const int32_t* page_table,
+                           int32_t n_seqs, int32_t max_pages_per_seq, const int32_t* slots,
+                           saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || !block_ok(c)) return SAW_EINVAL;
+  if (in_dtype != SAW_F16 && in_dtype != SAW_BF16) return SAW_EINVAL;
+  if (T < 0 || n_seqs < 1 || max_pages_per_seq < 1) return SAW_EINVAL;
+  if (T == 0) return SAW_OK;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !K || !V || !page_table || !slots)
+    return SAW_ENULL;
+  if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems & 7)) return SAW_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
+      (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
+    return SAW_EINVAL;
+  return launch_store(c, K, V, in_dtype, T, token_stride_elems, page_table, n_seqs, max_pages_per_seq,
+                      slots, (hipStream_t)stream);
+}
+
+size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_heads,
+                                  int32_t max_seq_len, int32_t num_splits) {
+  if (!c || !shape_ok(c) || B < 1 || n_q_heads < 1 || max_seq_len < 1) return 0;
+  SplitPlan plan;
+  const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return 0;
+  return (size_t)B * n_q_heads * plan.num_splits * (c->head_dim + 2) * sizeof(float);
+}
+
+int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_t num_splits,
+                    int32_t* splits_out, int32_t* chunk_tokens_out) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || B < 1 || max_seq_len < 1) return SAW_EINVAL;
+  SplitPlan plan;
+  const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
+  if (splits_out) *splits_out = plan.num_splits;
+  if (chunk_tokens_out) *chunk_tokens_out = plan.chunk_tokens;
+  return SAW_OK;
+}
+
+static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const void* vp, int kv_dtype,
+                         const void* q, int32_t q_dtype, int32_t B, int32_t Hq, const int32_t* pt,
+                         int32_t max_pages, const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                         void* out, int32_t out_dtype, void* ws, size_t ws_bytes, int32_t num_splits,
+                         saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c)) return SAW_EINVAL;
+  if (!kv16 && !block_ok(c)) return SAW_EINVAL;
+  if (kv16 && kv_dtype != SAW_F16 && kv_dtype != SAW_BF16) return SAW_EINVAL;
+  if (q_dtype != SAW_F16 && q_dtype != SAW_BF16 && q_dtype != SAW_F32) return SAW_EINVAL;
+  if (out_dtype != SAW_F16 && out_dtype != SAW_BF16 && out_dtype != SAW_F32) return SAW_EINVAL;
+  if (B < 1 || Hq < 1 || max_pages < 1) return SAW_EINVAL;
+  if (B > 65535 || c->n_kv_heads > 65535) return SAW_EINVAL;
+  if (Hq % c->n_kv_heads) return SAW_EINVAL;
+  const int G = Hq / c->n_kv_heads;
+  if (!(G == 1 || G == 2 || G == 4 || G == 8)) return SAW_EINVAL;
+  if (!kp || !vp || !q || !pt || !seq_lens || !out || !ws) return SAW_ENULL;
+  if (!kv16 && (!c->k_meta || !c->v_meta)) return SAW_ENULL;
+  if (!aligned16(kp) || !aligned16(vp) || !aligned16(ws)) return SAW_EINVAL;
+  if (!isfinite(sm_scale)) return SAW_EINVAL;
+  SplitPlan plan;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
+  const size_t need = (size_t)B * Hq * plan.num_splits * (c->head_dim + 2) * sizeof(float);
+  if (ws_bytes < need) return SAW_EWORKSPACE;
+  return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
+                    out_dtype, ws, plan, (hipStream_t)stream);
+}
+
+int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, int32_t B,
+                          int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                          const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                          int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                          int32_t num_splits, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
+                       max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
+                       workspace_bytes, num_splits, stream);
+}
+
+int saw_dequant_pages(const saw_cache_t* c, const int32_t* page_table, int32_t max_pages_per_seq,
+                      int32_t seq, int32_t pos_begin, int32_t pos_end, int32_t unrotate, float* k_out,
+                      float* v_out, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || !block_ok(c)) return SAW_EINVAL;
+  if (seq < 0 || pos_begin < 0 || pos_end < pos_begin || max_pages_per_seq < 1) return SAW_EINVAL;
+  if ((int64_t)pos_end > (int64_t)max_pages_per_seq * c->page_size) return SAW_EINVAL;
+  if (pos_end == pos_begin) return SAW_OK;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !page_table) return SAW_ENULL;
+  if (!k_out && !v_out) return SAW_OK;
+  if ((k_out && !aligned16(k_out)) || (v_out && !aligned16(v_out))) return SAW_EINVAL;
+  return launch_dequant(c, page_table, max_pages_per_seq, seq, pos_begin, pos_end, unrotate, k_out, v_out,
+                        (hipStream_t)stream);
+}
+
+int saw_kv16_store(const saw_cache_t* c, void* k_pages, void* v_pages, int32_t dtype, const void* K,
+                   const void* V, int64_t T, int64_t token_stride_elems, const int32_t* page_table,
+                   int32_t n_seqs, int32_t max_pages_per_seq, const int32_t* slots, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c)) return SAW_EINVAL;
+  if (dtype != SAW_F16 && dtype != SAW_BF16) return SAW_EINVAL;
+  if (T < 0 || n_seqs < 1 || max_pages_per_seq < 1) return SAW_EINVAL;
+  if (T == 0) return SAW_OK;
+  if (!k_pages || !v_pages || !K || !V || !page_table || !slots) return SAW_ENULL;
+  if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems & 7)) return SAW_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(k_pages) || !aligned16(v_pages)) return SAW_EINVAL;
+  return launch_kv16_store(c, k_pages, v_pages, K, V, T, token_stride_elems, page_table, n_seqs,
+                           max_pages_per_seq, slots, (hipStream_t)stream);
+}
+
+int saw_kv16_paged_decode_attn(const saw_cache_t* c, const void* k_pages, const void* v_pages,
+                               int32_t dtype, const void* q, int32_t q_dtype, int32_t B,
+                               int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                               const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                               int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                               int32_t num_splits, saw_stream_t stream) {
+  return decode_common(c, true, k_pages, v_pages, dtype, q, q_dtype, B, n_q_heads, page_table,
+                       max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
+                       workspace_bytes, num_splits, stream);
+}
+
+}  // extern "C"

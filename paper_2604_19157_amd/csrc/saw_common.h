@@ -1,0 +1,69 @@
+// Device-side helpers shared by the SAW-INT4 kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "saw.h"
+
+#define SAW_WAVE 64
+
+namespace saw {
+
+// ---- 16-bit element conversions (exact widening; round-to-nearest-even narrowing) ----
+__device__ __forceinline__ float bf16_to_f32(uint32_t u16) { return __uint_as_float(u16 << 16); }
+__device__ __forceinline__ float f16_to_f32(uint32_t u16) {
+  union { uint16_t u; _Float16 h; } c;
+  c.u = (uint16_t)u16;
+  return (float)c.h;
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint16_t f32_to_f16(float f) {
+  union { uint16_t u; _Float16 h; } c;
+  c.h = (_Float16)f;
+  return c.u;
+}
+
+// Widen the two 16-bit halves of a dword.
+template <int DT>
+__device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi) {
+  if (DT == SAW_BF16) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xffff0000u);
+  } else {
+    lo = f16_to_f32(w & 0xffffu);
+    hi = f16_to_f32(w >> 16);
+  }
+}
+
+__device__ __forceinline__ float load_elem(const void* p, int dtype, int64_t i) {
+  if (dtype == SAW_F32) return ((const float*)p)[i];
+  uint32_t u = ((const uint16_t*)p)[i];
+  return dtype == SAW_BF16 ? bf16_to_f32(u) : f16_to_f32(u);
+}
+__device__ __forceinline__ void store_elem(void* p, int dtype, int64_t i, float v) {
+  if (dtype == SAW_F32) ((float*)p)[i] = v;
+  else if (dtype == SAW_BF16) ((uint16_t*)p)[i] = f32_to_bf16(v);
+  else ((uint16_t*)p)[i] = f32_to_f16(v);
+}
+
+// 1/sqrt(h) for the supported Hadamard orders (correctly rounded constants).
+__device__ __forceinline__ float had_norm(int h) {
+  return h == 16 ? 0.25f : h == 32 ? 0.17677669529663687f : h == 64 ? 0.125f
+       : h == 128 ? 0.08838834764831845f : 1.0f;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Split-KV geometry shared by host and device code.
+struct SplitPlan {
+  int32_t num_splits;     // partitions per sequence
+  int32_t chunk_tokens;   // tokens per partition (multiple of 64)
+  int32_t bound;          // clamp for seq_lens
+};
+
+}  // namespace saw

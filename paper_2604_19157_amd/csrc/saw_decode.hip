@@ -1,0 +1,444 @@
+// Paged decode attention over the INT4 cache (and over a 16-bit cache for comparison),
+// split-KV with a log-sum-exp merge.  Paper: Sec. 2 (decode step), Sec. 4.1 and App. A.4
+// (q is rotated once, K is consumed in the rotated space, the output is rotated back
+// once for V), App. A.1 (x^ = s (c - z)).
+//
+// The zero-point never enters the inner loop:
+//   q~ . k^_t      = s_t (q~ . c_t) - s_t z_t sum(q~)
+//   sum_t p_t v^_t = sum_t (p_t s_t) c_t - sum_t p_t s_t z_t
+// Logits are kept in base-2 units (log2 e folded into q~) so the softmax uses exp2.
+#include "saw_common.h"
+
+namespace saw {
+
+struct DecodeParams {
+  const uint8_t* k_codes;
+  const uint8_t* v_codes;
+  const float* k_meta;
+  const float* v_meta;
+  const void* q;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  float* ws;            // [B][Hq][S][D + 2]: (m, l, acc[D])
+  void* out;
+  float q_scale;        // sm_scale * log2(e)
+  int32_t q_dtype, out_dtype;
+  int32_t n_q_heads, n_kv_heads, max_pages, num_pages;
+  int32_t had_block, rot_k, rot_v;
+  int32_t num_splits, chunk_tokens, bound;
+};
+
+// In-place un-normalised block Walsh-Hadamard over `n_vec` vectors of length D held in LDS.
+template <int D>
+__device__ __forceinline__ void lds_fwht(float* x, int n_vec, int h, int tid, int nthreads) {
+  for (int st = 1; st < h; st <<= 1) {
+    for (int idx = tid; idx < n_vec * (D / 2); idx += nthreads) {
+      const int v = idx / (D / 2);
+      const int r = idx % (D / 2);
+      const int i = v * D + (r / st) * 2 * st + (r % st);
+      const float a = x[i], b = x[i + st];
+      x[i] = a + b;
+      x[i + st] = a - b;
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// INT4 decode, VALU formulation.  One 256-thread block per (sequence, kv head, split).
+// A wavefront covers 64/LPT tokens per pass; a token's code row is split over LPT lanes.
+template <int D, int G, int LPT>
+__global__ __launch_bounds__(256) void decode_int4_kernel(DecodeParams p) {
+  constexpr int TPW = 64 / LPT;        // tokens per wave pass
+  constexpr int CPL = D / LPT;         // codes per lane
+  constexpr int WPL = CPL / 8;         // dwords per lane
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int L = min(p.seq_lens[b], p.bound);
+  const int t_begin = split * p.chunk_tokens;
+  const int t_end = min(L, t_begin + p.chunk_tokens);
+  if (t_begin >= t_end) return;
+
+  __shared__ float qs[G * D];
+  __shared__ float qsum[G];
+  __shared__ float red[4][G][D + 4];
+
+  // ---- q~ = (q H_blk) * sm_scale * log2 e ----
+  for (int i = tid; i < G * D; i += 256)
+    qs[i] = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+  __syncthreads();
+  float qmul = p.q_scale;
+  if (p.rot_k) {
+    lds_fwht<D>(qs, G, p.had_block, tid, 256);
+    qmul *= had_norm(p.had_block);
+  }
+  for (int i = tid; i < G * D; i += 256) qs[i] *= qmul;
+  __syncthreads();
+  if (tid < G) {
+    float s = 0.f;
+    for (int c = 0; c < D; ++c) s += qs[tid * D + c];
+    qsum[tid] = s;
+  }
+  __syncthreads();
+
+  const int part = lane % LPT;
+  float m[G], lsum[G], zsum[G], acc[G][CPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -INFINITY; lsum[g] = 0.f; zsum[g] = 0.f;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) acc[g][j] = 0.f;
+  }
+
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  for (int t0 = t_begin + wave * TPW; t0 < t_end; t0 += 4 * TPW) {
+    const int t = t0 + lane / LPT;
+    const bool valid = t < t_end;
+    const int tt = valid ? t : t_end - 1;
+    int32_t page = p.page_table[pt_row + (tt >> 4)];
+    page = (page < 0 || page >= p.num_pages) ? 0 : page;
+    const int64_t vec = ((int64_t)page * p.n_kv_heads + kvh) * 16 + (tt & 15);
+    uint32_t kw[WPL], vw[WPL];
+    {
+      const uint32_t* kp = (const uint32_t*)(p.k_codes + vec * (D / 2)) + part * WPL;
+      const uint32_t* vp = (const uint32_t*)(p.v_codes + vec * (D / 2)) + part * WPL;
+#pragma unroll
+      for (int i = 0; i < WPL; ++i) { kw[i] = kp[i]; vw[i] = vp[i]; }
+    }
+    const float2 ksz = *(const float2*)(p.k_meta + vec * 2);
+    const float2 vsz = *(const float2*)(p.v_meta + vec * 2);
+
+    float dot[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) dot[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < WPL; ++i) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float c = (float)((kw[i] >> (4 * j)) & 15u);
+#pragma unroll
+        for (int g = 0; g < G; ++g) dot[g] = fmaf(qs[g * D + part * CPL + i * 8 + j], c, dot[g]);
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int mk = 1; mk < LPT; mk <<= 1) dot[g] += __shfl_xor(dot[g], mk, SAW_WAVE);
+    }
+    float w[G];
+    bool grow = false;
+    float mnew[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float logit = valid ? ksz.x * (dot[g] - ksz.y * qsum[g]) : -INFINITY;
+      float mt = logit;
+#pragma unroll
+      for (int mk = LPT; mk < 64; mk <<= 1) mt = fmaxf(mt, __shfl_xor(mt, mk, SAW_WAVE));
+      mnew[g] = fmaxf(m[g], mt);
+      grow |= mnew[g] > m[g];
+      w[g] = logit;
+    }
+    if (grow) {  // wave-uniform: m and mt are identical in every lane
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float a = fast_exp2(m[g] - mnew[g]);   // exp2(-inf) = 0 on the first pass
+        lsum[g] *= a; zsum[g] *= a;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) acc[g][j] *= a;
+        m[g] = mnew[g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float pr = valid ? fast_exp2(w[g] - m[g]) : 0.f;
+      lsum[g] += pr;
+      w[g] = pr * vsz.x;
+      zsum[g] = fmaf(w[g], vsz.y, zsum[g]);
+    }
+#pragma unroll
+    for (int i = 0; i < WPL; ++i) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float c = (float)((vw[i] >> (4 * j)) & 15u);
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g][i * 8 + j] = fmaf(w[g], c, acc[g][i * 8 + j]);
+      }
+    }
+  }
+
+  // ---- reduce over the token lanes of the wave ----
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int mk = LPT; mk < 64; mk <<= 1) {
+      lsum[g] += __shfl_xor(lsum[g], mk, SAW_WAVE);
+      zsum[g] += __shfl_xor(zsum[g], mk, SAW_WAVE);
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], mk, SAW_WAVE);
+    }
+  }
+  if (lane < LPT) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) red[wave][g][part * CPL + j] = acc[g][j] - zsum[g];
+      if (part == 0) { red[wave][g][D] = m[g]; red[wave][g][D + 1] = lsum[g]; }
+    }
+  }
+  __syncthreads();
+  // ---- merge the four waves, write the split's partial ----
+  for (int idx = tid; idx < G * (D + 2); idx += 256) {
+    const int g = idx / (D + 2), c = idx % (D + 2);
+    float mm = -INFINITY;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, red[wv][g][D]);
+    float v;
+    if (c == 0) {
+      v = mm;
+    } else {
+      const int src = (c == 1) ? D + 1 : c - 2;
+      v = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) v += fast_exp2(red[wv][g][D] - mm) * red[wv][g][src];
+    }
+    p.ws[(((int64_t)b * p.n_q_heads + kvh * G + g) * p.num_splits + split) * (D + 2) + c] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// 16-bit KV decode (comparison path).  Same decomposition; a token row of D 16-bit values is
+// split over LPT lanes.
+template <int D, int G, int LPT, int DT>
+__global__ __launch_bounds__(256) void decode_kv16_kernel(DecodeParams p) {
+  constexpr int TPW = 64 / LPT;
+  constexpr int CPL = D / LPT;         // elements per lane
+  constexpr int WPL = CPL / 2;         // dwords per lane
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int L = min(p.seq_lens[b], p.bound);
+  const int t_begin = split * p.chunk_tokens;
+  const int t_end = min(L, t_begin + p.chunk_tokens);
+  if (t_begin >= t_end) return;
+
+  __shared__ float qs[G * D];
+  __shared__ float red[4][G][D + 4];
+  for (int i = tid; i < G * D; i += 256)
+    qs[i] = p.q_scale * load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+  __syncthreads();
+
+  const int part = lane % LPT;
+  float m[G], lsum[G], acc[G][CPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -INFINITY; lsum[g] = 0.f;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) acc[g][j] = 0.f;
+  }
+  const uint16_t* kpages = (const uint16_t*)p.k_codes;
+  const uint16_t* vpages = (const uint16_t*)p.v_codes;
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  for (int t0 = t_begin + wave * TPW; t0 < t_end; t0 += 4 * TPW) {
+    const int t = t0 + lane / LPT;
+    const bool valid = t < t_end;
+    const int tt = valid ? t : t_end - 1;
+    int32_t page = p.page_table[pt_row + (tt >> 4)];
+    page = (page < 0 || page >= p.num_pages) ? 0 : page;
+    const int64_t vec = ((int64_t)page * p.n_kv_heads + kvh) * 16 + (tt & 15);
+    const uint4* kp = (const uint4*)(kpages + vec * D + part * CPL);
+    const uint4* vp = (const uint4*)(vpages + vec * D + part * CPL);
+    float dot[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) dot[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < WPL / 4; ++i) {
+      const uint4 w4 = kp[i];
+      const uint32_t ww[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float lo, hi;
+        widen2<DT>(ww[j], lo, hi);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          dot[g] = fmaf(qs[g * D + part * CPL + i * 8 + 2 * j], lo, dot[g]);
+          dot[g] = fmaf(qs[g * D + part * CPL + i * 8 + 2 * j + 1], hi, dot[g]);
+        }
+      }
+    }
+    float w[G], mnew[G];
+    bool grow = false;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int mk = 1; mk < LPT; mk <<= 1) dot[g] += __shfl_xor(dot[g], mk, SAW_WAVE);
+      const float logit = valid ? dot[g] : -INFINITY;
+      float mt = logit;
+#pragma unroll
+      for (int mk = LPT; mk < 64; mk <<= 1) mt = fmaxf(mt, __shfl_xor(mt, mk, SAW_WAVE));
+      mnew[g] = fmaxf(m[g], mt);
+      grow |= mnew[g] > m[g];
+      w[g] = logit;
+    }
+    if (grow) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float a = fast_exp2(m[g] - mnew[g]);
+        lsum[g] *= a;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) acc[g][j] *= a;
+        m[g] = mnew[g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      w[g] = valid ? fast_exp2(w[g] - m[g]) : 0.f;
+      lsum[g] += w[g];
+    }
+#pragma unroll
+    for (int i = 0; i < WPL / 4; ++i) {
+      const uint4 w4 = vp[i];
+      const uint32_t ww[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float lo, hi;
+        widen2<DT>(ww[j], lo, hi);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          acc[g][i * 8 + 2 * j] = fmaf(w[g], lo, acc[g][i * 8 + 2 * j]);
+          acc[g][i * 8 + 2 * j + 1] = fmaf(w[g], hi, acc[g][i * 8 + 2 * j + 1]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int mk = LPT; mk < 64; mk <<= 1) {
+      lsum[g] += __shfl_xor(lsum[g], mk, SAW_WAVE);
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], mk, SAW_WAVE);
+    }
+  }
+  if (lane < LPT) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) red[wave][g][part * CPL + j] = acc[g][j];
+      if (part == 0) { red[wave][g][D] = m[g]; red[wave][g][D + 1] = lsum[g]; }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * (D + 2); idx += 256) {
+    const int g = idx / (D + 2), c = idx % (D + 2);
+    float mm = -INFINITY;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, red[wv][g][D]);
+    float v;
+    if (c == 0) {
+      v = mm;
+    } else {
+      const int src = (c == 1) ? D + 1 : c - 2;
+      v = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) v += fast_exp2(red[wv][g][D] - mm) * red[wv][g][src];
+    }
+    p.ws[(((int64_t)b * p.n_q_heads + kvh * G + g) * p.num_splits + split) * (D + 2) + c] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge the splits of one (sequence, query head), rotate the output back, write it.
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  const int c = threadIdx.x;
+  const int L = min(p.seq_lens[b], p.bound);
+  const int64_t o_idx = ((int64_t)b * p.n_q_heads + j) * D + c;
+  if (L <= 0) {
+    store_elem(p.out, p.out_dtype, o_idx, 0.f);
+    return;
+  }
+  const int ns = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+  const float* base = p.ws + ((int64_t)b * p.n_q_heads + j) * p.num_splits * (D + 2);
+  float mm = -INFINITY;
+  for (int s = 0; s < ns; ++s) mm = fmaxf(mm, base[s * (D + 2)]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float a = fast_exp2(base[s * (D + 2)] - mm);
+    den = fmaf(a, base[s * (D + 2) + 1], den);
+    num = fmaf(a, base[s * (D + 2) + 2 + c], num);
+  }
+  float o = num / den;
+  if (p.rot_v) {
+    __shared__ float x[D];
+    x[c] = o;
+    __syncthreads();
+    lds_fwht<D>(x, 1, p.had_block, c, D);
+    o = x[c] * had_norm(p.had_block);
+  }
+  store_elem(p.out, p.out_dtype, o_idx, o);
+}
+
+// ---------------------------------------------------------------------------------------
+template <int D, int G>
+static void launch_int4(const DecodeParams& p, dim3 grid, hipStream_t st) {
+  constexpr int LPT = (G >= 8) ? 8 : 4;
+  decode_int4_kernel<D, G, LPT><<<grid, dim3(256), 0, st>>>(p);
+}
+template <int D, int G, int DT>
+static void launch_kv16(const DecodeParams& p, dim3 grid, hipStream_t st) {
+  constexpr int LPT = (G >= 8 || D == 128) ? 8 : 4;
+  constexpr int LPT2 = (G >= 8 && D == 128) ? 16 : LPT;
+  decode_kv16_kernel<D, G, LPT2, DT><<<grid, dim3(256), 0, st>>>(p);
+}
+
+int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_dtype, hipStream_t st) {
+  dim3 grid(p.num_splits, p.n_kv_heads, B);
+#define SAW_DISPATCH_G(DD)                                                          \
+  switch (G) {                                                                      \
+    case 1: if (kv16) { if (kv_dtype == SAW_BF16) launch_kv16<DD, 1, SAW_BF16>(p, grid, st); else launch_kv16<DD, 1, SAW_F16>(p, grid, st); } else launch_int4<DD, 1>(p, grid, st); break; \
+    case 2: if (kv16) { if (kv_dtype == SAW_BF16) launch_kv16<DD, 2, SAW_BF16>(p, grid, st); else launch_kv16<DD, 2, SAW_F16>(p, grid, st); } else launch_int4<DD, 2>(p, grid, st); break; \
+    case 4: if (kv16) { if (kv_dtype == SAW_BF16) launch_kv16<DD, 4, SAW_BF16>(p, grid, st); else launch_kv16<DD, 4, SAW_F16>(p, grid, st); } else launch_int4<DD, 4>(p, grid, st); break; \
+    case 8: if (kv16) { if (kv_dtype == SAW_BF16) launch_kv16<DD, 8, SAW_BF16>(p, grid, st); else launch_kv16<DD, 8, SAW_F16>(p, grid, st); } else launch_int4<DD, 8>(p, grid, st); break; \
+    default: return SAW_EINVAL;                                                     \
+  }
+  if (D == 128) { SAW_DISPATCH_G(128) } else { SAW_DISPATCH_G(64) }
+#undef SAW_DISPATCH_G
+  if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
+  dim3 mgrid(p.n_q_heads, B);
+  if (D == 128) decode_merge_kernel<128><<<mgrid, dim3(128), 0, st>>>(p);
+  else decode_merge_kernel<64><<<mgrid, dim3(64), 0, st>>>(p);
+  return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
+}
+
+int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void* v_pages, int kv_dtype,
+               const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
+               const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
+               const SplitPlan& plan, hipStream_t st) {
+  DecodeParams p;
+  p.k_codes = (const uint8_t*)k_pages;
+  p.v_codes = (const uint8_t*)v_pages;
+  p.k_meta = c->k_meta;
+  p.v_meta = c->v_meta;
+  p.q = q;
+  p.page_table = pt;
+  p.seq_lens = seq_lens;
+  p.ws = (float*)ws;
+  p.out = out;
+  const float scale = (sm_scale > 0.f) ? sm_scale : 1.0f / sqrtf((float)c->head_dim);
+  p.q_scale = scale * 1.4426950408889634f;
+  p.q_dtype = q_dtype;
+  p.out_dtype = out_dtype;
+  p.n_q_heads = Hq;
+  p.n_kv_heads = c->n_kv_heads;
+  p.max_pages = max_pages;
+  p.num_pages = c->num_pages;
+  p.had_block = c->had_block;
+  p.rot_k = !kv16 && c->had_block > 1 && (c->rotate_mask & SAW_ROT_K);
+  p.rot_v = !kv16 && c->had_block > 1 && (c->rotate_mask & SAW_ROT_V);
+  p.num_splits = plan.num_splits;
+  p.chunk_tokens = plan.chunk_tokens;
+  p.bound = plan.bound;
+  return launch_decode(p, B, c->head_dim, Hq / c->n_kv_heads, kv16, kv_dtype, st);
+}
+
+}  // namespace saw

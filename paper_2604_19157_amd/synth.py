@@ -78,7 +78,9 @@ def _page_table(rng: np.random.Generator, seq_lens: np.ndarray, P: int, extra_to
     need = [(int(L) + extra_tokens + P - 1) // P for L in seq_lens]
     total = int(sum(need))
     num_pages = total + slack_pages
-    perm = rng.permutation(num_pages) if shuffle else np.arange(num_pages)
+    perm = rng.permutation(num_pages)          # always drawn, so later draws do not depend on `shuffle`
+    if not shuffle:
+        perm = np.arange(num_pages)
     width = max(1, max(need))
     pt = np.zeros((len(seq_lens), width), np.int32)
     o = 0

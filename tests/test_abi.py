@@ -1,0 +1,119 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and rejects
+bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def saw():
+    from paper_2604_19157_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_19157_amd import build
+        build.build_library()
+    return binding
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "saw.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(saw_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(saw):
+    names = _declared()
+    assert {"saw_rotate_quant_store", "saw_paged_decode_attn", "saw_dequant_pages",
+            "saw_decode_workspace_bytes", "saw_kv16_paged_decode_attn"} <= set(names)
+    L = saw.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.saw_version() == 100
+    assert L.saw_strerror(0) == b"ok" and b"null" in L.saw_strerror(-2)
+
+
+def _struct(saw, **kw):
+    f = dict(k_codes=16, v_codes=16, k_meta=16, v_meta=16, num_pages=4, n_kv_heads=2, page_size=16,
+             head_dim=128, had_block=128, rotate_mask=3)
+    f.update(kw)
+    return saw.SawCacheStruct(**f)
+
+
+def test_store_rejects_bad_arguments_before_launch(saw):
+    L = saw.lib()
+    P = ctypes.c_void_p
+
+    def call(st, K=16, V=16, dt=1, T=4, stride=256, pt=16, nseq=1, mp=4, slots=16):
+        return L.saw_rotate_quant_store(ctypes.byref(st), P(K), P(V), dt, T, stride, P(pt), nseq, mp, P(slots), P(0))
+
+    assert call(_struct(saw), T=0) == 0                              # empty call is a no-op
+    assert call(_struct(saw, had_block=24)) == -1                    # not a power of two
+    assert call(_struct(saw, had_block=8)) == -1                     # unsupported order
+    assert call(_struct(saw, head_dim=64, had_block=128)) == -1      # h > head_dim
+    assert call(_struct(saw, head_dim=96)) == -1
+    assert call(_struct(saw, page_size=32)) == -1
+    assert call(_struct(saw, rotate_mask=7)) == -1
+    assert call(_struct(saw), dt=3) == -1                            # fp32 K/V not accepted
+    assert call(_struct(saw), stride=100) == -1                      # stride below Hkv*d
+    assert call(_struct(saw), stride=260) == -1                      # stride not a multiple of 8
+    assert call(_struct(saw), K=8) == -1                             # misaligned
+    assert call(_struct(saw), K=0) == -2
+    assert call(_struct(saw), slots=0) == -2
+    assert call(_struct(saw, k_meta=0)) == -2
+    assert call(_struct(saw), T=-1) == -1
+
+
+def test_decode_rejects_bad_arguments_before_launch(saw):
+    L = saw.lib()
+    P = ctypes.c_void_p
+
+    def call(st, q=16, qdt=1, B=2, Hq=8, pt=16, mp=8, sl=16, msl=0, scale=0.0, out=16, odt=3, ws=16,
+             wsb=1 << 30, ns=0):
+        return L.saw_paged_decode_attn(ctypes.byref(st), P(q), qdt, B, Hq, P(pt), mp, P(sl), msl, scale, P(out),
+                                       odt, P(ws), wsb, ns, P(0))
+
+    assert call(_struct(saw), Hq=7) == -1                            # not a multiple of the kv heads
+    assert call(_struct(saw), Hq=6) == -1                            # group size 3 unsupported
+    assert call(_struct(saw), Hq=32) == -1                           # group size 16 unsupported
+    assert call(_struct(saw), msl=129) == -1                         # bound beyond the page table
+    assert call(_struct(saw), ns=2000) == -1
+    assert call(_struct(saw), qdt=9) == -1
+    assert call(_struct(saw), q=0) == -2
+    assert call(_struct(saw), ws=0) == -2
+    assert call(_struct(saw), wsb=64) == -3
+    assert call(_struct(saw), scale=float("nan")) == -1
+    assert call(_struct(saw, had_block=3)) == -1
+
+
+def test_workspace_and_plan(saw):
+    L = saw.lib()
+    st = _struct(saw, n_kv_heads=8)
+    for B, Hq, msl, ns in [(256, 32, 4096, 0), (1, 64, 131072, 0), (4, 32, 256, 0), (16, 32, 4096, 3), (2, 8, 1, 0)]:
+        s, c = ctypes.c_int32(), ctypes.c_int32()
+        assert L.saw_decode_plan(ctypes.byref(st), B, msl, ns, ctypes.byref(s), ctypes.byref(c)) == 0
+        assert c.value % 64 == 0 and s.value >= 1 and s.value * c.value >= msl
+        assert (s.value - 1) * c.value < msl                         # no empty trailing partition
+        if ns:
+            assert s.value <= ns
+        assert L.saw_decode_workspace_bytes(ctypes.byref(st), B, Hq, msl, ns) == B * Hq * s.value * 130 * 4
+    assert L.saw_decode_workspace_bytes(ctypes.byref(st), 0, 32, 100, 0) == 0
+
+
+def test_dequant_rejects_bad_arguments(saw):
+    L = saw.lib()
+    P = ctypes.c_void_p
+    st = _struct(saw)
+    assert L.saw_dequant_pages(ctypes.byref(st), P(16), 4, 0, 0, 0, 0, P(16), P(16), P(0)) == 0   # empty range
+    assert L.saw_dequant_pages(ctypes.byref(st), P(16), 4, 0, 5, 3, 0, P(16), P(16), P(0)) == -1
+    assert L.saw_dequant_pages(ctypes.byref(st), P(16), 4, 0, 0, 65, 0, P(16), P(16), P(0)) == -1  # past the page table
+    assert L.saw_dequant_pages(ctypes.byref(st), P(0), 4, 0, 0, 8, 0, P(16), P(16), P(0)) == -2
+
+
+def test_binding_fails_loudly_without_library(saw, monkeypatch):
+    monkeypatch.setattr(saw, "_lib", None)
+    monkeypatch.setattr(saw, "LIB_PATH", "/nonexistent/libsaw.so")
+    with pytest.raises(RuntimeError):
+        saw.lib()

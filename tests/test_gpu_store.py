@@ -1,0 +1,139 @@
+"""Parity of saw_rotate_quant_store / saw_dequant_pages with the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_cases as gc
+import parity
+from oracle import saw_oracle as O
+from paper_2604_19157_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def saw():
+    from paper_2604_19157_amd import binding
+    binding.lib()
+    return binding
+
+
+def _run(saw, w, **kw):
+    cache, ref, recs, pt = gc.fill_caches(w, saw, **kw)
+    got = gc.cache_to_numpy(cache, w)
+    res = gc.compare_store(got, ref, recs)
+    print(f"[{w.name} h={w.had_block} d={w.head_dim} mask={w.rotate_mask} {w.dtype}] {res}", flush=True)
+    parity.assert_store_ok(res)
+    assert res["untouched_ok"]
+    return cache, ref, got, pt, res
+
+
+def test_tiny_full_parity(saw):
+    """Config 1 in full: every code, scale and zero-point of 4 x 256 tokens x 8 heads."""
+    w = synth.make_workload("tiny")
+    _, ref, got, _, res = _run(saw, w)
+    assert res["vectors"] > 0
+    # placement is exact: the byte arrays agree wherever no exemption applies
+    frac = (got["k_codes"] != ref["k_codes"]).mean()
+    assert frac < 1e-4
+
+
+@pytest.mark.parametrize("h", [1, 16, 32, 64, 128])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_block_size_sweep_d128(saw, h, dtype):
+    w = synth.make_workload("prefill", ctx=700, had_block=h, dtype=dtype)     # several blocks + a ragged tail
+    _run(saw, w)
+
+
+@pytest.mark.parametrize("h", [1, 16, 32, 64])
+def test_block_size_sweep_mha_d64(saw, h):
+    w = synth.make_workload("prefill_mha", ctx=333, had_block=h)
+    _run(saw, w)
+
+
+@pytest.mark.parametrize("mask", [0, 1, 2, 3])
+def test_rotate_mask(saw, mask):
+    w = synth.make_workload("llama8b", batch=3, ctx=97, rotate_mask=mask)
+    _run(saw, w)
+
+
+def test_heavy_tailed_ragged_batch(saw):
+    w = synth.make_workload("highconc", batch=9, ctx=(1, 300))
+    _run(saw, w, order_rng=np.random.default_rng(5))
+
+
+def test_small_head_counts_and_single_token(saw):
+    for Hkv in (1, 2, 3):
+        w = synth.make_workload("tiny", batch=2, seq_lens=[1, 17], n_kv_heads=Hkv, n_q_heads=Hkv)
+        _run(saw, w)
+
+
+def test_degenerate_vectors_and_huge_offsets(saw):
+    dev = "cuda"
+    Hkv, d = 2, 128
+    cache = saw.Cache(4, Hkv, d, 64, 3, device=dev)
+    ref = O.new_cache(4, Hkv, 16, d)
+    K = torch.zeros((6, Hkv, d), dtype=torch.float16)
+    V = torch.zeros_like(K)
+    K[1] = 3.25                                  # constant vectors: rotate to one DC coefficient per block
+    K[2, 0, :64] = -7.5                          # constant inside one Hadamard block only
+    V[3] = -2.0
+    V[4, 1] = torch.linspace(1000.0, 1001.0, d).to(torch.float16)   # range far from zero: large |z|
+    K[5, :, 5] = 60000.0                         # one huge channel
+    pt = np.array([[2, 0]], np.int32)
+    sl = synth.slots_for(0, 11, 17)              # straddles a page boundary
+    saw.rotate_quant_store(cache, K.to(dev), V.to(dev), torch.from_numpy(pt).to(dev), torch.from_numpy(sl).to(dev))
+    rec = O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), pt, sl, 64, 3, return_prerounding=True)
+    torch.cuda.synchronize()
+    got = {k: getattr(cache, k).cpu().numpy() for k in ("k_codes", "v_codes", "k_meta", "v_meta")}
+    res = gc.compare_store(got, ref, [rec])
+    print(res, flush=True)
+    parity.assert_store_ok(res)
+    # the all-zero vector: s = 1, z = 0, codes 0
+    assert got["k_meta"][2, 0, 11].tolist() == [1.0, 0.0] and not got["k_codes"][2, 0, 11].any()
+
+
+def test_out_of_range_slots_are_skipped_and_strided_input(saw):
+    dev = "cuda"
+    Hkv, d = 2, 64
+    cache = saw.Cache(3, Hkv, d, 32, 3, device=dev)
+    g = torch.Generator().manual_seed(3)
+    big = torch.randn((5, Hkv * d + 24), generator=g).to(torch.bfloat16)      # token stride > Hkv*d
+    bigv = torch.randn((5, Hkv * d + 24), generator=g).to(torch.bfloat16)
+    Kd, Vd = big.to(dev), bigv.to(dev)
+    K = Kd[:, :Hkv * d].view(5, Hkv, d)
+    V = Vd[:, :Hkv * d].view(5, Hkv, d)
+    pt = np.array([[1, 7]], np.int32)                                          # page 7 does not exist
+    sl = np.array([[0, 3], [0, 20], [1, 0], [0, -1], [0, 40]], np.int32)       # only the first is valid
+    saw.rotate_quant_store(cache, K, V, torch.from_numpy(pt).to(dev), torch.from_numpy(sl).to(dev))
+    torch.cuda.synchronize()
+    ref = O.new_cache(3, Hkv, 16, d)
+    O.rotate_quant_store(ref, big[:1, :Hkv * d].float().numpy().reshape(1, Hkv, d),
+                         bigv[:1, :Hkv * d].float().numpy().reshape(1, Hkv, d), pt, sl[:1], 32, 3)
+    assert np.array_equal(cache.k_codes.cpu().numpy(), ref["k_codes"])
+    assert np.array_equal(cache.v_codes.cpu().numpy(), ref["v_codes"])
+    assert np.allclose(cache.k_meta.cpu().numpy(), ref["k_meta"], rtol=1e-6)
+
+
+@pytest.mark.parametrize("name,kw", [("tiny", dict(batch=2, ctx=90)),
+                                     ("prefill_mha", dict(ctx=70, had_block=16)),
+                                     ("llama8b", dict(batch=1, ctx=50, rotate_mask=1))])
+@pytest.mark.parametrize("unrotate", [False, True])
+def test_dequant_pages(saw, name, kw, unrotate):
+    w = synth.make_workload(name, **kw)
+    cache, _, _, pt = gc.fill_caches(w, saw, with_ref=False)
+    got = gc.cache_to_numpy(cache, w)
+    for b in range(w.batch):
+        L = int(w.seq_lens[b])
+        for (p0, p1) in [(0, L), (5, min(L, 37)), (L - 1, L)]:
+            k, v = saw.dequant_pages(cache, pt, b, p0, p1, unrotate=unrotate)
+            kr, vr = O.dequant_pages(got, w.page_table, b, p0, p1, w.had_block, w.rotate_mask, unrotate=unrotate)
+            for a, r in ((k, kr), (v, vr)):
+                a = a.cpu().numpy().astype(np.float64)
+                assert np.abs(a - r).max() <= 2e-6 * np.abs(r).max()
+    # with rotation undone the values are the inputs up to the quantisation step
+    if unrotate:
+        K, V = synth.gen_kv(w, 0, 0, int(w.seq_lens[0]))
+        k, v = saw.dequant_pages(cache, pt, 0, 0, int(w.seq_lens[0]), unrotate=True)
+        s = got["k_meta"][..., 0].max()
+        assert (k.cpu() - K.float()).abs().max() <= 0.51 * s * (w.head_dim ** 0.5)
