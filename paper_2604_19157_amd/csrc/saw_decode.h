@@ -1,0 +1,28 @@
+// Kernel argument block shared by the decode kernels.
+#pragma once
+
+#include "saw_common.h"
+
+namespace saw {
+
+struct DecodeParams {
+  const uint8_t* k_codes;
+  const uint8_t* v_codes;
+  const float* k_meta;
+  const float* v_meta;
+  const void* q;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  float* ws;            // [B][Hq][S][D + 2]: (m, l, acc[D])
+  void* out;
+  float q_scale;        // sm_scale * log2(e)
+  int32_t q_dtype, out_dtype;
+  int32_t n_q_heads, n_kv_heads, max_pages, num_pages;
+  int32_t had_block, rot_k, rot_v;
+  int32_t num_splits, chunk_tokens, bound;
+};
+
+// MFMA INT4 decode for head_dim 128 (saw_decode_mfma.hip); grid = (splits, kv heads, batch).
+int launch_decode_int4_mfma(const DecodeParams& p, int G, dim3 grid, hipStream_t st);
+
+}  // namespace saw

@@ -7,26 +7,10 @@
 //   q~ . k^_t      = s_t (q~ . c_t) - s_t z_t sum(q~)
 //   sum_t p_t v^_t = sum_t (p_t s_t) c_t - sum_t p_t s_t z_t
 // Logits are kept in base-2 units (log2 e folded into q~) so the softmax uses exp2.
-#include "saw_common.h"
+#include "saw_decode.h"
 
 namespace saw {
 
-struct DecodeParams {
-  const uint8_t* k_codes;
-  const uint8_t* v_codes;
-  const float* k_meta;
-  const float* v_meta;
-  const void* q;
-  const int32_t* page_table;
-  const int32_t* seq_lens;
-  float* ws;            // [B][Hq][S][D + 2]: (m, l, acc[D])
-  void* out;
-  float q_scale;        // sm_scale * log2(e)
-  int32_t q_dtype, out_dtype;
-  int32_t n_q_heads, n_kv_heads, max_pages, num_pages;
-  int32_t had_block, rot_k, rot_v;
-  int32_t num_splits, chunk_tokens, bound;
-};
 
 // In-place un-normalised block Walsh-Hadamard over `n_vec` vectors of length D held in LDS.
 template <int D>
@@ -393,6 +377,9 @@ static void launch_kv16(const DecodeParams& p, dim3 grid, hipStream_t st) {
 
 int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_dtype, hipStream_t st) {
   dim3 grid(p.num_splits, p.n_kv_heads, B);
+  if (!kv16 && D == 128) {
+    if (launch_decode_int4_mfma(p, G, grid, st) != SAW_OK) return SAW_EINVAL;
+  } else {
 #define SAW_DISPATCH_G(DD)                                                          \
   switch (G) {                                                                      \
     case 1: if (kv16) { if (kv_dtype == SAW_BF16) launch_kv16<DD, 1, SAW_BF16>(p, grid, st); else launch_kv16<DD, 1, SAW_F16>(p, grid, st); } else launch_int4<DD, 1>(p, grid, st); break; \
@@ -403,6 +390,7 @@ int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_
   }
   if (D == 128) { SAW_DISPATCH_G(128) } else { SAW_DISPATCH_G(64) }
 #undef SAW_DISPATCH_G
+  }
   if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
   dim3 mgrid(p.n_q_heads, B);
   if (D == 128) decode_merge_kernel<128><<<mgrid, dim3(128), 0, st>>>(p);

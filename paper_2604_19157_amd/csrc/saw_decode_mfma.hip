@@ -1,0 +1,362 @@
+// INT4 paged decode attention for head_dim 128 on the gfx950 matrix cores.
+// Paper: Sec. 2 (decode step), Sec. 4.1 / App. A.4 (rotated-space attention), App. A.1.
+//
+// One wavefront (a 64-thread block) owns one (sequence, kv head, context partition) and walks
+// it in batches of four pages (64 tokens).  Per batch:
+//   * the four K and four V code tiles (1 KiB each, contiguous in HBM) are fetched one
+//     batch ahead into registers and dropped into LDS with a 16-byte-chunk swizzle
+//     pos(t, Q) = 4t + ((Q + t/4) & 3) that makes every later LDS read bank-conflict free;
+//   * nibbles become bf16 operands with two ALU ops per pair: (w >> 4i) & 0x000F000F | 0x43004300
+//     is the bf16 pair (128 + c_lo, 128 + c_hi); the constant 128 joins the zero-point;
+//   * logits: D[head][token] = q~ (heads x channels) . codes (channels x tokens) with
+//     v_mfma_f32_16x16x32_bf16; q~ is carried as bf16 hi + lo limbs accumulated into the
+//     same tile, so it keeps ~16 bits; rows >= G of the tile are idle;
+//   * the four pages' result rows are gathered with v_permlane16/32_swap so that lane =
+//     token of the batch and registers = heads: the softmax runs on all 64 lanes;
+//   * the running maximum is a lazily updated reference: it only moves (with a rescale of
+//     the accumulators) when some logit exceeds it by more than 2^8;
+//   * P.V needs tokens along the contraction: ds_read_b64_tr_b4 hands each lane the 16
+//     tokens of one channel (a 16x16 nibble transpose inside LDS); P goes through LDS once as
+//     bf16 hi/lo rows; O[head][channel] accumulates in eight 16x16 tiles.
+// Zero-points never enter the loops:  q~.k^ = s (q~.(c+128) - (z+128) sum q~),
+// sum_t w_t v^_t = sum_t w_t (c_t+128) - sum_t w_t (z_t+128),  w_t = p_t s_t.
+#include "saw_decode.h"
+
+namespace saw {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#define LDS_AS __attribute__((address_space(3)))
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Eight packed nibbles -> eight bf16 values 128 + c, in k-order (n0, n4, n1, n5, n2, n6, n3, n7).
+__device__ __forceinline__ bf16x8 unpack8(uint32_t w) {
+  u32x4 r;
+  r.x = (w & 0x000F000Fu) | 0x43004300u;
+  r.y = ((w >> 4) & 0x000F000Fu) | 0x43004300u;
+  r.z = ((w >> 8) & 0x000F000Fu) | 0x43004300u;
+  r.w = ((w >> 12) & 0x000F000Fu) | 0x43004300u;
+  return as_bf16x8(r);
+}
+
+__device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// x = hi + lo with hi a truncated bf16 and lo a rounded bf16 of the remainder.
+__device__ __forceinline__ void split_bf16(float x, uint32_t& hi16, uint32_t& lo16, float& sum) {
+  const uint32_t u = __float_as_uint(x);
+  const float hf = __uint_as_float(u & 0xffff0000u);
+  hi16 = u >> 16;
+  uint32_t r = __float_as_uint(x - hf);
+  r += 0x7fffu + ((r >> 16) & 1u);
+  lo16 = r >> 16;
+  sum = hf + __uint_as_float(r & 0xffff0000u);
+}
+
+__device__ __forceinline__ float swap16x(float a, float b) {   // rows (a0, b0, a2, b2)
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]);
+}
+__device__ __forceinline__ float swap32x(float a, float b) {   // rows (a0, a1, b0, b1)
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, false));
+}
+// max over the 16 lanes of each row (rotations by 1, 2, 4, 8)
+__device__ __forceinline__ float row_allmax(float v) {
+  v = fmaxf(v, dpp_f<0x121>(v));
+  v = fmaxf(v, dpp_f<0x122>(v));
+  v = fmaxf(v, dpp_f<0x124>(v));
+  v = fmaxf(v, dpp_f<0x128>(v));
+  return v;
+}
+__device__ __forceinline__ float row_allsum(float v) {
+  v += dpp_f<0x121>(v);
+  v += dpp_f<0x122>(v);
+  v += dpp_f<0x124>(v);
+  v += dpp_f<0x128>(v);
+  return v;
+}
+
+constexpr int kTileBytes = 1024;               // one (page, head) code tile: 16 tokens x 64 B
+constexpr int kStageBytes = 8 * kTileBytes;    // four K tiles then four V tiles
+constexpr int kPbufBytes = 16 * 64 * 2;        // P as bf16 [16 rows][64 tokens]
+constexpr float kLazyTau = 8.0f;               // reference max may lag the true max by 2^8
+
+template <int G>
+__global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
+  constexpr int D = 128;
+  constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
+  constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
+  constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x;
+  const int L = min(p.seq_lens[b], p.bound);
+  const int t_begin = split * p.chunk_tokens;
+  const int t_end = min(L, t_begin + p.chunk_tokens);
+  if (t_begin >= t_end) return;
+
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kStageBytes + kPbufBytes];
+  uint8_t* const pbuf = lds + kStageBytes;
+
+  const int row16 = lane & 15, grp = lane >> 4;
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  const int last_page = (t_end - 1) >> 4;
+  const int64_t head_tile = (int64_t)kvh * kTileBytes;
+  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
+  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
+  const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
+
+  // ---- staging registers: one batch ahead ----
+  u32x4 kst[4], vst[4];
+  f32x2 kmeta[NS], vmeta[NS];
+#define SAW_FETCH(batch)                                                                        \
+  {                                                                                             \
+    const int pg0_ = (t_begin >> 4) + 4 * (batch);                                              \
+    int pid_[4];                                                                                \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
+      int id = p.page_table[pt_row + min(pg0_ + q, last_page)];                                 \
+      pid_[q] = (id < 0 || id >= p.num_pages) ? 0 : id;                                         \
+    }                                                                                           \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
+      const int64_t off = (int64_t)pid_[q] * page_stride + head_tile + lane * 16;               \
+      kst[q] = *(const u32x4*)(p.k_codes + off);                                                \
+      vst[q] = *(const u32x4*)(p.v_codes + off);                                                \
+    }                                                                                           \
+    _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                            \
+      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp; /* page of this lane's token */     \
+      const int id = pg == 0 ? pid_[0] : pg == 1 ? pid_[1] : pg == 2 ? pid_[2] : pid_[3];       \
+      const int64_t moff = (int64_t)id * page_meta + head_meta + row16 * 2;                     \
+      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                             \
+      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                             \
+    }                                                                                           \
+  }
+  SAW_FETCH(0)
+
+  // ---- prologue: q~ = (q H_blk) sm_scale log2(e), as bf16 hi/lo MFMA operands ----
+  // (the stage area doubles as fp32 scratch; nothing has been staged yet)
+  float* const qs = (float*)lds;
+  for (int i = lane; i < G * D; i += 64)
+    qs[i] = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+  __syncthreads();
+  float qmul = p.q_scale;
+  if (p.rot_k) {
+    for (int st = 1; st < p.had_block; st <<= 1) {
+      for (int idx = lane; idx < G * (D / 2); idx += 64) {
+        const int v = idx / (D / 2), r = idx % (D / 2);
+        const int i = v * D + (r / st) * 2 * st + (r % st);
+        const float a = qs[i], c = qs[i + st];
+        qs[i] = a + c;
+        qs[i + st] = a - c;
+      }
+      __syncthreads();
+    }
+    qmul *= had_norm(p.had_block);
+  }
+  // lane (row16 = head row m, grp = k-group): channels 32*grp + 8*kk + {0,4,1,5,2,6,3,7}
+  u32x4 a_hi[4], a_lo[4];
+  float qpart = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    uint32_t h16[8], l16[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float x = (row16 < G) ? qs[row16 * D + 32 * grp + 8 * kk + j] * qmul : 0.f;
+      float sum;
+      split_bf16(x, h16[j], l16[j], sum);
+      qpart += sum;
+    }
+    a_hi[kk] = u32x4{h16[0] | (h16[4] << 16), h16[1] | (h16[5] << 16), h16[2] | (h16[6] << 16), h16[3] | (h16[7] << 16)};
+    a_lo[kk] = u32x4{l16[0] | (l16[4] << 16), l16[1] | (l16[5] << 16), l16[2] | (l16[6] << 16), l16[3] | (l16[7] << 16)};
+  }
+  qpart += __shfl_xor(qpart, 16, 64);
+  qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the rounded q~_m
+  __syncthreads();
+  if (lane < 16) qs[lane] = qpart;
+  __syncthreads();
+  float qsum[NH];
+#pragma unroll
+  for (int i = 0; i < NH; ++i) qsum[i] = qs[(G > 4) ? (4 * (grp & 1) + i) : i];
+  __syncthreads();
+  for (int i = lane; i < kPbufBytes / 4; i += 64) ((uint32_t*)pbuf)[i] = 0u;
+
+  // ---- per-lane constants ----
+  const int st_off = 16 * (4 * (lane >> 2) + (((lane & 3) + (lane >> 4)) & 3));     // staging write: t = lane>>2, Q = lane&3
+  const int kr_off = 16 * (4 * row16 + ((grp + (row16 >> 2)) & 3));                 // K read: t = row16, Q = grp
+  int vr_off[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+    vr_off[c] = 4 * kTileBytes + grp * kTileBytes + 16 * (4 * row16 + (((c >> 1) + (row16 >> 2)) & 3)) + 8 * (c & 1);
+  // P write column inside the batch: 16*page + 8*(t/8) + perm^-1(t%8),  perm^-1(u) = (u&3)<<1 | u>>2
+  const int pcol_t = (row16 & 8) + (((row16 & 3) << 1) | ((row16 >> 2) & 1));
+  const int head0 = (G > 4) ? 4 * (grp & 1) : 0;                                    // first head of this lane
+
+  f32x4 oacc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) oacc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_ref[NH], lsum[NH], zs[NH];
+#pragma unroll
+  for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
+
+  const int nb = (t_end - t_begin + 63) >> 6;
+  for (int bi = 0; bi < nb; ++bi) {
+    // ---- stage the fetched batch, start the next fetch ----
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      *(u32x4*)(lds + q * kTileBytes + st_off) = kst[q];
+      *(u32x4*)(lds + (4 + q) * kTileBytes + st_off) = vst[q];
+    }
+    f32x2 km[NS], vm[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) { km[s] = kmeta[s]; vm[s] = vmeta[s]; }
+    if (bi + 1 < nb) SAW_FETCH(bi + 1)
+    __syncthreads();
+
+    // ---- logits: D_q[head][token of page q] ----
+    f32x4 dq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const u32x4 kw = *(const u32x4*)(lds + q * kTileBytes + kr_off);
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 bk = unpack8(kw[kk]);
+        acc = mfma_bf16(as_bf16x8(a_hi[kk]), bk, acc);
+        acc = mfma_bf16(as_bf16x8(a_lo[kk]), bk, acc);
+      }
+      dq[q] = acc;
+    }
+    // ---- gather: lane = token of the batch, registers = heads ----
+    float sraw[NS][NH];
+#pragma unroll
+    for (int i = 0; i < NH; ++i) {
+      if (G > 4) {
+        sraw[0][i] = swap32x(dq[0][i], dq[1][i]);
+        sraw[NS - 1][i] = swap32x(dq[2][i], dq[3][i]);
+      } else {
+        sraw[0][i] = swap32x(swap16x(dq[0][i], dq[1][i]), swap16x(dq[2][i], dq[3][i]));
+      }
+    }
+    // ---- softmax with a lazily updated reference maximum ----
+    const int tok0 = t_begin + 64 * bi;
+    float lg[NS][NH];
+    bool valid[NS];
+    bool need = false;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;
+      valid[s] = (tok0 + 16 * pg + row16) < t_end;
+      const float kz = km[s].y + 128.f;
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        const float v = km[s].x * fmaf(-kz, qsum[i], sraw[s][i]);
+        lg[s][i] = valid[s] ? v : -INFINITY;
+        need |= lg[s][i] > m_ref[i] + kLazyTau;
+      }
+    }
+    if (__any(need)) {
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        float mx = lg[0][i];
+        if (NS > 1) mx = fmaxf(mx, lg[NS - 1][i]);
+        mx = row_allmax(mx);
+        if (G > 4) {
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));      // lanes 32 apart share the head group
+        } else {
+          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        }
+        const float mnew = fmaxf(m_ref[i], mx);
+        const float alpha = fast_exp2(m_ref[i] - mnew);      // 0 on the first batch
+        lsum[i] *= alpha;
+        zs[i] *= alpha;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) oacc[c][i] *= alpha;
+        m_ref[i] = mnew;
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;
+      const int col = 16 * pg + pcol_t;
+      const float vs = valid[s] ? vm[s].x : 0.f;
+      const float vz = valid[s] ? vm[s].y + 128.f : 0.f;
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        const float pr = fast_exp2(lg[s][i] - m_ref[i]);     // exp2(-inf) = 0 for masked tokens
+        lsum[i] += pr;
+        uint32_t h16, l16;
+        float wsum;
+        split_bf16(pr * vs, h16, l16, wsum);
+        zs[i] = fmaf(wsum, vz, zs[i]);
+        ((uint16_t*)pbuf)[(head0 + i) * 64 + col] = (uint16_t)h16;
+        ((uint16_t*)pbuf)[(LO + head0 + i) * 64 + col] = (uint16_t)l16;
+      }
+    }
+    __syncthreads();
+    // ---- O[row][channel] += P (rows x 64 tokens) . V codes ----
+    const u32x4 pa0 = *(const u32x4*)(pbuf + (row16 * 64 + 16 * grp) * 2);
+    const u32x4 pa1 = *(const u32x4*)(pbuf + (row16 * 64 + 16 * grp + 8) * 2);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const i32x2 tv = __builtin_amdgcn_ds_read_tr4_b64_v2i32((LDS_AS i32x2*)(lds + vr_off[c]));
+      oacc[c] = mfma_bf16(as_bf16x8(pa0), unpack8((uint32_t)tv.x), oacc[c]);
+      oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y), oacc[c]);
+    }
+  }
+
+  // ---- epilogue: reduce the per-lane sums, fold hi + lo rows, write the partial ----
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    lsum[i] = row_allsum(lsum[i]);
+    zs[i] = row_allsum(zs[i]);
+    if (G > 4) {
+      lsum[i] += __shfl_xor(lsum[i], 32, 64);
+      zs[i] += __shfl_xor(zs[i], 32, 64);
+    } else {
+      lsum[i] += __shfl_xor(lsum[i], 16, 64);
+      lsum[i] += __shfl_xor(lsum[i], 32, 64);
+      zs[i] += __shfl_xor(zs[i], 16, 64);
+      zs[i] += __shfl_xor(zs[i], 32, 64);
+    }
+  }
+  constexpr int LOSHIFT = (G > 4) ? 32 : 16;     // lanes holding the lo rows sit this far above the hi rows
+  const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    const int head = head0 + i;
+    float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (D + 2);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
+      if (writer && i < G) dst[2 + 16 * c + row16] = o - zs[i];
+    }
+    if (writer && row16 == 0 && i < G) { dst[0] = m_ref[i]; dst[1] = lsum[i]; }
+  }
+}
+
+#undef SAW_FETCH
+
+int launch_decode_int4_mfma(const DecodeParams& p, int G, dim3 grid, hipStream_t st) {
+  switch (G) {
+    case 1: decode_int4_mfma_kernel<1><<<grid, dim3(64), 0, st>>>(p); break;
+    case 2: decode_int4_mfma_kernel<2><<<grid, dim3(64), 0, st>>>(p); break;
+    case 4: decode_int4_mfma_kernel<4><<<grid, dim3(64), 0, st>>>(p); break;
+    case 8: decode_int4_mfma_kernel<8><<<grid, dim3(64), 0, st>>>(p); break;
+    default: return SAW_EINVAL;
+  }
+  return SAW_OK;
+}
+
+}  // namespace saw
