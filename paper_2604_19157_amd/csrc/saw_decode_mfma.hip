@@ -9,8 +9,8 @@
 //   * nibbles become bf16 operands with two ALU ops per pair: (w >> 4i) & 0x000F000F | 0x43004300
 //     is the bf16 pair (128 + c_lo, 128 + c_hi); the constant 128 joins the zero-point;
 //   * logits: D[head][token] = q~ (heads x channels) . codes (channels x tokens) with
-//     v_mfma_f32_16x16x32_bf16; q~ is carried as bf16 hi + lo limbs accumulated into the
-//     same tile, so it keeps ~16 bits; rows >= G of the tile are idle;
+//     v_mfma_f32_16x16x32_bf16; q~ is carried as bf16 hi + lo limbs in separate rows of the
+//     tile (~16 bits together), added after the gather below;
 //   * the four pages' result rows are gathered with v_permlane16/32_swap so that lane =
 //     token of the batch and registers = heads: the softmax runs on all 64 lanes;
 //   * the running maximum is a lazily updated reference: it only moves (with a rescale of
@@ -35,13 +35,20 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // Eight packed nibbles -> eight bf16 values 128 + c, in k-order (n0, n4, n1, n5, n2, n6, n3, n7).
-__device__ __forceinline__ bf16x8 unpack8(uint32_t w) {
+// `k` holds 0x43004300 in a VGPR (see bf16_bias()), which lets each mask-and-bias be one
+// v_and_or_b32 with a single scalar operand.
+__device__ __forceinline__ bf16x8 unpack8(uint32_t w, uint32_t k) {
   u32x4 r;
-  r.x = (w & 0x000F000Fu) | 0x43004300u;
-  r.y = ((w >> 4) & 0x000F000Fu) | 0x43004300u;
-  r.z = ((w >> 8) & 0x000F000Fu) | 0x43004300u;
-  r.w = ((w >> 12) & 0x000F000Fu) | 0x43004300u;
+  r.x = (w & 0x000F000Fu) | k;
+  r.y = ((w >> 4) & 0x000F000Fu) | k;
+  r.z = ((w >> 8) & 0x000F000Fu) | k;
+  r.w = ((w >> 12) & 0x000F000Fu) | k;
   return as_bf16x8(r);
+}
+__device__ __forceinline__ uint32_t bf16_bias() {
+  uint32_t k;
+  asm volatile("v_mov_b32 %0, 0x43004300" : "=v"(k));
+  return k;
 }
 
 __device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -59,13 +66,17 @@ __device__ __forceinline__ void split_bf16(float x, uint32_t& hi16, uint32_t& lo
   sum = hf + __uint_as_float(r & 0xffff0000u);
 }
 
-__device__ __forceinline__ float swap16x(float a, float b) {   // rows (a0, b0, a2, b2)
+// v_permlane16_swap: x <- rows (a0, b0, a2, b2), y <- rows (a1, b1, a3, b3)   (row = 16 lanes)
+__device__ __forceinline__ void swap16(float a, float b, float& x, float& y) {
   auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  return __uint_as_float(r[0]);
+  x = __uint_as_float(r[0]);
+  y = __uint_as_float(r[1]);
 }
-__device__ __forceinline__ float swap32x(float a, float b) {   // rows (a0, a1, b0, b1)
+// v_permlane32_swap: x <- rows (a0, a1, b0, b1), y <- rows (a2, a3, b2, b3)
+__device__ __forceinline__ void swap32(float a, float b, float& x, float& y) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  return __uint_as_float(r[0]);
+  x = __uint_as_float(r[0]);
+  y = __uint_as_float(r[1]);
 }
 
 template <int CTRL>
@@ -90,7 +101,8 @@ __device__ __forceinline__ float row_allsum(float v) {
 
 constexpr int kTileBytes = 1024;               // one (page, head) code tile: 16 tokens x 64 B
 constexpr int kStageBytes = 8 * kTileBytes;    // four K tiles then four V tiles
-constexpr int kPbufBytes = 16 * 64 * 2;        // P as bf16 [16 rows][64 tokens]
+constexpr int kProw = 72;                      // P row stride in bf16 (64 tokens + 8 pad: conflict-free b128 reads)
+constexpr int kPbufBytes = 16 * kProw * 2;     // P as bf16 [16 rows][64 tokens]
 constexpr float kLazyTau = 8.0f;               // reference max may lag the true max by 2^8
 
 template <int G>
@@ -120,14 +132,28 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   // ---- staging registers: one batch ahead ----
   u32x4 kst[4], vst[4];
   f32x2 kmeta[NS], vmeta[NS];
+  // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page pg_first + l,
+  // i.e. one vector load covers 16 batches; `pidv_nx` is the following 64 pages, loaded 16
+  // batches ahead.  A batch takes its four ids with v_readlane, so no page-table latency sits
+  // between consecutive batches.
+  const int pg_first = t_begin >> 4;
+#define SAW_LOAD_PIDS(dst, first)                                                               \
+  {                                                                                             \
+    int id = p.page_table[pt_row + min((first) + lane, last_page)];                             \
+    dst = (id < 0 || id >= p.num_pages) ? 0 : id;                                               \
+  }
+  int pidv, pidv_nx;
+  SAW_LOAD_PIDS(pidv, pg_first)
+  SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
 #define SAW_FETCH(batch)                                                                        \
   {                                                                                             \
-    const int pg0_ = (t_begin >> 4) + 4 * (batch);                                              \
-    int pid_[4];                                                                                \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
-      int id = p.page_table[pt_row + min(pg0_ + q, last_page)];                                 \
-      pid_[q] = (id < 0 || id >= p.num_pages) ? 0 : id;                                         \
+    if ((batch) > 0 && ((batch) & 15) == 0) {                                                   \
+      pidv = pidv_nx;                                                                           \
+      SAW_LOAD_PIDS(pidv_nx, pg_first + 4 * (batch) + 64)                                       \
     }                                                                                           \
+    int pid_[4];                                                                                \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                               \
+      pid_[q] = __builtin_amdgcn_readlane(pidv, 4 * ((batch) & 15) + q);                        \
     _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
       const int64_t off = (int64_t)pid_[q] * page_stride + head_tile + lane * 16;               \
       kst[q] = *(const u32x4*)(p.k_codes + off);                                                \
@@ -137,8 +163,8 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
       const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp; /* page of this lane's token */     \
       const int id = pg == 0 ? pid_[0] : pg == 1 ? pid_[1] : pg == 2 ? pid_[2] : pid_[3];       \
       const int64_t moff = (int64_t)id * page_meta + head_meta + row16 * 2;                     \
-      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                             \
-      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                             \
+      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                              \
+      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                              \
     }                                                                                           \
   }
   SAW_FETCH(0)
@@ -163,32 +189,42 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
     }
     qmul *= had_norm(p.had_block);
   }
-  // lane (row16 = head row m, grp = k-group): channels 32*grp + 8*kk + {0,4,1,5,2,6,3,7}
-  u32x4 a_hi[4], a_lo[4];
+  // A operand of the logit MFMA.  Rows m < LO carry the hi limbs of head m, rows LO + g the lo
+  // limbs of head g; lane (row16 = m, grp = k-group) holds channels 32*grp + 8*kk + {0,4,1,5,2,6,3,7}.
+  const bool is_lo = row16 >= LO;
+  const int qhead = row16 - (is_lo ? LO : 0);
+  const bool q_live = qhead < G;
+  const float* qrow = qs + (q_live ? qhead : 0) * D + 32 * grp;
+  u32x4 a_q[4];
   float qpart = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    uint32_t h16[8], l16[8];
+    uint32_t limb[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float x = (row16 < G) ? qs[row16 * D + 32 * grp + 8 * kk + j] * qmul : 0.f;
+      const float x = q_live ? qrow[8 * kk + j] * qmul : 0.f;
+      uint32_t h16, l16;
       float sum;
-      split_bf16(x, h16[j], l16[j], sum);
-      qpart += sum;
+      split_bf16(x, h16, l16, sum);
+      limb[j] = is_lo ? l16 : h16;
+      qpart += __uint_as_float(limb[j] << 16);
     }
-    a_hi[kk] = u32x4{h16[0] | (h16[4] << 16), h16[1] | (h16[5] << 16), h16[2] | (h16[6] << 16), h16[3] | (h16[7] << 16)};
-    a_lo[kk] = u32x4{l16[0] | (l16[4] << 16), l16[1] | (l16[5] << 16), l16[2] | (l16[6] << 16), l16[3] | (l16[7] << 16)};
+    a_q[kk] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
   }
   qpart += __shfl_xor(qpart, 16, 64);
-  qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the rounded q~_m
+  qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the limbs it feeds
   __syncthreads();
   if (lane < 16) qs[lane] = qpart;
   __syncthreads();
-  float qsum[NH];
+  float qsum[NH];                                // sum over channels of (hi + lo), per head of this lane
 #pragma unroll
-  for (int i = 0; i < NH; ++i) qsum[i] = qs[(G > 4) ? (4 * (grp & 1) + i) : i];
+  for (int i = 0; i < NH; ++i) {
+    const int hd = (G > 4) ? (4 * (grp & 1) + i) : i;
+    qsum[i] = qs[hd] + qs[LO + hd];
+  }
   __syncthreads();
   for (int i = lane; i < kPbufBytes / 4; i += 64) ((uint32_t*)pbuf)[i] = 0u;
+  const uint32_t kbias = bf16_bias();
 
   // ---- per-lane constants ----
   const int st_off = 16 * (4 * (lane >> 2) + (((lane & 3) + (lane >> 4)) & 3));     // staging write: t = lane>>2, Q = lane&3
@@ -231,9 +267,7 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 bk = unpack8(kw[kk]);
-        acc = mfma_bf16(as_bf16x8(a_hi[kk]), bk, acc);
-        acc = mfma_bf16(as_bf16x8(a_lo[kk]), bk, acc);
+        acc = mfma_bf16(as_bf16x8(a_q[kk]), unpack8(kw[kk], kbias), acc);
       }
       dq[q] = acc;
     }
@@ -241,11 +275,19 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
     float sraw[NS][NH];
 #pragma unroll
     for (int i = 0; i < NH; ++i) {
-      if (G > 4) {
-        sraw[0][i] = swap32x(dq[0][i], dq[1][i]);
-        sraw[NS - 1][i] = swap32x(dq[2][i], dq[3][i]);
-      } else {
-        sraw[0][i] = swap32x(swap16x(dq[0][i], dq[1][i]), swap16x(dq[2][i], dq[3][i]));
+      float hi, lo, junk;
+      if (G > 4) {      // tile rows: hi heads 0-3 | hi 4-7 | lo 0-3 | lo 4-7
+        swap32(dq[0][i], dq[1][i], hi, lo);
+        sraw[0][i] = hi + lo;
+        swap32(dq[2][i], dq[3][i], hi, lo);
+        sraw[NS - 1][i] = hi + lo;
+      } else {          // tile rows: hi heads | lo heads | idle | idle
+        float h01, l01, h23, l23;
+        swap16(dq[0][i], dq[1][i], h01, l01);
+        swap16(dq[2][i], dq[3][i], h23, l23);
+        swap32(h01, h23, hi, junk);
+        swap32(l01, l23, lo, junk);
+        sraw[0][i] = hi + lo;
       }
     }
     // ---- softmax with a lazily updated reference maximum ----
@@ -300,19 +342,19 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
         float wsum;
         split_bf16(pr * vs, h16, l16, wsum);
         zs[i] = fmaf(wsum, vz, zs[i]);
-        ((uint16_t*)pbuf)[(head0 + i) * 64 + col] = (uint16_t)h16;
-        ((uint16_t*)pbuf)[(LO + head0 + i) * 64 + col] = (uint16_t)l16;
+        ((uint16_t*)pbuf)[(head0 + i) * kProw + col] = (uint16_t)h16;
+        ((uint16_t*)pbuf)[(LO + head0 + i) * kProw + col] = (uint16_t)l16;
       }
     }
     __syncthreads();
     // ---- O[row][channel] += P (rows x 64 tokens) . V codes ----
-    const u32x4 pa0 = *(const u32x4*)(pbuf + (row16 * 64 + 16 * grp) * 2);
-    const u32x4 pa1 = *(const u32x4*)(pbuf + (row16 * 64 + 16 * grp + 8) * 2);
+    const u32x4 pa0 = *(const u32x4*)(pbuf + (row16 * kProw + 16 * grp) * 2);
+    const u32x4 pa1 = *(const u32x4*)(pbuf + (row16 * kProw + 16 * grp + 8) * 2);
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const i32x2 tv = __builtin_amdgcn_ds_read_tr4_b64_v2i32((LDS_AS i32x2*)(lds + vr_off[c]));
-      oacc[c] = mfma_bf16(as_bf16x8(pa0), unpack8((uint32_t)tv.x), oacc[c]);
-      oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y), oacc[c]);
+      oacc[c] = mfma_bf16(as_bf16x8(pa0), unpack8((uint32_t)tv.x, kbias), oacc[c]);
+      oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y, kbias), oacc[c]);
     }
   }
 
@@ -347,6 +389,7 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
 }
 
 #undef SAW_FETCH
+#undef SAW_LOAD_PIDS
 
 int launch_decode_int4_mfma(const DecodeParams& p, int G, dim3 grid, hipStream_t st) {
   switch (G) {
