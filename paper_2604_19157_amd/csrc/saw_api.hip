@@ -50,12 +50,9 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
   int S = num_splits;
   if (S == 0) {
     const int64_t items = (int64_t)B * c->n_kv_heads;
-    int64_t want = (4096 + items - 1) / items;             // enough items to fill the chip
-    int64_t max_by_min_chunk = (units + 3) / 4;            // partitions of >= 256 tokens
-    int64_t min_by_max_chunk = (units + 15) / 16;          // partitions of <= 1024 tokens
-    int64_t s = want;
+    int64_t s = (2048 + items - 1) / items;                // one wavefront per item, ~8 per compute unit
+    const int64_t max_by_min_chunk = (units + 3) / 4;      // partitions of >= 256 tokens
     if (s > max_by_min_chunk) s = max_by_min_chunk;
-    if (s < min_by_max_chunk) s = min_by_max_chunk;
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
     S = (int)s;

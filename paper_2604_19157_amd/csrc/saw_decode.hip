@@ -331,34 +331,77 @@ __global__ __launch_bounds__(256) void decode_kv16_kernel(DecodeParams p) {
 
 // ---------------------------------------------------------------------------------------
 // Merge the splits of one (sequence, query head), rotate the output back, write it.
-template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p) {
+template <int D, int NT>
+__global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
+  constexpr int NG = NT / D;                  // channel groups working on different splits
+  constexpr int NW = NT / 64;
   const int j = blockIdx.x, b = blockIdx.y;
-  const int c = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = tid % D, g = tid / D;
   const int L = min(p.seq_lens[b], p.bound);
   const int64_t o_idx = ((int64_t)b * p.n_q_heads + j) * D + c;
   if (L <= 0) {
-    store_elem(p.out, p.out_dtype, o_idx, 0.f);
+    if (g == 0) store_elem(p.out, p.out_dtype, o_idx, 0.f);
     return;
   }
+  __shared__ float wgt[1024];
+  __shared__ float red[NG][D];
+  __shared__ float wred[2][NW];
   const int ns = (L + p.chunk_tokens - 1) / p.chunk_tokens;
   const float* base = p.ws + ((int64_t)b * p.n_q_heads + j) * p.num_splits * (D + 2);
+  // reference maximum over the splits
   float mm = -INFINITY;
-  for (int s = 0; s < ns; ++s) mm = fmaxf(mm, base[s * (D + 2)]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < ns; ++s) {
+  for (int s = tid; s < ns; s += NT) mm = fmaxf(mm, base[s * (D + 2)]);
+#pragma unroll
+  for (int mk = 1; mk < 64; mk <<= 1) mm = fmaxf(mm, __shfl_xor(mm, mk, SAW_WAVE));
+  if (lane == 0) wred[0][wave] = mm;
+  __syncthreads();
+  mm = wred[0][0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, wred[0][k]);
+  // per-split weights and the denominator
+  float den = 0.f;
+  for (int s = tid; s < ns; s += NT) {
     const float a = fast_exp2(base[s * (D + 2)] - mm);
+    wgt[s] = a;
     den = fmaf(a, base[s * (D + 2) + 1], den);
-    num = fmaf(a, base[s * (D + 2) + 2 + c], num);
   }
-  float o = num / den;
-  if (p.rot_v) {
-    __shared__ float x[D];
-    x[c] = o;
+#pragma unroll
+  for (int mk = 1; mk < 64; mk <<= 1) den += __shfl_xor(den, mk, SAW_WAVE);
+  if (lane == 0) wred[1][wave] = den;
+  __syncthreads();
+  den = wred[1][0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) den += wred[1][k];
+  // numerator: group g takes splits g, g + NG, ...
+  float num = 0.f;
+#pragma unroll 4
+  for (int s = g; s < ns; s += NG) num = fmaf(wgt[s], base[s * (D + 2) + 2 + c], num);
+  red[g][c] = num;
+  __syncthreads();
+  float o = 0.f;
+  if (g == 0) {
+#pragma unroll
+    for (int k = 1; k < NG; ++k) num += red[k][c];
+    o = num / den;
+  }
+  if (p.rot_v) {                      // block-uniform
+    float* x = red[0];
+    __syncthreads();                  // every read of red[][] above is done
+    if (g == 0) x[c] = o;
     __syncthreads();
-    lds_fwht<D>(x, 1, p.had_block, c, D);
+    for (int st = 1; st < p.had_block; st <<= 1) {
+      if (tid < D / 2) {              // each butterfly pair is owned by one thread
+        const int i = (tid / st) * 2 * st + (tid % st);
+        const float a = x[i], bb = x[i + st];
+        x[i] = a + bb;
+        x[i + st] = a - bb;
+      }
+      __syncthreads();
+    }
     o = x[c] * had_norm(p.had_block);
   }
+  if (g != 0) return;
   store_elem(p.out, p.out_dtype, o_idx, o);
 }
 
@@ -379,6 +422,8 @@ int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_
   dim3 grid(p.num_splits, p.n_kv_heads, B);
   if (!kv16 && D == 128) {
     if (launch_decode_int4_mfma(p, G, grid, st) != SAW_OK) return SAW_EINVAL;
+    if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
+    if (p.num_splits == 1) return SAW_OK;       // the kernel wrote the output itself
   } else {
 #define SAW_DISPATCH_G(DD)                                                          \
   switch (G) {                                                                      \
@@ -393,8 +438,13 @@ int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_
   }
   if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
   dim3 mgrid(p.n_q_heads, B);
-  if (D == 128) decode_merge_kernel<128><<<mgrid, dim3(128), 0, st>>>(p);
-  else decode_merge_kernel<64><<<mgrid, dim3(64), 0, st>>>(p);
+  if (p.num_splits > 16) {
+    if (D == 128) decode_merge_kernel<128, 1024><<<mgrid, dim3(1024), 0, st>>>(p);
+    else decode_merge_kernel<64, 1024><<<mgrid, dim3(1024), 0, st>>>(p);
+  } else {
+    if (D == 128) decode_merge_kernel<128, 256><<<mgrid, dim3(256), 0, st>>>(p);
+    else decode_merge_kernel<64, 256><<<mgrid, dim3(256), 0, st>>>(p);
+  }
   return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
 }
 

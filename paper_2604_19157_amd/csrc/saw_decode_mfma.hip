@@ -99,6 +99,21 @@ __device__ __forceinline__ float row_allsum(float v) {
   return v;
 }
 
+// In-place un-normalised block Walsh-Hadamard transform of n_vec vectors of 128 floats in LDS,
+// run by one wavefront (the block is a single wave, so __syncthreads is a wave-level fence).
+__device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int lane) {
+  for (int st = 1; st < h; st <<= 1) {
+    for (int idx = lane; idx < n_vec * 64; idx += 64) {
+      const int v = idx >> 6, r = idx & 63;
+      const int i = v * 128 + (r / st) * 2 * st + (r % st);
+      const float a = x[i], c = x[i + st];
+      x[i] = a + c;
+      x[i + st] = a - c;
+    }
+    __syncthreads();
+  }
+}
+
 constexpr int kTileBytes = 1024;               // one (page, head) code tile: 16 tokens x 64 B
 constexpr int kStageBytes = 8 * kTileBytes;    // four K tiles then four V tiles
 constexpr int kProw = 72;                      // P row stride in bf16 (64 tokens + 8 pad: conflict-free b128 reads)
@@ -113,17 +128,36 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x;
-  const int L = min(p.seq_lens[b], p.bound);
   const int t_begin = split * p.chunk_tokens;
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page pg_first + l,
+  // i.e. one vector load covers 16 batches; `pidv_nx` is the following 64 pages, loaded 16
+  // batches ahead.  A batch takes its four ids with v_readlane, so no page-table latency sits
+  // between consecutive batches.  The first load does not wait for the sequence length:
+  // entries past the sequence's last page are read (inside the row) and clamped to a valid
+  // page, and the tokens they stand for are masked out below.
+  const int pg_first = t_begin >> 4;
+#define SAW_LOAD_PIDS(dst, first)                                                               \
+  {                                                                                             \
+    int id = p.page_table[pt_row + min((first) + lane, p.max_pages - 1)];                       \
+    dst = (id < 0 || id >= p.num_pages) ? 0 : id;                                               \
+  }
+  int pidv, pidv_nx;
+  SAW_LOAD_PIDS(pidv, pg_first)
+  const int L = min(p.seq_lens[b], p.bound);
   const int t_end = min(L, t_begin + p.chunk_tokens);
-  if (t_begin >= t_end) return;
+  if (t_begin >= t_end) {
+    if (p.num_splits == 1)          // empty sequence and no merge pass: the output row is zero
+      for (int i = lane; i < G * 128; i += 64)
+        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
+    return;
+  }
+  SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
 
   __shared__ __attribute__((aligned(16))) uint8_t lds[kStageBytes + kPbufBytes];
   uint8_t* const pbuf = lds + kStageBytes;
 
   const int row16 = lane & 15, grp = lane >> 4;
-  const int64_t pt_row = (int64_t)b * p.max_pages;
-  const int last_page = (t_end - 1) >> 4;
   const int64_t head_tile = (int64_t)kvh * kTileBytes;
   const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
   const int64_t head_meta = (int64_t)kvh * 32;                    // floats
@@ -132,19 +166,6 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   // ---- staging registers: one batch ahead ----
   u32x4 kst[4], vst[4];
   f32x2 kmeta[NS], vmeta[NS];
-  // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page pg_first + l,
-  // i.e. one vector load covers 16 batches; `pidv_nx` is the following 64 pages, loaded 16
-  // batches ahead.  A batch takes its four ids with v_readlane, so no page-table latency sits
-  // between consecutive batches.
-  const int pg_first = t_begin >> 4;
-#define SAW_LOAD_PIDS(dst, first)                                                               \
-  {                                                                                             \
-    int id = p.page_table[pt_row + min((first) + lane, last_page)];                             \
-    dst = (id < 0 || id >= p.num_pages) ? 0 : id;                                               \
-  }
-  int pidv, pidv_nx;
-  SAW_LOAD_PIDS(pidv, pg_first)
-  SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
 #define SAW_FETCH(batch)                                                                        \
   {                                                                                             \
     if ((batch) > 0 && ((batch) & 15) == 0) {                                                   \
@@ -177,16 +198,7 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   __syncthreads();
   float qmul = p.q_scale;
   if (p.rot_k) {
-    for (int st = 1; st < p.had_block; st <<= 1) {
-      for (int idx = lane; idx < G * (D / 2); idx += 64) {
-        const int v = idx / (D / 2), r = idx % (D / 2);
-        const int i = v * D + (r / st) * 2 * st + (r % st);
-        const float a = qs[i], c = qs[i + st];
-        qs[i] = a + c;
-        qs[i + st] = a - c;
-      }
-      __syncthreads();
-    }
+    wave_lds_fwht128(qs, G, p.had_block, lane);
     qmul *= had_norm(p.had_block);
   }
   // A operand of the logit MFMA.  Rows m < LO carry the hi limbs of head m, rows LO + g the lo
@@ -375,6 +387,29 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   }
   constexpr int LOSHIFT = (G > 4) ? 32 : 16;     // lanes holding the lo rows sit this far above the hi rows
   const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
+  if (p.num_splits == 1) {
+    // The partition is the whole sequence: normalise, rotate back once for V, write the output.
+    float* const fb = (float*)lds;               // [G][128]; every read of the stage area is done
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NH; ++i) {
+      const float inv = 1.0f / lsum[i];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
+        if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = (o - zs[i]) * inv;
+      }
+    }
+    __syncthreads();
+    float onorm = 1.0f;
+    if (p.rot_v) {
+      wave_lds_fwht128(fb, G, p.had_block, lane);
+      onorm = had_norm(p.had_block);
+    }
+    const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
+    for (int i = lane; i < G * D; i += 64) store_elem(p.out, p.out_dtype, obase + i, fb[i] * onorm);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
     const int head = head0 + i;
