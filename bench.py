@@ -29,6 +29,19 @@ from paper_2604_19157_amd import synth  # noqa: E402
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 
+def profiled_traffic():
+    """HBM bytes per decode launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by the copy-kernel calibration written there); None if it is absent."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "decode_int4_mfma_highconc.md")) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def decode_bytes(w, lens) -> int:
     """Algorithmic bytes of one decode call: codes + metadata of every cached token, page-table
     entries, q in and o out."""
@@ -151,6 +164,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the kv16 / store-sweep / other-config figures")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="highconc")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -158,10 +174,19 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    from paper_2604_19157_amd import binding as saw
-    saw.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "reads": n, "writes": n, "repeats": 5}))
+        return
+    from paper_2604_19157_amd import binding as saw
+    saw.lib()
 
     w = synth.make_workload(args.workload)
     B = w.batch
@@ -223,7 +248,8 @@ def main():
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "saw_paged_decode_attn (split kernel + merge)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": profiled_traffic() if args.workload == "highconc" else None,
                      "bytes_per_launch": dbytes, "avg_us": round(dec_mean_us, 2),
                      "median_us": round(float(np.median(dec_us)), 2)},
     }
