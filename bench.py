@@ -164,6 +164,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the kv16 / store-sweep / other-config figures")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="highconc")
+    ap.add_argument("--num-splits", type=int, default=0, help="split-KV factor (0 = the library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -204,14 +205,14 @@ def main():
     max_len = int(lens1.max())
     q = synth.gen_q(w, device=dev)
     out = torch.empty((B, w.n_q_heads, w.head_dim), dtype=torch.float32, device=dev)
-    ws = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len), dtype=torch.uint8, device=dev)
-    splits, chunk = saw.decode_plan(cache, B, max_len)
+    ws = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len, args.num_splits), dtype=torch.uint8, device=dev)
+    splits, chunk = saw.decode_plan(cache, B, max_len, args.num_splits)
 
     def store_step():
         saw.rotate_quant_store(cache, newK, newV, pt, new_slots)
 
     def decode_step():
-        saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
+        saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws, num_splits=args.num_splits)
 
     for _ in range(args.warmup):
         store_step()

@@ -2,11 +2,10 @@
 // caller's stream.  No allocation, no synchronisation, no global state.
 #include <math.h>
 
-#include "saw_common.h"
+#include "saw_decode.h"
 
 namespace saw {
 
-struct DecodeParams;  // defined in saw_decode.hip (kept opaque here)
 
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
                  int32_t, int32_t, const int32_t*, hipStream_t);
@@ -63,6 +62,12 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
   plan->chunk_tokens = chunk_units * 64;
   plan->num_splits = (units + chunk_units - 1) / chunk_units;
   plan->bound = bound;
+  // wavefronts per partition: only when the partitions alone cannot fill the chip (about 2560
+  // wavefront slots), and while every wavefront keeps at least 8 batches (512 tokens) of its own
+  const int64_t blocks = (int64_t)B * c->n_kv_heads * plan->num_splits;
+  int nw = 1;
+  while (nw < 4 && blocks * nw * 2 <= 2560 && plan->chunk_tokens / (nw * 2) >= 512) nw *= 2;
+  plan->waves_per_item = nw;
   return true;
 }
 
@@ -110,7 +115,7 @@ size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_h
   SplitPlan plan;
   const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
   if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return 0;
-  return (size_t)B * n_q_heads * plan.num_splits * (c->head_dim + 2) * sizeof(float);
+  return partial_bytes(B, n_q_heads, plan.num_splits, c->head_dim) + qprep_bytes(B, c->n_kv_heads);
 }
 
 int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_t num_splits,
@@ -147,7 +152,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   if (!isfinite(sm_scale)) return SAW_EINVAL;
   SplitPlan plan;
   if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
-  const size_t need = (size_t)B * Hq * plan.num_splits * (c->head_dim + 2) * sizeof(float);
+  const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim) + qprep_bytes(B, c->n_kv_heads);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
                     out_dtype, ws, plan, (hipStream_t)stream);

@@ -64,6 +64,7 @@ struct SplitPlan {
   int32_t num_splits;     // partitions per sequence
   int32_t chunk_tokens;   // tokens per partition (multiple of 64)
   int32_t bound;          // clamp for seq_lens
+  int32_t waves_per_item; // wavefronts that share one partition in the MFMA decode kernel
 };
 
 }  // namespace saw

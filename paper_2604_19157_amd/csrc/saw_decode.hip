@@ -421,7 +421,7 @@ static void launch_kv16(const DecodeParams& p, dim3 grid, hipStream_t st) {
 int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_dtype, hipStream_t st) {
   dim3 grid(p.num_splits, p.n_kv_heads, B);
   if (!kv16 && D == 128) {
-    if (launch_decode_int4_mfma(p, G, grid, st) != SAW_OK) return SAW_EINVAL;
+    if (launch_decode_int4_mfma(p, G, B, p.waves_per_item, grid, st) != SAW_OK) return SAW_EINVAL;
     if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
     if (p.num_splits == 1) return SAW_OK;       // the kernel wrote the output itself
   } else {
@@ -461,6 +461,8 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.page_table = pt;
   p.seq_lens = seq_lens;
   p.ws = (float*)ws;
+  p.qprep = (uint32_t*)((uint8_t*)ws + partial_bytes(B, Hq, plan.num_splits, c->head_dim));
+  p.qsum = (float*)((uint8_t*)p.qprep + (size_t)B * c->n_kv_heads * 4096);
   p.out = out;
   const float scale = (sm_scale > 0.f) ? sm_scale : 1.0f / sqrtf((float)c->head_dim);
   p.q_scale = scale * 1.4426950408889634f;
@@ -476,6 +478,7 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.num_splits = plan.num_splits;
   p.chunk_tokens = plan.chunk_tokens;
   p.bound = plan.bound;
+  p.waves_per_item = plan.waves_per_item;
   return launch_decode(p, B, c->head_dim, Hq / c->n_kv_heads, kv16, kv_dtype, st);
 }
 

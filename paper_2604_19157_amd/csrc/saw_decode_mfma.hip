@@ -3,9 +3,12 @@
 //
 // One wavefront (a 64-thread block) owns one (sequence, kv head, context partition) and walks
 // it in batches of four pages (64 tokens).  Per batch:
-//   * the four K and four V code tiles (1 KiB each, contiguous in HBM) are fetched one
-//     batch ahead into registers and dropped into LDS with a 16-byte-chunk swizzle
-//     pos(t, Q) = 4t + ((Q + t/4) & 3) that makes every later LDS read bank-conflict free;
+//   * the four K and four V code tiles (1 KiB each, contiguous in HBM) go straight from
+//     global memory into LDS (global_load_lds_dwordx4, no staging registers): V one batch
+//     ahead into a double buffer, K into a single buffer that is refilled as soon as its
+//     operand reads are done.  Each lane fetches the 16-byte chunk that belongs at its LDS
+//     position under the swizzle pos(t, Q) = 4t + ((Q + t/4) & 3), which makes every later
+//     LDS read bank-conflict free while a lane quad still reads one whole 64-byte row;
 //   * nibbles become bf16 operands with two ALU ops per pair: (w >> 4i) & 0x000F000F | 0x43004300
 //     is the bf16 pair (128 + c_lo, 128 + c_hi); the constant 128 joins the zero-point;
 //   * logits: D[head][token] = q~ (heads x channels) . codes (channels x tokens) with
@@ -31,6 +34,7 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_AS __attribute__((address_space(3)))
+#define GLOBAL_AS __attribute__((address_space(1)))
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -99,8 +103,18 @@ __device__ __forceinline__ float row_allsum(float v) {
   return v;
 }
 
+// The block is one wavefront: LDS operations of a wave execute in order, so exchanging data
+// between lanes through LDS needs no barrier and no wait, only a point the compiler will not
+// move memory accesses across.  (A workgroup barrier would also wait for every LDS-DMA transfer
+// in flight, which is exactly what the prefetch must not do.)
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // In-place un-normalised block Walsh-Hadamard transform of n_vec vectors of 128 floats in LDS,
-// run by one wavefront (the block is a single wave, so __syncthreads is a wave-level fence).
+// run by one wavefront.
 __device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int lane) {
   for (int st = 1; st < h; st <<= 1) {
     for (int idx = lane; idx < n_vec * 64; idx += 64) {
@@ -110,104 +124,42 @@ __device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int
       x[i] = a + c;
       x[i + st] = a - c;
     }
-    __syncthreads();
+    wave_sync();
   }
 }
 
 constexpr int kTileBytes = 1024;               // one (page, head) code tile: 16 tokens x 64 B
-constexpr int kStageBytes = 8 * kTileBytes;    // four K tiles then four V tiles
 constexpr int kProw = 72;                      // P row stride in bf16 (64 tokens + 8 pad: conflict-free b128 reads)
 constexpr int kPbufBytes = 16 * kProw * 2;     // P as bf16 [16 rows][64 tokens]
 constexpr float kLazyTau = 8.0f;               // reference max may lag the true max by 2^8
 
+// ---------------------------------------------------------------------------------------
+// q~ = (q H_blk) sm_scale log2(e) for one (sequence, kv head), written once per decode call in
+// the lane layout of the logit MFMA's A operand, as bf16 hi and lo limbs (Sec. 4.1: the query
+// is rotated once and consumed by the q.K loop).  Rows m < LO carry the hi limbs of head m,
+// rows LO + g the lo limbs of head g; lane (row16 = m, grp = k-group) holds channels
+// 32*grp + 8*kk + {0,4,1,5,2,6,3,7}.  qsum[head] is the sum over channels of hi + lo.
 template <int G>
-__global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
+__global__ __launch_bounds__(64) void decode_qprep_kernel(DecodeParams p) {
   constexpr int D = 128;
-  constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
-  constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
-  constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  constexpr int LO = (G > 4) ? 8 : 4;
+  const int kvh = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x;
-  const int t_begin = split * p.chunk_tokens;
-  const int64_t pt_row = (int64_t)b * p.max_pages;
-  // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page pg_first + l,
-  // i.e. one vector load covers 16 batches; `pidv_nx` is the following 64 pages, loaded 16
-  // batches ahead.  A batch takes its four ids with v_readlane, so no page-table latency sits
-  // between consecutive batches.  The first load does not wait for the sequence length:
-  // entries past the sequence's last page are read (inside the row) and clamped to a valid
-  // page, and the tokens they stand for are masked out below.
-  const int pg_first = t_begin >> 4;
-#define SAW_LOAD_PIDS(dst, first)                                                               \
-  {                                                                                             \
-    int id = p.page_table[pt_row + min((first) + lane, p.max_pages - 1)];                       \
-    dst = (id < 0 || id >= p.num_pages) ? 0 : id;                                               \
-  }
-  int pidv, pidv_nx;
-  SAW_LOAD_PIDS(pidv, pg_first)
-  const int L = min(p.seq_lens[b], p.bound);
-  const int t_end = min(L, t_begin + p.chunk_tokens);
-  if (t_begin >= t_end) {
-    if (p.num_splits == 1)          // empty sequence and no merge pass: the output row is zero
-      for (int i = lane; i < G * 128; i += 64)
-        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
-    return;
-  }
-  SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
-
-  __shared__ __attribute__((aligned(16))) uint8_t lds[kStageBytes + kPbufBytes];
-  uint8_t* const pbuf = lds + kStageBytes;
-
   const int row16 = lane & 15, grp = lane >> 4;
-  const int64_t head_tile = (int64_t)kvh * kTileBytes;
-  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
-  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
-  const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
-
-  // ---- staging registers: one batch ahead ----
-  u32x4 kst[4], vst[4];
-  f32x2 kmeta[NS], vmeta[NS];
-#define SAW_FETCH(batch)                                                                        \
-  {                                                                                             \
-    if ((batch) > 0 && ((batch) & 15) == 0) {                                                   \
-      pidv = pidv_nx;                                                                           \
-      SAW_LOAD_PIDS(pidv_nx, pg_first + 4 * (batch) + 64)                                       \
-    }                                                                                           \
-    int pid_[4];                                                                                \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                               \
-      pid_[q] = __builtin_amdgcn_readlane(pidv, 4 * ((batch) & 15) + q);                        \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
-      const int64_t off = (int64_t)pid_[q] * page_stride + head_tile + lane * 16;               \
-      kst[q] = *(const u32x4*)(p.k_codes + off);                                                \
-      vst[q] = *(const u32x4*)(p.v_codes + off);                                                \
-    }                                                                                           \
-    _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                            \
-      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp; /* page of this lane's token */     \
-      const int id = pg == 0 ? pid_[0] : pg == 1 ? pid_[1] : pg == 2 ? pid_[2] : pid_[3];       \
-      const int64_t moff = (int64_t)id * page_meta + head_meta + row16 * 2;                     \
-      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                              \
-      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                              \
-    }                                                                                           \
-  }
-  SAW_FETCH(0)
-
-  // ---- prologue: q~ = (q H_blk) sm_scale log2(e), as bf16 hi/lo MFMA operands ----
-  // (the stage area doubles as fp32 scratch; nothing has been staged yet)
-  float* const qs = (float*)lds;
+  __shared__ float qs[G * D];
   for (int i = lane; i < G * D; i += 64)
     qs[i] = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
-  __syncthreads();
+  wave_sync();
   float qmul = p.q_scale;
   if (p.rot_k) {
     wave_lds_fwht128(qs, G, p.had_block, lane);
     qmul *= had_norm(p.had_block);
   }
-  // A operand of the logit MFMA.  Rows m < LO carry the hi limbs of head m, rows LO + g the lo
-  // limbs of head g; lane (row16 = m, grp = k-group) holds channels 32*grp + 8*kk + {0,4,1,5,2,6,3,7}.
   const bool is_lo = row16 >= LO;
   const int qhead = row16 - (is_lo ? LO : 0);
   const bool q_live = qhead < G;
   const float* qrow = qs + (q_live ? qhead : 0) * D + 32 * grp;
-  u32x4 a_q[4];
+  u32x4* dst = (u32x4*)p.qprep + ((int64_t)b * p.n_kv_heads + kvh) * 256 + lane;
   float qpart = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
@@ -221,33 +173,135 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
       limb[j] = is_lo ? l16 : h16;
       qpart += __uint_as_float(limb[j] << 16);
     }
-    a_q[kk] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
+    dst[kk * 64] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
   }
   qpart += __shfl_xor(qpart, 16, 64);
   qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the limbs it feeds
-  __syncthreads();
+  wave_sync();
   if (lane < 16) qs[lane] = qpart;
-  __syncthreads();
+  wave_sync();
+  if (lane < 16) p.qsum[((int64_t)b * p.n_kv_heads + kvh) * 16 + lane] = (lane < G) ? qs[lane] + qs[LO + lane] : 0.f;
+}
+
+constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes;   // per wavefront: K buffer, two V buffers, P buffer
+
+// NW wavefronts share one (sequence, kv head, partition): wavefront w takes batches w, w + NW, ...
+// and the block folds their running (max, sum, accumulator) states together in LDS at the end.
+template <int G, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void decode_int4_mfma_kernel(DecodeParams p) {
+  constexpr int D = 128;
+  constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
+  constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
+  constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int t_begin = split * p.chunk_tokens;
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page
+  // pg_first + 64*window + l, i.e. one vector load covers a window of 16 batches; `pidv_nx` is
+  // the following window, loaded a window ahead.  A batch takes its four ids with v_readlane, so
+  // no page-table latency sits between consecutive batches.  The first load does not wait for
+  // the sequence length: entries past the sequence's last page are read (inside the row) and
+  // clamped to a valid page, and the tokens they stand for are masked out below.
+  const int pg_first = t_begin >> 4;
+#define SAW_LOAD_PIDS(dst, first) dst = p.page_table[pt_row + min((first) + lane, p.max_pages - 1)];
+#define SAW_CLAMP_PID(id) (((id) < 0 || (id) >= p.num_pages) ? 0 : (id))
+  int pidv, pidv_nx;                 // pidv_nx stays unclamped until it becomes pidv
+  int window = 0;                    // 16-batch window pidv covers
+  SAW_LOAD_PIDS(pidv, pg_first)
+  const int L = min(p.seq_lens[b], p.bound);
+  const int t_end = min(L, t_begin + p.chunk_tokens);
+  if (t_begin >= t_end) {            // block-uniform
+    if (p.num_splits == 1)           // empty sequence and no merge pass: the output row is zero
+      for (int i = threadIdx.x; i < G * 128; i += 64 * NW)
+        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
+    return;
+  }
+  SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
+  pidv = SAW_CLAMP_PID(pidv);
+
+  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds];
+  uint8_t* const kbuf = lds_all + wave * kWaveLds;
+  uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
+  uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
+  uint8_t* const pbuf = kbuf + 12 * kTileBytes;
+
+  const int row16 = lane & 15, grp = lane >> 4;
+  const int64_t head_tile = (int64_t)kvh * kTileBytes;
+  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
+  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
+  const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
+  const int nb = (t_end - t_begin + 63) >> 6;                     // batches of the partition
+  const int my_last = nb - 1 - ((nb - 1 - wave) % NW + NW) % NW;  // last batch of this wavefront (< wave if none)
+
+  // ---- fetch: LDS-DMA for the code tiles, registers for this lane's token metadata ----
+  // lane l fills LDS chunk l of a tile = token t = l/4, stored quarter (l & 3) = (Q + t/4) & 3
+  const int g_swz = 64 * (lane >> 2) + 16 * (((lane & 3) - (lane >> 4)) & 3);
+  f32x2 kmeta[NS], vmeta[NS];
+#define SAW_ROTATE_PIDS(batch)                                                                  \
+  if (((batch) >> 4) != window) {                                                               \
+    window = (batch) >> 4;                                                                      \
+    pidv = SAW_CLAMP_PID(pidv_nx);                                                              \
+    SAW_LOAD_PIDS(pidv_nx, pg_first + 64 * window + 64)                                         \
+  }
+#define SAW_PID(batch, q) __builtin_amdgcn_readlane(pidv, 4 * ((batch) & 15) + (q))
+#define SAW_DMA(gptr, ldsptr)                                                                   \
+  __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(gptr), (LDS_AS void*)(ldsptr), 16, 0, 0)
+  // V tiles of `batch` into VDST, plus the metadata of this lane's token(s)
+#define SAW_FETCH_V(batch, VDST)                                                                \
+  {                                                                                             \
+    SAW_ROTATE_PIDS(batch)                                                                      \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
+      const uint8_t* vp = p.v_codes + (int64_t)SAW_PID(batch, q) * page_stride + head_tile;     \
+      SAW_DMA(vp + g_swz, VDST + q * kTileBytes);                                               \
+    }                                                                                           \
+    _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                            \
+      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp; /* page of this lane's token */     \
+      const int id = pg == 0 ? SAW_PID(batch, 0) : pg == 1 ? SAW_PID(batch, 1)                  \
+                   : pg == 2 ? SAW_PID(batch, 2) : SAW_PID(batch, 3);                           \
+      const int64_t moff = (int64_t)id * page_meta + head_meta + row16 * 2;                     \
+      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                              \
+      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                              \
+    }                                                                                           \
+  }
+  // K tiles of `batch` into KDST (the ids were rotated by the V fetch of the same batch)
+#define SAW_FETCH_K(batch, KDST)                                                                \
+  {                                                                                             \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
+      const uint8_t* kp = p.k_codes + (int64_t)SAW_PID(batch, q) * page_stride + head_tile;     \
+      SAW_DMA(kp + g_swz, KDST + q * kTileBytes);                                               \
+    }                                                                                           \
+  }
+  if (wave < nb) {
+    SAW_FETCH_V(wave, vbuf_a)
+    SAW_FETCH_K(wave, kbuf)
+  }
+
+  // ---- q~ operands, prepared by decode_qprep_kernel ----
+  u32x4 a_q[4];
+  {
+    const u32x4* qp = (const u32x4*)p.qprep + ((int64_t)b * p.n_kv_heads + kvh) * 256 + lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a_q[kk] = qp[kk * 64];
+  }
   float qsum[NH];                                // sum over channels of (hi + lo), per head of this lane
 #pragma unroll
-  for (int i = 0; i < NH; ++i) {
-    const int hd = (G > 4) ? (4 * (grp & 1) + i) : i;
-    qsum[i] = qs[hd] + qs[LO + hd];
-  }
-  __syncthreads();
-  for (int i = lane; i < kPbufBytes / 4; i += 64) ((uint32_t*)pbuf)[i] = 0u;
+  for (int i = 0; i < NH; ++i)
+    qsum[i] = p.qsum[((int64_t)b * p.n_kv_heads + kvh) * 16 + ((G > 4) ? (4 * (grp & 1) + i) : i)];
   const uint32_t kbias = bf16_bias();
 
   // ---- per-lane constants ----
-  const int st_off = 16 * (4 * (lane >> 2) + (((lane & 3) + (lane >> 4)) & 3));     // staging write: t = lane>>2, Q = lane&3
   const int kr_off = 16 * (4 * row16 + ((grp + (row16 >> 2)) & 3));                 // K read: t = row16, Q = grp
   int vr_off[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c)
-    vr_off[c] = 4 * kTileBytes + grp * kTileBytes + 16 * (4 * row16 + (((c >> 1) + (row16 >> 2)) & 3)) + 8 * (c & 1);
+    vr_off[c] = grp * kTileBytes + 16 * (4 * row16 + (((c >> 1) + (row16 >> 2)) & 3)) + 8 * (c & 1);
   // P write column inside the batch: 16*page + 8*(t/8) + perm^-1(t%8),  perm^-1(u) = (u&3)<<1 | u>>2
   const int pcol_t = (row16 & 8) + (((row16 & 3) << 1) | ((row16 >> 2) & 1));
   const int head0 = (G > 4) ? 4 * (grp & 1) : 0;                                    // first head of this lane
+  const uint32_t pa_addr = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)pbuf + (row16 * kProw + 16 * grp) * 2;   // LDS byte address
 
   f32x4 oacc[8];
 #pragma unroll
@@ -256,30 +310,41 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
 
-  const int nb = (t_end - t_begin + 63) >> 6;
-  for (int bi = 0; bi < nb; ++bi) {
-    // ---- stage the fetched batch, start the next fetch ----
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      *(u32x4*)(lds + q * kTileBytes + st_off) = kst[q];
-      *(u32x4*)(lds + (4 + q) * kTileBytes + st_off) = vst[q];
-    }
+  // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
+  // only ones this wavefront has in flight.
+  // The buffers come in as __restrict__ parameters: after inlining that gives the LDS accesses
+  // and the LDS-DMA transfers distinct alias scopes, so the compiler's own wait-count insertion
+  // does not drain the prefetch before reading a buffer no transfer is writing.  Correctness
+  // does not rest on that analysis: the explicit vmcnt(0) below covers everything batch bi needs.
+  auto body = [&](const int bi, uint8_t* __restrict__ const kb, uint8_t* __restrict__ const vcur,
+                  uint8_t* __restrict__ const vnext, uint8_t* __restrict__ const pb) {
+    // (issued through the builtin, not inline asm, so that the compiler's wait-count pass sees it
+    // and stops guarding earlier loads, e.g. the q~ operands, with waits of its own further down)
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): batch bi has landed (codes in LDS, metadata)
     f32x2 km[NS], vm[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) { km[s] = kmeta[s]; vm[s] = vmeta[s]; }
-    if (bi + 1 < nb) SAW_FETCH(bi + 1)
-    __syncthreads();
+    // K operand reads first, before the next transfers are issued.
+    u32x4 kw[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) kw[q] = *(const u32x4*)(kb + q * kTileBytes + kr_off);
+    __builtin_amdgcn_s_waitcnt(0xC07F);                    // lgkmcnt(0): ... and they have returned: kb is free
+    // The next batch is fetched unconditionally (the last iteration re-fetches its own batch,
+    // which the caches absorb): a fetch under a branch would make the number of transfers in
+    // flight path-dependent and force conservative vmcnt(0) waits further down.  vnext was last
+    // read two batches ago.
+    const int nxt = min(bi + NW, my_last);
+    SAW_FETCH_V(nxt, vnext)
+    SAW_FETCH_K(nxt, kb)
 
     // ---- logits: D_q[head][token of page q] ----
     f32x4 dq[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const u32x4 kw = *(const u32x4*)(lds + q * kTileBytes + kr_off);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        acc = mfma_bf16(as_bf16x8(a_q[kk]), unpack8(kw[kk], kbias), acc);
+        acc = mfma_bf16(as_bf16x8(a_q[kk]), unpack8(kw[q][kk], kbias), acc);
       }
       dq[q] = acc;
     }
@@ -354,19 +419,65 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
         float wsum;
         split_bf16(pr * vs, h16, l16, wsum);
         zs[i] = fmaf(wsum, vz, zs[i]);
-        ((uint16_t*)pbuf)[(head0 + i) * kProw + col] = (uint16_t)h16;
-        ((uint16_t*)pbuf)[(LO + head0 + i) * kProw + col] = (uint16_t)l16;
+        ((uint16_t*)pb)[(head0 + i) * kProw + col] = (uint16_t)h16;
+        ((uint16_t*)pb)[(LO + head0 + i) * kProw + col] = (uint16_t)l16;
+      }
+    }
+    wave_sync();
+    // ---- O[row][channel] += P (rows x 64 tokens) . V codes ----
+    // The two P operand reads are issued by hand: written as ordinary LDS loads, the compiler's
+    // wait insertion cannot tell them from the buffers the LDS-DMA prefetch is filling and would
+    // drain every transfer in flight (s_waitcnt vmcnt(0)) right here.
+    u32x4 pa0, pa1;
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(pa0), "=&v"(pa1)
+                 : "v"(pa_addr)
+                 : "memory");
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const i32x2 tv = __builtin_amdgcn_ds_read_tr4_b64_v2i32((LDS_AS i32x2*)(vcur + vr_off[c]));
+      oacc[c] = mfma_bf16(as_bf16x8(pa0), unpack8((uint32_t)tv.x, kbias), oacc[c]);
+      oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y, kbias), oacc[c]);
+    }
+  };
+  for (int bi = wave; bi < nb; bi += 2 * NW) {
+    body(bi, kbuf, vbuf_a, vbuf_b, pbuf);
+    if (bi + NW < nb) body(bi + NW, kbuf, vbuf_b, vbuf_a, pbuf);
+  }
+
+  // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
+  if (NW > 1) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the trailing re-fetch has landed, buffers are free
+    float* const st = (float*)kbuf;                         // this wavefront's state: [j][lane]
+    if (wave > 0) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st[(4 * c + i) * 64 + lane] = oacc[c][i];
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        st[(32 + i) * 64 + lane] = m_ref[i];
+        st[(36 + i) * 64 + lane] = lsum[i];
+        st[(40 + i) * 64 + lane] = zs[i];
       }
     }
     __syncthreads();
-    // ---- O[row][channel] += P (rows x 64 tokens) . V codes ----
-    const u32x4 pa0 = *(const u32x4*)(pbuf + (row16 * kProw + 16 * grp) * 2);
-    const u32x4 pa1 = *(const u32x4*)(pbuf + (row16 * kProw + 16 * grp + 8) * 2);
+    if (wave > 0) return;
+#pragma unroll 1
+    for (int w = 1; w < NW; ++w) {
+      const float* so = (const float*)(lds_all + w * kWaveLds);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const i32x2 tv = __builtin_amdgcn_ds_read_tr4_b64_v2i32((LDS_AS i32x2*)(lds + vr_off[c]));
-      oacc[c] = mfma_bf16(as_bf16x8(pa0), unpack8((uint32_t)tv.x, kbias), oacc[c]);
-      oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y, kbias), oacc[c]);
+      for (int i = 0; i < NH; ++i) {
+        const float mo = so[(32 + i) * 64 + lane];
+        const float mnew = fmaxf(m_ref[i], mo);             // wavefront 0 always has a batch: finite
+        const float a0 = fast_exp2(m_ref[i] - mnew);
+        const float a1 = fast_exp2(mo - mnew);              // 0 for a wavefront that had no batch
+        lsum[i] = a0 * lsum[i] + a1 * so[(36 + i) * 64 + lane];
+        zs[i] = a0 * zs[i] + a1 * so[(40 + i) * 64 + lane];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) oacc[c][i] = a0 * oacc[c][i] + a1 * so[(4 * c + i) * 64 + lane];
+        m_ref[i] = mnew;
+      }
     }
   }
 
@@ -389,8 +500,8 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
   if (p.num_splits == 1) {
     // The partition is the whole sequence: normalise, rotate back once for V, write the output.
-    float* const fb = (float*)lds;               // [G][128]; every read of the stage area is done
-    __syncthreads();
+    float* const fb = (float*)vbuf_a;            // [G][128]; every read of the V buffers is done
+    wave_sync();
 #pragma unroll
     for (int i = 0; i < NH; ++i) {
       const float inv = 1.0f / lsum[i];
@@ -400,7 +511,7 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
         if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = (o - zs[i]) * inv;
       }
     }
-    __syncthreads();
+    wave_sync();
     float onorm = 1.0f;
     if (p.rot_v) {
       wave_lds_fwht128(fb, G, p.had_block, lane);
@@ -423,15 +534,29 @@ __global__ __launch_bounds__(64) void decode_int4_mfma_kernel(DecodeParams p) {
   }
 }
 
-#undef SAW_FETCH
+#undef SAW_FETCH_V
+#undef SAW_FETCH_K
+#undef SAW_DMA
+#undef SAW_PID
+#undef SAW_ROTATE_PIDS
 #undef SAW_LOAD_PIDS
+#undef SAW_CLAMP_PID
 
-int launch_decode_int4_mfma(const DecodeParams& p, int G, dim3 grid, hipStream_t st) {
+template <int G>
+static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
+  decode_qprep_kernel<G><<<dim3(p.n_kv_heads, B), dim3(64), 0, st>>>(p);
+  if (nw >= 4) decode_int4_mfma_kernel<G, 4><<<grid, dim3(256), 0, st>>>(p);
+  else if (nw == 2) decode_int4_mfma_kernel<G, 2><<<grid, dim3(128), 0, st>>>(p);
+  else decode_int4_mfma_kernel<G, 1><<<grid, dim3(64), 0, st>>>(p);
+}
+
+// `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or 4.
+int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st) {
   switch (G) {
-    case 1: decode_int4_mfma_kernel<1><<<grid, dim3(64), 0, st>>>(p); break;
-    case 2: decode_int4_mfma_kernel<2><<<grid, dim3(64), 0, st>>>(p); break;
-    case 4: decode_int4_mfma_kernel<4><<<grid, dim3(64), 0, st>>>(p); break;
-    case 8: decode_int4_mfma_kernel<8><<<grid, dim3(64), 0, st>>>(p); break;
+    case 1: launch_g<1>(p, B, nw, grid, st); break;
+    case 2: launch_g<2>(p, B, nw, grid, st); break;
+    case 4: launch_g<4>(p, B, nw, grid, st); break;
+    case 8: launch_g<8>(p, B, nw, grid, st); break;
     default: return SAW_EINVAL;
   }
   return SAW_OK;
