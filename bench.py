@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="highconc")
     ap.add_argument("--num-splits", type=int, default=0, help="split-KV factor (0 = the library's choice)")
+    ap.add_argument("--store-sweep-only", action="store_true",
+                    help="only run the prefill store sweep (32768-token chunk, every Hadamard block size) and print it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -188,6 +190,9 @@ def main():
         return
     from paper_2604_19157_amd import binding as saw
     saw.lib()
+    if args.store_sweep_only:
+        print(json.dumps({"prefill_store_sweep": store_sweep(saw, dev, iters=args.steps, warmup=args.warmup)}))
+        return
 
     w = synth.make_workload(args.workload)
     B = w.batch

@@ -1,28 +1,13 @@
-// Fused rotate -> token-wise INT4 quantise -> pack -> paged store, and the read-back
-// (dequantise / un-rotate) kernel.  Paper: Sec. 3 eqs. (1)-(3), App. A.1, App. A.4.
+// Read-back (dequantise / un-rotate) of the INT4 pages, and the 16-bit comparison cache's store.
+// Paper: App. A.1 (x^ = s (c - z)), App. A.4 (H is its own inverse).
 //
-// Lane layout: a head vector of D 16-bit values is spread over D/8 adjacent lanes, eight
-// contiguous channels (one 128-bit load) per lane, so a wavefront reads 1 KiB of
-// contiguous input per instruction and writes whole 64-byte (D = 128) code rows.
-// The Walsh-Hadamard butterfly runs its first three stages inside the lane and the
-// remaining log2(h) - 3 stages across lanes; it is un-normalised (+/-1 sums only) and the
-// 1/sqrt(h) factor is folded into the stored scale, which leaves the codes unchanged.
+// Lane layout: a head vector of D values is spread over D/8 adjacent lanes, eight contiguous
+// channels per lane.  The Walsh-Hadamard butterfly runs its first three stages inside the lane
+// and the remaining log2(h) - 3 stages across lanes; it is un-normalised (+/-1 sums only).
 #include "saw_common.h"
 
 namespace saw {
 
-struct StoreParams {
-  uint8_t* codes[2];
-  float* meta[2];
-  const void* in[2];
-  const int32_t* page_table;
-  const int32_t* slots;
-  int64_t T;
-  int64_t token_stride;
-  int32_t n_seqs, max_pages, num_pages, n_kv_heads;
-  int32_t had_block;
-  int32_t rot[2];
-};
 
 // One in-lane radix-2 stage over e[0..7] with span S.
 template <int S>
@@ -55,79 +40,6 @@ __device__ __forceinline__ void fwht(float (&e)[8], int sub, int h) {
       }
     }
   }
-}
-
-template <int D, int DT>
-__global__ __launch_bounds__(256) void rotate_quant_store_kernel(StoreParams p) {
-  constexpr int LPV = D / 8;         // lanes per vector
-  constexpr int VPB = 256 / LPV;     // vectors per block
-  const int tid = threadIdx.x;
-  const int sub = tid % LPV;
-  const int64_t vid = (int64_t)blockIdx.x * VPB + tid / LPV;
-  const int64_t n_vec = p.T * 2 * p.n_kv_heads;
-  // whole vectors (LPV-lane groups) are in or out together, so the shuffles below always
-  // see their partners
-  const bool live = vid < n_vec;
-  const int64_t vv = live ? vid : 0;
-  const int head = (int)(vv % p.n_kv_heads);
-  const int which = (int)((vv / p.n_kv_heads) & 1);
-  const int64_t t = vv / (2 * p.n_kv_heads);
-
-  float e[8];
-  {
-    const uint16_t* src = (const uint16_t*)p.in[which] + t * p.token_stride + head * D + sub * 8;
-    uint4 w = live ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
-    widen2<DT>(w.x, e[0], e[1]);
-    widen2<DT>(w.y, e[2], e[3]);
-    widen2<DT>(w.z, e[4], e[5]);
-    widen2<DT>(w.w, e[6], e[7]);
-  }
-  float norm = 1.0f;
-  if (p.rot[which]) {
-    fwht<LPV>(e, sub, p.had_block);
-    norm = had_norm(p.had_block);
-  }
-  float mn = e[0], mx = e[0];
-#pragma unroll
-  for (int i = 1; i < 8; ++i) {
-    mn = fminf(mn, e[i]);
-    mx = fmaxf(mx, e[i]);
-  }
-#pragma unroll
-  for (int m = 1; m < LPV; m <<= 1) {
-    mn = fminf(mn, __shfl_xor(mn, m, SAW_WAVE));
-    mx = fmaxf(mx, __shfl_xor(mx, m, SAW_WAVE));
-  }
-  const float range = mx - mn;
-  float inv, zq, s_store, z_store;
-  if (range > 0.0f) {
-    inv = 15.0f / range;
-    s_store = range * (norm * (1.0f / 15.0f));
-    zq = rintf(-mn * inv);
-    z_store = zq;
-  } else {  // constant vector
-    inv = 0.0f;
-    zq = 0.0f;
-    s_store = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
-    z_store = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
-  }
-  uint32_t packed = 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float c = rintf(e[i] * inv) + zq;
-    c = fminf(fmaxf(c, 0.0f), 15.0f);
-    packed |= ((uint32_t)c) << (4 * i);
-  }
-  if (!live) return;
-  // paged placement
-  const int32_t seq = p.slots[2 * t];
-  const int32_t pos = p.slots[2 * t + 1];
-  if (seq < 0 || seq >= p.n_seqs || pos < 0 || (pos >> 4) >= p.max_pages) return;
-  const int32_t page = p.page_table[(int64_t)seq * p.max_pages + (pos >> 4)];
-  if (page < 0 || page >= p.num_pages) return;
-  const int64_t vec = ((int64_t)page * p.n_kv_heads + head) * 16 + (pos & 15);
-  ((uint32_t*)(p.codes[which] + vec * (D / 2)))[sub] = packed;
-  if (sub == 0) *(float2*)(p.meta[which] + vec * 2) = make_float2(s_store, z_store);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -212,29 +124,15 @@ __global__ __launch_bounds__(256) void kv16_store_kernel(Kv16StoreParams p) {
 
 // ---------------------------------------------------------------------------------------
 // host launchers (called from saw_api.hip)
+// the store kernel itself lives in saw_store_mfma.hip
+int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
+                      const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
+                      hipStream_t st);
+
 int launch_store(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                  const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
                  hipStream_t st) {
-  StoreParams p;
-  p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
-  p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
-  p.in[0] = K; p.in[1] = V;
-  p.page_table = pt; p.slots = slots; p.T = T; p.token_stride = stride;
-  p.n_seqs = n_seqs; p.max_pages = max_pages; p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads;
-  p.had_block = c->had_block;
-  p.rot[0] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);
-  p.rot[1] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
-  const int D = c->head_dim;
-  const int vpb = 256 / (D / 8);
-  const int64_t n_vec = T * 2 * c->n_kv_heads;
-  const int64_t blocks = (n_vec + vpb - 1) / vpb;
-  if (blocks > 0x7fffffffLL) return SAW_EINVAL;
-  dim3 grid((unsigned)blocks), block(256);
-  if (D == 128 && dt == SAW_BF16) rotate_quant_store_kernel<128, SAW_BF16><<<grid, block, 0, st>>>(p);
-  else if (D == 128) rotate_quant_store_kernel<128, SAW_F16><<<grid, block, 0, st>>>(p);
-  else if (dt == SAW_BF16) rotate_quant_store_kernel<64, SAW_BF16><<<grid, block, 0, st>>>(p);
-  else rotate_quant_store_kernel<64, SAW_F16><<<grid, block, 0, st>>>(p);
-  return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
+  return launch_store_mfma(c, K, V, dt, T, stride, pt, n_seqs, max_pages, slots, st);
 }
 
 int launch_dequant(const saw_cache_t* c, const int32_t* pt, int32_t max_pages, int32_t seq,

@@ -1,0 +1,269 @@
+// Fused rotate -> token-wise INT4 quantise -> pack -> paged store on the gfx950 matrix cores.
+// Paper: Sec. 3 eqs. (1)-(3) (K~ = quant(K H_blk)), App. A.1 (s, z, codes, nibble packing),
+// App. A.4 (block-diagonal Hadamard of order h | d).
+//
+// One wavefront takes 16 consecutive tokens of one (K|V, kv head): a 16 x D tile of 16-bit values.
+//   * the tile is read with coalesced 128-bit loads (each 16-lane row reads 256 contiguous
+//     bytes) and passed through LDS once, with an XOR chunk swizzle that keeps both sides free
+//     of bank conflicts, to reach the MFMA operand layout (column = token);
+//   * the Walsh-Hadamard transform over the low five channel bits (32 contiguous channels) is one
+//     pair of v_mfma_f32_16x16x32 with a +/-1 matrix: the 16-bit inputs are the B operand as they
+//     are (no widening), products with +/-1 are exact and the sums accumulate in fp32.  The
+//     matrix also encodes smaller orders (block-diagonal for h = 16, identity for h = 1), so
+//     every Hadamard order runs the same instruction stream; its rows are ordered so that a
+//     lane ends up with eight *contiguous* output channels;
+//   * a lane ends up with 8 values of each 32-channel group of ONE token, so the one or two
+//     remaining butterfly stages of orders 64 and 128 are register-to-register;
+//   * min/max: in-lane, then across the four 16-lane rows that hold the same token;
+//   * quantise with a reciprocal multiply, pack eight nibbles per dword; when the 16 tokens are
+//     the 16 slots of one page (prefill) the code dwords are transposed through LDS and leave as
+//     one contiguous 1 KiB tile write, otherwise as per-token dword stores.
+// The transform is un-normalised; 1/sqrt(h) is folded into the stored scale (codes unchanged).
+#include "saw_common.h"
+
+namespace saw {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct StoreMfmaParams {
+  uint8_t* codes[2];
+  float* meta[2];
+  const void* in[2];
+  const int32_t* page_table;
+  const int32_t* slots;
+  int64_t T;
+  int64_t token_stride;
+  int32_t n_seqs, max_pages, num_pages, n_kv_heads;
+  int32_t had_block;
+  int32_t rot[2];
+};
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma_pm1(u32x4 a, u32x4 b, f32x4 c) {
+  if (DT == SAW_BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dppf(float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, false));
+}
+
+// XS = number of register-to-register butterfly stages after the MFMA (0: h <= 32 or no rotation,
+// 1: h = 64, 2: h = 128) when K and V agree; XS = -1 decides per wavefront at run time (K-only
+// or V-only rotation).
+template <int D, int DT, int XS>
+__global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaParams p) {
+  constexpr int ROWB = D * 2;            // bytes of one token's head vector
+  constexpr int XC = ROWB / 16;          // 16-byte chunks per vector (16 | 8)
+  constexpr int NA = D / 32;             // 32-channel groups per vector (4 | 2)
+  constexpr int RP = 256 / ROWB;         // token rows per 256 bytes of LDS (1 | 2)
+  constexpr int NLD = (16 * ROWB) / 1024;  // 128-bit loads per lane (4 | 2)
+  constexpr int NV = 8 * NA;             // output values per lane
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n16 = lane & 15, rg = lane >> 4;
+  const int n_kinds = 2 * p.n_kv_heads;                       // (K|V, head) combinations
+  const int kind_raw = blockIdx.y * 4 + __builtin_amdgcn_readfirstlane(wave);
+  const bool wave_live = kind_raw < n_kinds;                  // wave-uniform
+  const int kind = wave_live ? kind_raw : 0;                  // an idle wavefront shadows kind 0 and stores nothing
+  const int which = kind >= p.n_kv_heads ? 1 : 0;
+  const int head = kind - which * p.n_kv_heads;
+  const int64_t t0 = (int64_t)blockIdx.x * 16;
+  const bool rot = p.rot[which] != 0;
+
+  __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][16 * ROWB];
+  uint8_t* const stage = stage_all[wave];
+
+  // ---- issue the tile loads (coalesced: each 16-lane row reads 256 contiguous bytes) ----
+  u32x4 ld[NLD];
+#pragma unroll
+  for (int r = 0; r < NLD; ++r) {
+    const int off = r * 1024 + 16 * lane;                      // byte offset in the dense 16 x D tile
+    const int tok = off / ROWB, x = (off % ROWB) / 16;
+    const int64_t t = min(t0 + tok, p.T - 1);                  // tokens past the end shadow the last one; never stored
+    ld[r] = *(const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * D + 8 * x);
+  }
+  // this lane's token (column n16 of the tile) and where it goes
+  const int64_t t_mine = t0 + n16;
+  int2 slot = make_int2(-1, -1);
+  if (wave_live && t_mine < p.T) slot = *(const int2*)(p.slots + 2 * t_mine);
+
+  // ---- the +/-1 matrix: A[m][k], m = output row, k = input channel (low five bits) ----
+  // MFMA #1 row m -> output channel (low five bits) 8*(m/4) + m%4, MFMA #2 row m -> that + 4,
+  // so lane (n16, rg) receives channels 8*rg .. 8*rg+7 of every 32-channel group.
+  // Entry = (-1)^popcount(lo & k & (hm-1)) where the bits above the order hm agree, else 0.
+  const int hm = rot ? min(p.had_block, 32) : 1;              // order handled inside the MFMA
+  u32x4 ha1, ha2;
+  {
+    const uint32_t one = (DT == SAW_BF16) ? 0x3F80u : 0x3C00u;
+    const int lo1 = 8 * (n16 >> 2) + (n16 & 3);                // A operand: lane (m = n16, k-group = rg)
+    uint32_t e1[8], e2[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int cl = 8 * rg + j;
+      const int lo2 = lo1 + 4;
+      const bool on1 = (((lo1 ^ cl) & ~(hm - 1)) & 31) == 0;
+      const bool on2 = (((lo2 ^ cl) & ~(hm - 1)) & 31) == 0;
+      const uint32_t s1 = (__builtin_popcount(lo1 & cl & (hm - 1)) & 1) ? 0x8000u : 0u;
+      const uint32_t s2 = (__builtin_popcount(lo2 & cl & (hm - 1)) & 1) ? 0x8000u : 0u;
+      e1[j] = on1 ? (one | s1) : 0u;
+      e2[j] = on2 ? (one | s2) : 0u;
+    }
+    ha1 = u32x4{e1[0] | (e1[1] << 16), e1[2] | (e1[3] << 16), e1[4] | (e1[5] << 16), e1[6] | (e1[7] << 16)};
+    ha2 = u32x4{e2[0] | (e2[1] << 16), e2[2] | (e2[3] << 16), e2[4] | (e2[5] << 16), e2[6] | (e2[7] << 16)};
+  }
+
+  // ---- through LDS into the B-operand layout: column = token, k-group rg = chunk 4a + rg ----
+  // chunk x of token tok sits at chunk position x ^ ((tok / RP) & (XC-1)): both the row-wise
+  // writes and the column-wise reads below touch every bank once.
+#pragma unroll
+  for (int r = 0; r < NLD; ++r) {
+    const int off = r * 1024 + 16 * lane;
+    const int tok = off / ROWB, x = (off % ROWB) / 16;
+    *(u32x4*)(stage + tok * ROWB + 16 * (x ^ ((tok / RP) & (XC - 1)))) = ld[r];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float y[NV];                                                  // y[8a + i]: channel 32a + 8rg + i of token n16
+#pragma unroll
+  for (int a = 0; a < NA; ++a) {
+    const int x = 4 * a + rg;
+    const u32x4 bv = *(const u32x4*)(stage + n16 * ROWB + 16 * (x ^ ((n16 / RP) & (XC - 1))));
+    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+    const f32x4 d1 = mfma_pm1<DT>(ha1, bv, zero);
+    const f32x4 d2 = mfma_pm1<DT>(ha2, bv, zero);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { y[8 * a + i] = d1[i]; y[8 * a + 4 + i] = d2[i]; }
+  }
+  // ---- orders 64 / 128: butterflies across the 32-channel groups, now register to register ----
+  if (XS >= 1 || (XS < 0 && rot && p.had_block >= 64)) {
+#pragma unroll
+    for (int a = 0; a < NA; a += 2)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float u = y[8 * a + i], v = y[8 * a + 8 + i];
+        y[8 * a + i] = u + v;
+        y[8 * a + 8 + i] = u - v;
+      }
+  }
+  if (D == 128 && (XS >= 2 || (XS < 0 && rot && p.had_block >= 128))) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float u = y[8 * a + i], v = y[8 * a + 16 + i];
+        y[8 * a + i] = u + v;
+        y[8 * a + 16 + i] = u - v;
+      }
+  }
+  const float norm = rot ? had_norm(p.had_block) : 1.0f;
+
+  // ---- token-wise min / max: in-lane, then the four rows holding the same token ----
+  float mn = y[0], mx = y[0];
+#pragma unroll
+  for (int i = 1; i < NV; ++i) { mn = fminf(mn, y[i]); mx = fmaxf(mx, y[i]); }
+  mn = fminf(mn, __shfl_xor(mn, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mn = fminf(mn, __shfl_xor(mn, 32, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+  // ---- scale / zero (App. A.1), quantise, pack ----
+  const float range = mx - mn;
+  float inv, zq, s_store, z_store;
+  if (range > 0.0f) {
+    inv = 15.0f / range;
+    s_store = range * (norm * (1.0f / 15.0f));
+    zq = rintf(-mn * inv);
+    z_store = zq;
+  } else {  // constant vector
+    inv = 0.0f;
+    zq = 0.0f;
+    s_store = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
+    z_store = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
+  }
+  uint32_t packed[NA];
+#pragma unroll
+  for (int a = 0; a < NA; ++a) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float c = rintf(y[8 * a + i] * inv) + zq;
+      c = __builtin_amdgcn_fmed3f(c, 0.0f, 15.0f);
+      w |= ((uint32_t)c) << (4 * i);
+    }
+    packed[a] = w;                                              // dword 4a + rg of the token's code row
+  }
+  if (!wave_live) return;
+
+  // ---- paged placement ----
+  int32_t page = -1;
+  const bool slot_ok = slot.x >= 0 && slot.x < p.n_seqs && slot.y >= 0 && (slot.y >> 4) < p.max_pages;
+  if (slot_ok) page = p.page_table[(int64_t)slot.x * p.max_pages + (slot.y >> 4)];
+  const bool ok = slot_ok && page >= 0 && page < p.num_pages;
+  // fast path: the 16 tokens are the 16 slots of one page, in order
+  const int seq0 = __builtin_amdgcn_readfirstlane(slot.x);
+  const int pos0 = __builtin_amdgcn_readfirstlane(slot.y);
+  const bool aligned = __all(ok && slot.x == seq0 && slot.y == pos0 + n16) && ((pos0 & 15) == 0);
+  if (aligned) {
+    const int page0 = __builtin_amdgcn_readfirstlane(page);
+    const int64_t vec0 = ((int64_t)page0 * p.n_kv_heads + head) * 16;
+    // transpose the code dwords through LDS so that every lane writes 16 contiguous bytes
+    uint32_t* const ob = (uint32_t*)stage;                     // [token][D/8 dwords]
+#pragma unroll
+    for (int a = 0; a < NA; ++a) ob[n16 * (D / 8) + 4 * a + rg] = packed[a];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (lane < 16 * (D / 2) / 16)
+      *(u32x4*)(p.codes[which] + vec0 * (D / 2) + 16 * lane) = *(const u32x4*)(stage + 16 * lane);
+    if (rg == 0) *(float2*)(p.meta[which] + (vec0 + n16) * 2) = make_float2(s_store, z_store);
+    return;
+  }
+  if (!ok) return;
+  const int64_t vec = ((int64_t)page * p.n_kv_heads + head) * 16 + (slot.y & 15);
+#pragma unroll
+  for (int a = 0; a < NA; ++a) ((uint32_t*)(p.codes[which] + vec * (D / 2)))[4 * a + rg] = packed[a];
+  if (rg == 0) *(float2*)(p.meta[which] + vec * 2) = make_float2(s_store, z_store);
+}
+
+int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
+                      const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
+                      hipStream_t st) {
+  StoreMfmaParams p;
+  p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
+  p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
+  p.in[0] = K; p.in[1] = V;
+  p.page_table = pt; p.slots = slots; p.T = T; p.token_stride = stride;
+  p.n_seqs = n_seqs; p.max_pages = max_pages; p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads;
+  p.had_block = c->had_block;
+  p.rot[0] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);
+  p.rot[1] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
+  const int D = c->head_dim;
+  const int64_t tblocks = (T + 15) / 16;
+  if (tblocks > 0x7fffffffLL) return SAW_EINVAL;
+  const int kblocks = (2 * c->n_kv_heads + 3) / 4;
+  if (kblocks > 65535) return SAW_EINVAL;
+  dim3 grid((unsigned)tblocks, kblocks), block(256);
+  const int h = c->had_block;
+  int xs = -1;                                                  // static stage count when K and V agree
+  if (p.rot[0] == p.rot[1]) xs = !p.rot[0] ? 0 : (h >= 128 ? 2 : (h >= 64 ? 1 : 0));
+#define SAW_LAUNCH(DD, TT)                                                                             \
+  switch (xs) {                                                                                        \
+    case 0: rotate_quant_store_mfma_kernel<DD, TT, 0><<<grid, block, 0, st>>>(p); break;               \
+    case 1: rotate_quant_store_mfma_kernel<DD, TT, 1><<<grid, block, 0, st>>>(p); break;               \
+    case 2: rotate_quant_store_mfma_kernel<DD, TT, (DD == 128 ? 2 : 1)><<<grid, block, 0, st>>>(p); break; \
+    default: rotate_quant_store_mfma_kernel<DD, TT, -1><<<grid, block, 0, st>>>(p); break;             \
+  }
+  if (D == 128 && dt == SAW_BF16) { SAW_LAUNCH(128, SAW_BF16) }
+  else if (D == 128) { SAW_LAUNCH(128, SAW_F16) }
+  else if (dt == SAW_BF16) { SAW_LAUNCH(64, SAW_BF16) }
+  else { SAW_LAUNCH(64, SAW_F16) }
+#undef SAW_LAUNCH
+  return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
+}
+
+}  // namespace saw
