@@ -103,8 +103,7 @@ int saw_rotate_quant_store(const saw_cache_t* cache, const void* K, const void* 
 
 /*
  * Bytes of scratch saw_paged_decode_attn needs for these arguments (split-KV partial
- * results [B][n_q_heads][splits][head_dim + 2] float32, then the rotated query operands
- * [B][n_kv_heads] x 4160 bytes).  max_seq_len and num_splits
+ * results [B][n_q_heads][splits][head_dim + 2] float32, rounded up to 16 bytes).  max_seq_len and num_splits
  * have the meaning below; returns 0 on invalid arguments.
  */
 size_t saw_decode_workspace_bytes(const saw_cache_t* cache, int32_t B, int32_t n_q_heads,

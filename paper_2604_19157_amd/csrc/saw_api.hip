@@ -115,7 +115,7 @@ size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_h
   SplitPlan plan;
   const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
   if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return 0;
-  return partial_bytes(B, n_q_heads, plan.num_splits, c->head_dim) + qprep_bytes(B, c->n_kv_heads);
+  return partial_bytes(B, n_q_heads, plan.num_splits, c->head_dim);
 }
 
 int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_t num_splits,
@@ -152,7 +152,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   if (!isfinite(sm_scale)) return SAW_EINVAL;
   SplitPlan plan;
   if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
-  const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim) + qprep_bytes(B, c->n_kv_heads);
+  const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
                     out_dtype, ws, plan, (hipStream_t)stream);

@@ -14,8 +14,6 @@ struct DecodeParams {
   const int32_t* page_table;
   const int32_t* seq_lens;
   float* ws;            // [B][Hq][S][D + 2]: (m, l, acc[D])
-  uint32_t* qprep;      // [B][Hkv][4][64 lanes][4] dwords: rotated, scaled q as MFMA operand limbs (d = 128 path)
-  float* qsum;          // [B][Hkv][16]: per head, the sum over channels of the limbs in qprep
   void* out;
   float q_scale;        // sm_scale * log2(e)
   int32_t q_dtype, out_dtype;
@@ -28,8 +26,6 @@ struct DecodeParams {
 // MFMA INT4 decode for head_dim 128 (saw_decode_mfma.hip); grid = (splits, kv heads, batch).
 int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st);
 
-// Bytes of the q-operand area that follows the split partials in the workspace (d = 128 path).
-inline size_t qprep_bytes(int B, int n_kv_heads) { return (size_t)B * n_kv_heads * (4096 + 64); }
 inline size_t partial_bytes(int B, int Hq, int splits, int D) {
   return (((size_t)B * Hq * splits * (D + 2) * sizeof(float)) + 15) & ~(size_t)15;
 }

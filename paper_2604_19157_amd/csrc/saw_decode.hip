@@ -461,8 +461,6 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.page_table = pt;
   p.seq_lens = seq_lens;
   p.ws = (float*)ws;
-  p.qprep = (uint32_t*)((uint8_t*)ws + partial_bytes(B, Hq, plan.num_splits, c->head_dim));
-  p.qsum = (float*)((uint8_t*)p.qprep + (size_t)B * c->n_kv_heads * 4096);
   p.out = out;
   const float scale = (sm_scale > 0.f) ? sm_scale : 1.0f / sqrtf((float)c->head_dim);
   p.q_scale = scale * 1.4426950408889634f;

@@ -134,21 +134,23 @@ constexpr int kPbufBytes = 16 * kProw * 2;     // P as bf16 [16 rows][64 tokens]
 constexpr float kLazyTau = 8.0f;               // reference max may lag the true max by 2^8
 
 // ---------------------------------------------------------------------------------------
-// q~ = (q H_blk) sm_scale log2(e) for one (sequence, kv head), written once per decode call in
-// the lane layout of the logit MFMA's A operand, as bf16 hi and lo limbs (Sec. 4.1: the query
-// is rotated once and consumed by the q.K loop).  Rows m < LO carry the hi limbs of head m,
-// rows LO + g the lo limbs of head g; lane (row16 = m, grp = k-group) holds channels
-// 32*grp + 8*kk + {0,4,1,5,2,6,3,7}.  qsum[head] is the sum over channels of hi + lo.
-template <int G>
-__global__ __launch_bounds__(64) void decode_qprep_kernel(DecodeParams p) {
+// q~ = (q H_blk) sm_scale log2(e) for the G query heads of one kv head, in the lane layout of the
+// logit MFMA's A operand, as bf16 hi and lo limbs (Sec. 4.1: the query is rotated once and
+// consumed by the q.K loop).  Rows m < LO carry the hi limbs of head m, rows LO + g the lo limbs
+// of head g; lane (row16 = m, grp = k-group) holds channels 32*grp + 8*kk + {0,4,1,5,2,6,3,7}.
+// qsum[i] is the sum over channels of hi + lo for the i-th head of this lane's softmax layout.
+// `qraw` holds this lane's share of q (element lane + 64 j), loaded by the caller ahead of time;
+// `qs` is LDS scratch of G*128 floats.  It is a __restrict__ parameter on purpose: that keeps
+// these LDS accesses in an alias scope of their own, so the compiler does not make them wait for
+// the LDS-DMA transfers the caller already has in flight into other buffers.
+template <int G, int NH>
+__device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&qraw)[2 * G], int lane,
+                                          float* __restrict__ qs, u32x4 (&a_q)[4], float (&qsum)[NH]) {
   constexpr int D = 128;
   constexpr int LO = (G > 4) ? 8 : 4;
-  const int kvh = blockIdx.x, b = blockIdx.y;
-  const int lane = threadIdx.x;
   const int row16 = lane & 15, grp = lane >> 4;
-  __shared__ float qs[G * D];
-  for (int i = lane; i < G * D; i += 64)
-    qs[i] = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+#pragma unroll
+  for (int j = 0; j < 2 * G; ++j) qs[lane + 64 * j] = qraw[j];
   wave_sync();
   float qmul = p.q_scale;
   if (p.rot_k) {
@@ -159,7 +161,6 @@ __global__ __launch_bounds__(64) void decode_qprep_kernel(DecodeParams p) {
   const int qhead = row16 - (is_lo ? LO : 0);
   const bool q_live = qhead < G;
   const float* qrow = qs + (q_live ? qhead : 0) * D + 32 * grp;
-  u32x4* dst = (u32x4*)p.qprep + ((int64_t)b * p.n_kv_heads + kvh) * 256 + lane;
   float qpart = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
@@ -173,14 +174,19 @@ __global__ __launch_bounds__(64) void decode_qprep_kernel(DecodeParams p) {
       limb[j] = is_lo ? l16 : h16;
       qpart += __uint_as_float(limb[j] << 16);
     }
-    dst[kk * 64] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
+    a_q[kk] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
   }
   qpart += __shfl_xor(qpart, 16, 64);
   qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the limbs it feeds
   wave_sync();
   if (lane < 16) qs[lane] = qpart;
   wave_sync();
-  if (lane < 16) p.qsum[((int64_t)b * p.n_kv_heads + kvh) * 16 + lane] = (lane < G) ? qs[lane] + qs[LO + lane] : 0.f;
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    const int hd = (G > 4) ? (4 * (grp & 1) + i) : i;
+    qsum[i] = qs[hd] + qs[LO + hd];
+  }
+  wave_sync();
 }
 
 constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes;   // per wavefront: K buffer, two V buffers, P buffer
@@ -221,6 +227,18 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   }
   SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
   pidv = SAW_CLAMP_PID(pidv);
+  // this lane's share of the G query vectors (element lane + 64 j), issued ahead of the code transfers
+  uint32_t qbits[2 * G];
+  {
+    const int64_t qoff = ((int64_t)b * p.n_q_heads + kvh * G) * D + lane;
+    if (p.q_dtype == SAW_F32) {
+#pragma unroll
+      for (int j = 0; j < 2 * G; ++j) qbits[j] = ((const uint32_t*)p.q)[qoff + 64 * j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2 * G; ++j) qbits[j] = ((const uint16_t*)p.q)[qoff + 64 * j];
+    }
+  }
 
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds];
   uint8_t* const kbuf = lds_all + wave * kWaveLds;
@@ -274,22 +292,31 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       SAW_DMA(kp + g_swz, KDST + q * kTileBytes);                                               \
     }                                                                                           \
   }
-  if (wave < nb) {
-    SAW_FETCH_V(wave, vbuf_a)
-    SAW_FETCH_K(wave, kbuf)
-  }
 
-  // ---- q~ operands, prepared by decode_qprep_kernel ----
+  // ---- the q~ operands, then the first transfers ----
+  // (q~ first: its LDS scratch traffic would otherwise be made to wait for the transfers by the
+  // compiler's conservative LDS-DMA ordering; the query loads were issued further up, so this
+  // costs about a microsecond per block before the first transfer leaves)
   u32x4 a_q[4];
+  float qsum[NH];
   {
-    const u32x4* qp = (const u32x4*)p.qprep + ((int64_t)b * p.n_kv_heads + kvh) * 256 + lane;
+    float qraw[2 * G];
+    const bool q_is_f32 = p.q_dtype == SAW_F32, q_is_bf16 = p.q_dtype == SAW_BF16;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) a_q[kk] = qp[kk * 64];
+    for (int j = 0; j < 2 * G; ++j) {                       // all three widenings, then selects
+      const float as_f32 = __uint_as_float(qbits[j]);
+      const float as_bf16 = __uint_as_float(qbits[j] << 16);
+      const float as_f16 = f16_to_f32(qbits[j] & 0xffffu);
+      qraw[j] = q_is_f32 ? as_f32 : (q_is_bf16 ? as_bf16 : as_f16);
+    }
+    prepare_q<G, NH>(p, qraw, lane, (float*)vbuf_b, a_q, qsum);
   }
-  float qsum[NH];                                // sum over channels of (hi + lo), per head of this lane
-#pragma unroll
-  for (int i = 0; i < NH; ++i)
-    qsum[i] = p.qsum[((int64_t)b * p.n_kv_heads + kvh) * 16 + ((G > 4) ? (4 * (grp & 1) + i) : i)];
+  {
+    // issued unconditionally: a wavefront without a batch of its own shadows the last batch
+    const int first = min(wave, nb - 1);
+    SAW_FETCH_V(first, vbuf_a)
+    SAW_FETCH_K(first, kbuf)
+  }
   const uint32_t kbias = bf16_bias();
 
   // ---- per-lane constants ----
@@ -544,7 +571,6 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
 template <int G>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
-  decode_qprep_kernel<G><<<dim3(p.n_kv_heads, B), dim3(64), 0, st>>>(p);
   if (nw >= 4) decode_int4_mfma_kernel<G, 4><<<grid, dim3(256), 0, st>>>(p);
   else if (nw == 2) decode_int4_mfma_kernel<G, 2><<<grid, dim3(128), 0, st>>>(p);
   else decode_int4_mfma_kernel<G, 1><<<grid, dim3(64), 0, st>>>(p);

@@ -98,7 +98,7 @@ def test_workspace_and_plan(saw):
         assert (s.value - 1) * c.value < msl                         # no empty trailing partition
         if ns:
             assert s.value <= ns
-        assert L.saw_decode_workspace_bytes(ctypes.byref(st), B, Hq, msl, ns) == ((B * Hq * s.value * 130 * 4 + 15) // 16) * 16 + B * 8 * 4160
+        assert L.saw_decode_workspace_bytes(ctypes.byref(st), B, Hq, msl, ns) == ((B * Hq * s.value * 130 * 4 + 15) // 16) * 16
     assert L.saw_decode_workspace_bytes(ctypes.byref(st), 0, 32, 100, 0) == 0
 
 
