@@ -472,9 +472,13 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     if (bi + NW < nb) body(bi + NW, kbuf, vbuf_b, vbuf_a, pbuf);
   }
 
+  // The last iteration re-fetched its own batch into kbuf and one of the V buffers.  Everything
+  // below reuses those buffers as scratch, so that transfer has to have landed first: without this
+  // wait it can arrive after the scratch has been written and overwrite it.
+  __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
   if (NW > 1) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the trailing re-fetch has landed, buffers are free
     float* const st = (float*)kbuf;                         // this wavefront's state: [j][lane]
     if (wave > 0) {
 #pragma unroll

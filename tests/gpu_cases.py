@@ -34,6 +34,35 @@ def fill_caches(w, saw, dev="cuda", chunk=4096, order_rng=None, with_ref=True):
     return cache, ref, recs, pt
 
 
+def oracle_fill(w, chunk=4096, seqs=None):
+    """The oracle's cache for `w` (all sequences, or only `seqs`), written by the oracle's own store."""
+    ref = O.new_cache(w.num_pages, w.n_kv_heads, w.page_size, w.head_dim)
+    for b in (range(w.batch) if seqs is None else seqs):
+        L = int(w.seq_lens[b])
+        for p0 in range(0, L, chunk):
+            p1 = min(L, p0 + chunk)
+            K, V = synth.gen_kv(w, b, p0, p1)
+            O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), w.page_table,
+                                 synth.slots_for(b, p0, p1), w.had_block, w.rotate_mask)
+    return ref
+
+
+def upload_cache(ref, w, saw, dev="cuda", into=None, pages=None):
+    """Copy an oracle cache's bytes into a device cache (a new one, or rows `pages` of `into`)."""
+    cache = into if into is not None else saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block,
+                                                    w.rotate_mask, device=dev)
+    for k in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        dst = getattr(cache, k)
+        if pages is None:
+            dst.copy_(torch.from_numpy(ref[k]).reshape(dst.shape))
+        else:
+            idx = torch.from_numpy(np.asarray(pages, np.int64)).to(dev)
+            src = torch.from_numpy(ref[k][np.asarray(pages)]).to(dev)
+            dst.view(dst.shape[0], -1)[idx] = src.reshape(len(pages), -1).to(dst.dtype)
+    torch.cuda.synchronize()
+    return cache
+
+
 def cache_to_numpy(cache, w):
     d = {k: getattr(cache, k).cpu().numpy() for k in ("k_codes", "v_codes", "k_meta", "v_meta")}
     d.update(page_size=w.page_size, head_dim=w.head_dim, n_kv_heads=w.n_kv_heads)

@@ -1,0 +1,110 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (automatic split
+choice, bf16 inputs, fp32 or bf16 output): the whole workload runs through the HIP path, and the oracle
+computes the sequences of a seeded sample one by one.
+
+The sampled sequences' cache pages hold the bytes the oracle's store wrote (uploaded), so the decode
+comparison is over identical bytes; every other sequence is stored by the HIP store from device-generated
+synthetic K/V and is checked through properties that hold at any size (finite output, a convex combination
+of cached vectors cannot be longer than the longest of them).
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_cases as gc
+import parity
+from oracle import saw_oracle as O
+from paper_2604_19157_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def saw():
+    from paper_2604_19157_amd import binding
+    binding.lib()
+    return binding
+
+
+def _fill_device(w, saw, skip, chunk=8192):
+    cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask)
+    pt = torch.from_numpy(w.page_table).cuda()
+    for b in range(w.batch):
+        if b in skip:
+            continue
+        L = int(w.seq_lens[b])
+        for p0 in range(0, L, chunk):
+            p1 = min(L, p0 + chunk)
+            K, V = synth.gen_kv(w, b, p0, p1, device="cuda")
+            saw.rotate_quant_store(cache, K, V, pt, torch.from_numpy(synth.slots_for(b, p0, p1)).cuda())
+    torch.cuda.synchronize()
+    return cache, pt
+
+
+def _pages_of(w, seqs):
+    P = w.page_size
+    return np.concatenate([w.page_table[b, :(int(w.seq_lens[b]) + P - 1) // P] for b in seqs])
+
+
+def _sample(w, n):
+    order = np.argsort(w.seq_lens, kind="stable")
+    picks = {int(order[0]), int(order[-1])}                       # shortest and longest always
+    rng = np.random.default_rng(w.seed + 77)
+    while len(picks) < min(n, w.batch):
+        picks.add(int(rng.integers(0, w.batch)))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("name,n_sample,out_dtype", [
+    ("highconc", 6, torch.bfloat16),      # the headline configuration: 256 ragged sequences, bf16 in and out
+    ("highconc", 6, torch.float32),
+    ("llama8b", 3, torch.float32),
+    ("longctx4", 1, torch.float32),
+    ("longctx1", 1, torch.float32),
+])
+def test_decode_full_size_sampled(saw, name, n_sample, out_dtype):
+    w = synth.make_workload(name)
+    seqs = _sample(w, n_sample)
+    print(f"[{name}] B={w.batch} tokens={w.total_tokens} sampled sequences {seqs}", flush=True)
+    ref = gc.oracle_fill(w, chunk=8192, seqs=seqs)
+    cache, pt = _fill_device(w, saw, skip=set(seqs))
+    gc.upload_cache(ref, w, saw, into=cache, pages=_pages_of(w, seqs))
+    q = synth.gen_q(w)
+    sl = torch.from_numpy(w.seq_lens).cuda()
+    o = saw.paged_decode_attn(cache, q.cuda(), pt, sl, max_seq_len=int(w.seq_lens.max()), out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    # the path has no atomics and a fixed reduction order: repeated launches agree bit for bit
+    for _ in range(3):
+        again = saw.paged_decode_attn(cache, q.cuda(), pt, sl, max_seq_len=int(w.seq_lens.max()), out_dtype=out_dtype)
+        assert torch.equal(o, again), f"{name}: repeated launches differ"
+    o = o.float().cpu().numpy()
+    assert np.isfinite(o).all()
+    plan = saw.decode_plan(cache, w.batch, int(w.seq_lens.max()))
+    # sampled sequences against the oracle, one by one
+    worst = 0.0
+    for b in seqs:
+        o_ref = O.paged_decode_attn(ref, q[b:b + 1].float().numpy(), w.page_table[b:b + 1], w.seq_lens[b:b + 1],
+                                    w.had_block, w.rotate_mask)
+        err = parity.attn_error(o[b:b + 1], o_ref)
+        worst = max(worst, err)
+        print(f"  seq {b} len {int(w.seq_lens[b])}: err={err:.2e}", flush=True)
+    tol = TOL if out_dtype == torch.float32 else TOL + 2.0 ** -8
+    assert worst < tol, f"{name}: plan={plan} worst sampled error {worst:.2e}"
+    # every sequence: the output is a convex combination of dequantised V rows (un-rotated by an
+    # orthonormal matrix), so its norm cannot exceed the largest row norm; sqrt(d) * max|s (c - z)| <=
+    # sqrt(d) * 15 * max scale bounds that without dequantising the cache.
+    vmax = float(cache.v_meta[..., 0].abs().max()) * 15.0 * np.sqrt(w.head_dim)
+    assert np.linalg.norm(o, axis=-1).max() <= vmax * 1.01
+    nonempty = w.seq_lens > 0
+    assert (np.abs(o[nonempty]).max(axis=(1, 2)) > 0).all()
+
+
+@pytest.mark.parametrize("name", ["prefill", "prefill_mha"])
+def test_store_full_size(saw, name):
+    """32k-token prefill store, every vector compared with the oracle (bit-exact codes up to the boundary rule)."""
+    w = synth.make_workload(name)
+    cache, ref, recs, _ = gc.fill_caches(w, saw, chunk=32768)
+    res = gc.compare_store(gc.cache_to_numpy(cache, w), ref, recs)
+    print(f"[{name}] {res}", flush=True)
+    parity.assert_store_ok(res)
