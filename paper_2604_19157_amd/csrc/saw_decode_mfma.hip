@@ -189,6 +189,65 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   wave_sync();
 }
 
+// Which (sequence, kv head) this block works on when the launch is one block per item and all
+// blocks are resident at once (8 per compute unit).  The hardware hands block `lin` to compute
+// unit lin % 256 (measured: blocks go round-robin over the 8 dies, then over a die's 32 units), so
+// with the identity mapping a unit gets 8 random items and the launch ends with the unluckiest
+// unit.  Here block `lin` takes the item at position `lin` of the longest-first order instead, so
+// every unit gets one item out of each eighth of the length distribution.  (Dealing the rounds
+// out in alternating directions, which equalises the units' token totals exactly, measured
+// slower: 165 us against 159 us on the 256-sequence ragged batch, 177 us with the identity.)
+// The rank is by (64 length classes, sequence index): a histogram in LDS, a prefix sum across
+// lanes and two ballots; every block derives the same bijection from the same seq_lens.
+template <int NW>
+__device__ __forceinline__ void balanced_item(const DecodeParams& p, int B, int lane, int wave, int& b, int& kvh) {
+  __shared__ int hist_all[NW][64];
+  int* const hist = hist_all[wave];
+  const int srank = b;                                     // rank of the sequence this block takes; kvh stays
+  const float kscale = 63.0f / (float)((p.bound + 63) >> 6);
+  const int V = (B + 63) >> 6;
+  hist[lane] = 0;
+  wave_sync();
+  for (int v = 0; v < V; ++v) {
+    const int idx = 64 * v + lane;
+    if (idx < B) {
+      const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
+      atomicAdd(&hist[63 - (int)((float)max(nb, 0) * kscale)], 1);     // class 0 = longest
+    }
+  }
+  wave_sync();
+  const int cnt = hist[lane];
+  int incl = cnt;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += t;
+  }
+  const int start = incl - cnt;
+  const unsigned long long hit = __ballot(srank >= start && srank < incl);     // exactly one class
+  const int cls = __ffsll((long long)hit) - 1;
+  int o = srank - __builtin_amdgcn_readlane(start, cls);                      // index inside the class
+  int found = 0;
+  for (int v = 0; v < V; ++v) {
+    const int idx = 64 * v + lane;
+    bool in = false;
+    if (idx < B) {
+      const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
+      in = (63 - (int)((float)max(nb, 0) * kscale)) == cls;
+    }
+    const unsigned long long mask = __ballot(in);
+    const int c = __popcll(mask);
+    if (o < c) {
+      const int myrank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+      const unsigned long long me = __ballot(in && myrank == o);
+      found = 64 * v + __ffsll((long long)me) - 1;
+      break;
+    }
+    o -= c;
+  }
+  b = __builtin_amdgcn_readfirstlane(found);
+}
+
 constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes;   // per wavefront: K buffer, two V buffers, P buffer
 
 // NW wavefronts share one (sequence, kv head, partition): wavefront w takes batches w, w + NW, ...
@@ -200,9 +259,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
   constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
   constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int split = blockIdx.x;
+  int kvh = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (p.balance) balanced_item<NW>(p, gridDim.z, lane, wave, b, kvh);
   const int t_begin = split * p.chunk_tokens;
   const int64_t pt_row = (int64_t)b * p.max_pages;
   // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page

@@ -30,7 +30,9 @@ def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_
         q = q.to(q_dtype)
     sl = torch.from_numpy(w.seq_lens).cuda()
     kw = dict(max_seq_len=int(w.seq_lens.max()), sm_scale=sm_scale, out_dtype=out_dtype, num_splits=num_splits)
-    o = saw.paged_decode_attn(cache, q.cuda(), pt, sl, **kw)
+    # the output starts as NaN: a row the path never writes fails the comparison
+    o = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
+    saw.paged_decode_attn(cache, q.cuda(), pt, sl, out=o, **kw)
     torch.cuda.synchronize()
     o = o.float().cpu().numpy()
     qn = q.float().numpy()
@@ -80,6 +82,20 @@ def test_ragged_lengths_with_empty_and_single(saw):
     w = synth.make_workload("highconc", batch=7, seq_lens=[0, 1, 15, 16, 17, 64, 333])
     o, _ = _decode_case(saw, w, num_splits=2)
     assert not o[0].any()                                           # empty sequence -> zero row
+
+
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2)])
+def test_many_sequences_balanced_item_order(saw, B, Hkv):
+    """More (sequence, kv head) items than compute units: the kernel deals items out longest first.
+    Every sequence is compared, so an item served twice or never shows up; lengths include empty
+    sequences and many ties."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(0, 330, size=B)
+    lens[rng.integers(0, B, size=B // 5)] = 64                      # ties
+    lens[:3] = [0, 329, 1]
+    w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv)
+    _decode_case(saw, w, num_splits=1, end_to_end=False)
+    _decode_case(saw, w, num_splits=0, end_to_end=False)
 
 
 def test_long_context_many_splits(saw):

@@ -72,7 +72,8 @@ def test_decode_full_size_sampled(saw, name, n_sample, out_dtype):
     gc.upload_cache(ref, w, saw, into=cache, pages=_pages_of(w, seqs))
     q = synth.gen_q(w)
     sl = torch.from_numpy(w.seq_lens).cuda()
-    o = saw.paged_decode_attn(cache, q.cuda(), pt, sl, max_seq_len=int(w.seq_lens.max()), out_dtype=out_dtype)
+    o = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
+    saw.paged_decode_attn(cache, q.cuda(), pt, sl, max_seq_len=int(w.seq_lens.max()), out=o)   # every row written
     torch.cuda.synchronize()
     # the path has no atomics and a fixed reduction order: repeated launches agree bit for bit
     for _ in range(3):
