@@ -20,7 +20,8 @@ struct DecodeParams {
   int32_t n_q_heads, n_kv_heads, max_pages, num_pages;
   int32_t had_block, rot_k, rot_v;
   int32_t num_splits, chunk_tokens, bound;
-  int32_t balance;          // d = 128 path: blocks pick their item in balanced longest-first order
+  int32_t pair;             // d = 128 path: two-wavefront blocks over (long, short) sequence pairs
+  int32_t batch;
   int32_t waves_per_item;   // d = 128 path: wavefronts sharing one partition (1, 2 or 4)
 };
 

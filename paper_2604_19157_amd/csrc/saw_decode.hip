@@ -477,10 +477,11 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.chunk_tokens = plan.chunk_tokens;
   p.bound = plan.bound;
   p.waves_per_item = plan.waves_per_item;
-  // one block per (sequence, kv head), more than one round per compute unit, class histogram of
-  // at most 16 lengths per lane
-  p.balance = !kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
-              (int64_t)B * c->n_kv_heads > 256 && B <= 1024;
+  // Pair mode: one partition per sequence, enough (sequence, kv head) items that every compute
+  // unit gets several, and at most 16 lengths per lane for the in-kernel ranking.
+  p.batch = B;
+  p.pair = !kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
+           (int64_t)B * c->n_kv_heads > 256 && B <= 1024;
   return launch_decode(p, B, c->head_dim, Hq / c->n_kv_heads, kv16, kv_dtype, st);
 }
 

@@ -189,52 +189,49 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   wave_sync();
 }
 
-// Which (sequence, kv head) this block works on when the launch is one block per item and all
-// blocks are resident at once (8 per compute unit).  The hardware hands block `lin` to compute
-// unit lin % 256 (measured: blocks go round-robin over the 8 dies, then over a die's 32 units), so
-// with the identity mapping a unit gets 8 random items and the launch ends with the unluckiest
-// unit.  Here block `lin` takes the item at position `lin` of the longest-first order instead, so
-// every unit gets one item out of each eighth of the length distribution.  (Dealing the rounds
-// out in alternating directions, which equalises the units' token totals exactly, measured
-// slower: 165 us against 159 us on the 256-sequence ragged batch, 177 us with the identity.)
-// The rank is by (64 length classes, sequence index): a histogram in LDS, a prefix sum across
-// lanes and two ballots; every block derives the same bijection from the same seq_lens.
-template <int NW>
-__device__ __forceinline__ void balanced_item(const DecodeParams& p, int B, int lane, int wave, int& b, int& kvh) {
-  __shared__ int hist_all[NW][64];
-  int* const hist = hist_all[wave];
-  const int srank = b;                                     // rank of the sequence this block takes; kvh stays
-  const float kscale = 63.0f / (float)((p.bound + 63) >> 6);
-  const int V = (B + 63) >> 6;
+// Longest-first order of the batch's sequences, derived by every block from the same seq_lens:
+// rank by (64 length classes, sequence index).  `build` makes the class histogram in LDS and
+// its prefix sums across lanes (lane c owns class c, class 0 = longest); `seq_of_rank` finds
+// the sequence at a rank with two ballots per 64 sequences.
+struct LenClasses {
+  int cnt, start, incl;      // this lane's class: members, ranks [start, incl)
+  float kscale;
+  int V;                     // ceil(B / 64)
+};
+__device__ __forceinline__ int len_class(const DecodeParams& p, int idx, float kscale) {
+  const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
+  return 63 - (int)((float)max(nb, 0) * kscale);
+}
+__device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* hist) {
+  LenClasses lc;
+  lc.kscale = 63.0f / (float)((p.bound + 63) >> 6);
+  lc.V = (B + 63) >> 6;
   hist[lane] = 0;
   wave_sync();
-  for (int v = 0; v < V; ++v) {
+  for (int v = 0; v < lc.V; ++v) {
     const int idx = 64 * v + lane;
-    if (idx < B) {
-      const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
-      atomicAdd(&hist[63 - (int)((float)max(nb, 0) * kscale)], 1);     // class 0 = longest
-    }
+    if (idx < B) atomicAdd(&hist[len_class(p, idx, lc.kscale)], 1);
   }
   wave_sync();
-  const int cnt = hist[lane];
-  int incl = cnt;
+  lc.cnt = hist[lane];
+  int incl = lc.cnt;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int t = __shfl_up(incl, off, 64);
     if (lane >= off) incl += t;
   }
-  const int start = incl - cnt;
-  const unsigned long long hit = __ballot(srank >= start && srank < incl);     // exactly one class
+  lc.incl = incl;
+  lc.start = incl - lc.cnt;
+  return lc;
+}
+__device__ __forceinline__ int seq_of_rank(const DecodeParams& p, int B, int lane, const LenClasses& lc, int srank) {
+  const unsigned long long hit = __ballot(srank >= lc.start && srank < lc.incl);   // exactly one class
   const int cls = __ffsll((long long)hit) - 1;
-  int o = srank - __builtin_amdgcn_readlane(start, cls);                      // index inside the class
+  int o = srank - __builtin_amdgcn_readlane(lc.start, cls);                        // index inside the class
   int found = 0;
-  for (int v = 0; v < V; ++v) {
+  for (int v = 0; v < lc.V; ++v) {
     const int idx = 64 * v + lane;
-    bool in = false;
-    if (idx < B) {
-      const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
-      in = (63 - (int)((float)max(nb, 0) * kscale)) == cls;
-    }
+    const bool in = idx < B && len_class(p, idx, lc.kscale) == cls;
     const unsigned long long mask = __ballot(in);
     const int c = __popcll(mask);
     if (o < c) {
@@ -245,26 +242,124 @@ __device__ __forceinline__ void balanced_item(const DecodeParams& p, int B, int 
     }
     o -= c;
   }
-  b = __builtin_amdgcn_readfirstlane(found);
+  return __builtin_amdgcn_readfirstlane(found);
 }
 
-constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes;   // per wavefront: K buffer, two V buffers, P buffer
+constexpr int kMetaBytes = 1024;              // one batch's (scale, zero) pairs: K 4 pages x 128 B, then V
+constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes + 2 * kMetaBytes;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
 
-// NW wavefronts share one (sequence, kv head, partition): wavefront w takes batches w, w + NW, ...
-// and the block folds their running (max, sum, accumulator) states together in LDS at the end.
-template <int G, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(3, 3)))
+// Two ways of giving wavefronts their work.
+//
+// PAIR = false: NW wavefronts share one (sequence, kv head, partition): wavefront w takes batches
+// w, w + NW, ... and the block folds their running (max, sum, accumulator) states together in LDS
+// at the end; with several partitions the result goes to the workspace for the merge kernel.
+//
+// PAIR = true (one partition per sequence, batch too large for every wavefront to need help):
+// a block of two wavefronts owns the sequences at ranks r and B-1-r of the longest-first order
+// and splits their batches evenly: wavefront 0 takes the first half of the total from the long
+// sequence, wavefront 1 the rest of the long sequence and then the whole short one.  Wavefront 1
+// leaves its share of the long sequence as a (max, sum, accumulator) record in LDS and raises a
+// flag; wavefront 0 picks it up when it is done (the only wait, and wavefront 1 never waits for
+// anybody).  Every wavefront of the launch then streams the same number of tokens (give or take
+// a batch) however ragged the batch is, with no partial results in global memory; with equal
+// lengths it degenerates to one wavefront per sequence.
+enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegProduce = 2, kSegMerge = 3 };
+
+template <int G, int NW, bool PAIR>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(PAIR ? 2 : 3, PAIR ? 2 : 3)))
 void decode_int4_mfma_kernel(DecodeParams p) {
+  static_assert(!PAIR || NW == 2, "a pair block has two wavefronts");
   constexpr int D = 128;
   constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
   constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
   constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
+  constexpr int STEP = PAIR ? 1 : NW;          // batch stride of a wavefront inside its range
   const int split = blockIdx.x;
-  int kvh = blockIdx.y, b = blockIdx.z;
+  const int kvh = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (p.balance) balanced_item<NW>(p, gridDim.z, lane, wave, b, kvh);
-  const int t_begin = split * p.chunk_tokens;
+  const int first_batch = PAIR ? 0 : wave;     // first batch of this wavefront inside its range
+
+  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds];
+  uint8_t* const kbuf = lds_all + wave * kWaveLds;
+  uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
+  uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
+  uint8_t* const pbuf = kbuf + 12 * kTileBytes;
+  uint8_t* const mbuf_a = pbuf + kPbufBytes;   // metadata of the batch in vbuf_a / vbuf_b
+  uint8_t* const mbuf_b = mbuf_a + kMetaBytes;
+  // PAIR: wavefront 1's record of its share of the long sequence, [G][m, l, acc[128]], and its flag
+  __shared__ float xch[PAIR ? G * (D + 2) : 1];
+  __shared__ int xch_ready;
+
+  // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
+  int nseg = 1;
+  int sg_b[2] = {(int)blockIdx.z, 0}, sg_t0[2] = {split * p.chunk_tokens, 0}, sg_t1[2] = {0, 0};
+  int sg_mode[2] = {kSegSplitKV, kSegAlone};
+  if (PAIR) {
+    const int B = p.batch;
+    if (threadIdx.x == 0) xch_ready = 0;
+    __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
+    const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
+    const int r_long = blockIdx.z, r_short = B - 1 - r_long;
+    const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
+    const int b_long = seq_of_rank(p, B, lane, lc, r_long);
+    const int b_short = self ? b_long : seq_of_rank(p, B, lane, lc, r_short);
+    const int l_long = max(min(p.seq_lens[b_long], p.bound), 0);
+    const int l_short = self ? 0 : max(min(p.seq_lens[b_short], p.bound), 0);
+    const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
+    // wavefront 1 pays a second prologue when the long sequence is shared: one batch in its favour
+    const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
+    nseg = 0;
+    if (wave == 0) {
+      if (nb_long == 0) {                               // empty sequence: zero output row
+        for (int i = lane; i < G * D; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * D + i, 0.f);
+      } else {
+        sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut);
+        sg_mode[0] = cut < nb_long ? kSegMerge : kSegAlone;
+        nseg = 1;
+      }
+    } else {
+      if (cut < nb_long) {
+        sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_mode[0] = kSegProduce;
+        nseg = 1;
+      }
+      if (nb_short > 0) {
+        if (nseg == 0) { sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_mode[0] = kSegAlone; }
+        else           { sg_b[1] = b_short; sg_t0[1] = 0; sg_t1[1] = l_short; sg_mode[1] = kSegAlone; }
+        ++nseg;
+      } else if (!self) {
+        for (int i = lane; i < G * D; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * D + i, 0.f);
+      }
+    }
+    wave_sync();                                        // the histogram lived in kbuf
+  }
+
+  const int row16 = lane & 15, grp = lane >> 4;
+  const int64_t head_tile = (int64_t)kvh * kTileBytes;
+  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
+  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
+  const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
+  // lane l fills LDS chunk l of a tile = token t = l/4, stored quarter (l & 3) = (Q + t/4) & 3
+  const int g_swz = 64 * (lane >> 2) + 16 * (((lane & 3) - (lane >> 4)) & 3);
+  const uint32_t kbias = bf16_bias();
+  // ---- per-lane constants ----
+  const int kr_off = 16 * (4 * row16 + ((grp + (row16 >> 2)) & 3));                 // K read: t = row16, Q = grp
+  int vr_off[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+    vr_off[c] = grp * kTileBytes + 16 * (4 * row16 + (((c >> 1) + (row16 >> 2)) & 3)) + 8 * (c & 1);
+  // P write column inside the batch: 16*page + 8*(t/8) + perm^-1(t%8),  perm^-1(u) = (u&3)<<1 | u>>2
+  const int pcol_t = (row16 & 8) + (((row16 & 3) << 1) | ((row16 >> 2) & 1));
+  const int head0 = (G > 4) ? 4 * (grp & 1) : 0;                                    // first head of this lane
+  const uint32_t pa_addr = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)pbuf + (row16 * kProw + 16 * grp) * 2;   // LDS byte address
+
+#pragma unroll 1
+  for (int seg = 0; seg < nseg; ++seg) {
+  const int b = seg == 0 ? sg_b[0] : sg_b[1];
+  const int t_begin = seg == 0 ? sg_t0[0] : sg_t0[1];
+  const int mode = seg == 0 ? sg_mode[0] : sg_mode[1];
   const int64_t pt_row = (int64_t)b * p.max_pages;
   // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page
   // pg_first + 64*window + l, i.e. one vector load covers a window of 16 batches; `pidv_nx` is
@@ -278,13 +373,18 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   int pidv, pidv_nx;                 // pidv_nx stays unclamped until it becomes pidv
   int window = 0;                    // 16-batch window pidv covers
   SAW_LOAD_PIDS(pidv, pg_first)
-  const int L = min(p.seq_lens[b], p.bound);
-  const int t_end = min(L, t_begin + p.chunk_tokens);
-  if (t_begin >= t_end) {            // block-uniform
-    if (p.num_splits == 1)           // empty sequence and no merge pass: the output row is zero
-      for (int i = threadIdx.x; i < G * 128; i += 64 * NW)
-        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
-    return;
+  int t_end;
+  if (PAIR) {
+    t_end = seg == 0 ? sg_t1[0] : sg_t1[1];
+  } else {
+    const int L = min(p.seq_lens[b], p.bound);
+    t_end = min(L, t_begin + p.chunk_tokens);
+    if (t_begin >= t_end) {            // block-uniform
+      if (p.num_splits == 1)           // empty sequence and no merge pass: the output row is zero
+        for (int i = threadIdx.x; i < G * 128; i += 64 * NW)
+          store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
+      return;
+    }
   }
   SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
   pidv = SAW_CLAMP_PID(pidv);
@@ -301,24 +401,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   }
 
-  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds];
-  uint8_t* const kbuf = lds_all + wave * kWaveLds;
-  uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
-  uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
-  uint8_t* const pbuf = kbuf + 12 * kTileBytes;
-
-  const int row16 = lane & 15, grp = lane >> 4;
-  const int64_t head_tile = (int64_t)kvh * kTileBytes;
-  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
-  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
-  const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
   const int nb = (t_end - t_begin + 63) >> 6;                     // batches of the partition
-  const int my_last = nb - 1 - ((nb - 1 - wave) % NW + NW) % NW;  // last batch of this wavefront (< wave if none)
+  // last batch of this wavefront (below first_batch if it has none)
+  const int my_last = nb - 1 - ((nb - 1 - first_batch) % STEP + STEP) % STEP;
 
   // ---- fetch: LDS-DMA for the code tiles, registers for this lane's token metadata ----
-  // lane l fills LDS chunk l of a tile = token t = l/4, stored quarter (l & 3) = (Q + t/4) & 3
-  const int g_swz = 64 * (lane >> 2) + 16 * (((lane & 3) - (lane >> 4)) & 3);
-  f32x2 kmeta[NS], vmeta[NS];
 #define SAW_ROTATE_PIDS(batch)                                                                  \
   if (((batch) >> 4) != window) {                                                               \
     window = (batch) >> 4;                                                                      \
@@ -328,22 +415,21 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #define SAW_PID(batch, q) __builtin_amdgcn_readlane(pidv, 4 * ((batch) & 15) + (q))
 #define SAW_DMA(gptr, ldsptr)                                                                   \
   __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(gptr), (LDS_AS void*)(ldsptr), 16, 0, 0)
-  // V tiles of `batch` into VDST, plus the metadata of this lane's token(s)
-#define SAW_FETCH_V(batch, VDST)                                                                \
+  // V tiles of `batch` into VDST and the batch's metadata into MDST: lanes 0-31 bring the K
+  // (scale, zero) pairs, lanes 32-63 the V pairs, 16 bytes (two tokens) each, so the metadata
+  // also goes HBM -> LDS and no register is the target of a load that is still in flight
+#define SAW_FETCH_V(batch, VDST, MDST)                                                          \
   {                                                                                             \
     SAW_ROTATE_PIDS(batch)                                                                      \
     _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
       const uint8_t* vp = p.v_codes + (int64_t)SAW_PID(batch, q) * page_stride + head_tile;     \
       SAW_DMA(vp + g_swz, VDST + q * kTileBytes);                                               \
     }                                                                                           \
-    _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                            \
-      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp; /* page of this lane's token */     \
-      const int id = pg == 0 ? SAW_PID(batch, 0) : pg == 1 ? SAW_PID(batch, 1)                  \
-                   : pg == 2 ? SAW_PID(batch, 2) : SAW_PID(batch, 3);                           \
-      const int64_t moff = (int64_t)id * page_meta + head_meta + row16 * 2;                     \
-      kmeta[s] = *(const f32x2*)(p.k_meta + moff);                                              \
-      vmeta[s] = *(const f32x2*)(p.v_meta + moff);                                              \
-    }                                                                                           \
+    const int mq = (lane >> 3) & 3;                                                             \
+    const int id = mq == 0 ? SAW_PID(batch, 0) : mq == 1 ? SAW_PID(batch, 1)                    \
+                 : mq == 2 ? SAW_PID(batch, 2) : SAW_PID(batch, 3);                             \
+    const float* mp = (lane < 32 ? p.k_meta : p.v_meta) + (int64_t)id * page_meta + head_meta + 4 * (lane & 7); \
+    SAW_DMA(mp, MDST);                                                                          \
   }
   // K tiles of `batch` into KDST (the ids were rotated by the V fetch of the same batch)
 #define SAW_FETCH_K(batch, KDST)                                                                \
@@ -374,22 +460,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   }
   {
     // issued unconditionally: a wavefront without a batch of its own shadows the last batch
-    const int first = min(wave, nb - 1);
-    SAW_FETCH_V(first, vbuf_a)
+    const int first = min(first_batch, nb - 1);
+    SAW_FETCH_V(first, vbuf_a, mbuf_a)
     SAW_FETCH_K(first, kbuf)
   }
-  const uint32_t kbias = bf16_bias();
-
-  // ---- per-lane constants ----
-  const int kr_off = 16 * (4 * row16 + ((grp + (row16 >> 2)) & 3));                 // K read: t = row16, Q = grp
-  int vr_off[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c)
-    vr_off[c] = grp * kTileBytes + 16 * (4 * row16 + (((c >> 1) + (row16 >> 2)) & 3)) + 8 * (c & 1);
-  // P write column inside the batch: 16*page + 8*(t/8) + perm^-1(t%8),  perm^-1(u) = (u&3)<<1 | u>>2
-  const int pcol_t = (row16 & 8) + (((row16 & 3) << 1) | ((row16 >> 2) & 1));
-  const int head0 = (G > 4) ? 4 * (grp & 1) : 0;                                    // first head of this lane
-  const uint32_t pa_addr = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)pbuf + (row16 * kProw + 16 * grp) * 2;   // LDS byte address
 
   f32x4 oacc[8];
 #pragma unroll
@@ -405,13 +479,18 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // does not drain the prefetch before reading a buffer no transfer is writing.  Correctness
   // does not rest on that analysis: the explicit vmcnt(0) below covers everything batch bi needs.
   auto body = [&](const int bi, uint8_t* __restrict__ const kb, uint8_t* __restrict__ const vcur,
-                  uint8_t* __restrict__ const vnext, uint8_t* __restrict__ const pb) {
+                  uint8_t* __restrict__ const vnext, uint8_t* __restrict__ const pb,
+                  uint8_t* __restrict__ const mcur, uint8_t* __restrict__ const mnext) {
     // (issued through the builtin, not inline asm, so that the compiler's wait-count pass sees it
     // and stops guarding earlier loads, e.g. the q~ operands, with waits of its own further down)
     __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): batch bi has landed (codes in LDS, metadata)
     f32x2 km[NS], vm[NS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) { km[s] = kmeta[s]; vm[s] = vmeta[s]; }
+    for (int s = 0; s < NS; ++s) {
+      const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;        // page of this lane's token
+      km[s] = *(const f32x2*)(mcur + 128 * pg + 8 * row16);
+      vm[s] = *(const f32x2*)(mcur + 512 + 128 * pg + 8 * row16);
+    }
     // K operand reads first, before the next transfers are issued.
     u32x4 kw[4];
 #pragma unroll
@@ -421,8 +500,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // which the caches absorb): a fetch under a branch would make the number of transfers in
     // flight path-dependent and force conservative vmcnt(0) waits further down.  vnext was last
     // read two batches ago.
-    const int nxt = min(bi + NW, my_last);
-    SAW_FETCH_V(nxt, vnext)
+    const int nxt = min(bi + STEP, my_last);
+    SAW_FETCH_V(nxt, vnext, mnext)
     SAW_FETCH_K(nxt, kb)
 
     // ---- logits: D_q[head][token of page q] ----
@@ -528,9 +607,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       oacc[c] = mfma_bf16(as_bf16x8(pa1), unpack8((uint32_t)tv.y, kbias), oacc[c]);
     }
   };
-  for (int bi = wave; bi < nb; bi += 2 * NW) {
-    body(bi, kbuf, vbuf_a, vbuf_b, pbuf);
-    if (bi + NW < nb) body(bi + NW, kbuf, vbuf_b, vbuf_a, pbuf);
+  for (int bi = first_batch; bi < nb; bi += 2 * STEP) {
+    body(bi, kbuf, vbuf_a, vbuf_b, pbuf, mbuf_a, mbuf_b);
+    if (bi + STEP < nb) body(bi + STEP, kbuf, vbuf_b, vbuf_a, pbuf, mbuf_b, mbuf_a);
   }
 
   // The last iteration re-fetched its own batch into kbuf and one of the V buffers.  Everything
@@ -539,7 +618,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
 
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
-  if (NW > 1) {
+  if (!PAIR && NW > 1) {
     float* const st = (float*)kbuf;                         // this wavefront's state: [j][lane]
     if (wave > 0) {
 #pragma unroll
@@ -573,7 +652,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   }
 
-  // ---- epilogue: reduce the per-lane sums, fold hi + lo rows, write the partial ----
+  // ---- epilogue: reduce the per-lane sums, fold hi + lo rows ----
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
     lsum[i] = row_allsum(lsum[i]);
@@ -590,40 +669,79 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   }
   constexpr int LOSHIFT = (G > 4) ? 32 : 16;     // lanes holding the lo rows sit this far above the hi rows
   const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
-  if (p.num_splits == 1) {
-    // The partition is the whole sequence: normalise, rotate back once for V, write the output.
-    float* const fb = (float*)vbuf_a;            // [G][128]; every read of the V buffers is done
-    wave_sync();
+  const int emode = PAIR ? mode : (p.num_splits == 1 ? (int)kSegAlone : (int)kSegSplitKV);
+  if (emode == kSegSplitKV) {
+    // one of several partitions: (max, sum, un-normalised accumulator) for the merge kernel
 #pragma unroll
     for (int i = 0; i < NH; ++i) {
-      const float inv = 1.0f / lsum[i];
+      const int head = head0 + i;
+      float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (D + 2);
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
-        if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = (o - zs[i]) * inv;
+        if (writer && i < G) dst[2 + 16 * c + row16] = o - zs[i];
       }
+      if (writer && row16 == 0 && i < G) { dst[0] = m_ref[i]; dst[1] = lsum[i]; }
     }
-    wave_sync();
-    float onorm = 1.0f;
-    if (p.rot_v) {
-      wave_lds_fwht128(fb, G, p.had_block, lane);
-      onorm = had_norm(p.had_block);
-    }
-    const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
-    for (int i = lane; i < G * D; i += 64) store_elem(p.out, p.out_dtype, obase + i, fb[i] * onorm);
     return;
   }
+  // The range's result as a record in LDS: acc[G][128] (un-normalised, zero-point term removed),
+  // then (max, sum) per head.  A producer writes it to the block's exchange area, everybody
+  // else to its own V buffers (every read of them is done; with G = 8 the (max, sum) pairs land
+  // at the start of the second buffer).
+  float* const fb = (emode == kSegProduce) ? xch : (float*)vbuf_a;
+  float* const ml = fb + G * D;
+  wave_sync();
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
-    const int head = head0 + i;
-    float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (D + 2);
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
-      if (writer && i < G) dst[2 + 16 * c + row16] = o - zs[i];
+      if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = o - zs[i];
     }
-    if (writer && row16 == 0 && i < G) { dst[0] = m_ref[i]; dst[1] = lsum[i]; }
+    if (writer && row16 == 0 && i < G) {
+      ml[2 * (head0 + i)] = m_ref[i];
+      ml[2 * (head0 + i) + 1] = lsum[i];
+    }
   }
+  if (emode == kSegProduce) {
+    // LDS operations of a wavefront complete in order: the record is in place before the flag
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_store(&xch_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    continue;
+  }
+  wave_sync();
+  if (emode == kSegMerge) {
+    // The other wavefront sets the flag without ever waiting for this one, so the wait ends.
+    while (__hip_atomic_load(&xch_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+      __builtin_amdgcn_s_sleep(8);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  }
+  // normalise (after adding the other wavefront's share of the same sequence, if there is one)
+  for (int idx = lane; idx < G * D; idx += 64) {
+    const int h = idx >> 7;
+    float l0 = ml[2 * h + 1];
+    float v = fb[idx];
+    if (emode == kSegMerge) {
+      const float m0 = ml[2 * h], m1 = xch[G * D + 2 * h], l1 = xch[G * D + 2 * h + 1];
+      const float mm = fmaxf(m0, m1);
+      const float a0 = fast_exp2(m0 - mm), a1 = fast_exp2(m1 - mm);
+      v = a0 * v + a1 * xch[idx];
+      l0 = a0 * l0 + a1 * l1;
+    }
+    fb[idx] = v / l0;
+  }
+  wave_sync();
+  // rotate back once for V (App. A.4), write the output
+  float onorm = 1.0f;
+  if (p.rot_v) {
+    wave_lds_fwht128(fb, G, p.had_block, lane);
+    onorm = had_norm(p.had_block);
+  }
+  const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
+  for (int i = lane; i < G * D; i += 64) store_elem(p.out, p.out_dtype, obase + i, fb[i] * onorm);
+  wave_sync();                                   // the next range's prologue reuses these buffers
+  }  // ranges of this wavefront
 }
 
 #undef SAW_FETCH_V
@@ -636,12 +754,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
 template <int G>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
-  if (nw >= 4) decode_int4_mfma_kernel<G, 4><<<grid, dim3(256), 0, st>>>(p);
-  else if (nw == 2) decode_int4_mfma_kernel<G, 2><<<grid, dim3(128), 0, st>>>(p);
-  else decode_int4_mfma_kernel<G, 1><<<grid, dim3(64), 0, st>>>(p);
+  if (p.pair) {
+    decode_int4_mfma_kernel<G, 2, true><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
+    return;
+  }
+  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false><<<grid, dim3(256), 0, st>>>(p);
+  else if (nw == 2) decode_int4_mfma_kernel<G, 2, false><<<grid, dim3(128), 0, st>>>(p);
+  else decode_int4_mfma_kernel<G, 1, false><<<grid, dim3(64), 0, st>>>(p);
 }
 
-// `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or 4.
+// `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or 4 (ignored in pair mode).
 int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st) {
   switch (G) {
     case 1: launch_g<1>(p, B, nw, grid, st); break;
