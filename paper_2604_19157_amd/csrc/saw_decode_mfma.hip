@@ -257,13 +257,13 @@ constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes + 2 * kMetaBytes;   // per
 // PAIR = true (one partition per sequence, batch too large for every wavefront to need help):
 // a block of two wavefronts owns the sequences at ranks r and B-1-r of the longest-first order
 // and splits their batches evenly: wavefront 0 takes the first half of the total from the long
-// sequence, wavefront 1 the rest of the long sequence and then the whole short one.  Wavefront 1
-// leaves its share of the long sequence as a (max, sum, accumulator) record in LDS and raises a
-// flag; wavefront 0 picks it up when it is done (the only wait, and wavefront 1 never waits for
-// anybody).  Every wavefront of the launch then streams the same number of tokens (give or take
-// a batch) however ragged the batch is, with no partial results in global memory; with equal
-// lengths it degenerates to one wavefront per sequence.
-enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegProduce = 2, kSegMerge = 3 };
+// sequence, wavefront 1 the whole short sequence and then the rest of the long one.  Each leaves
+// its share of the long sequence as a (max, sum, accumulator) record in its own LDS buffers and
+// counts itself in with an LDS atomic; whichever comes second combines the two records and writes
+// the output, so nobody waits for anybody.  Every wavefront of the launch then streams the same
+// number of tokens (give or take a batch) however ragged the batch is, with no partial results
+// in global memory; with equal lengths it degenerates to one wavefront per sequence.
+enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 
 template <int G, int NW, bool PAIR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(PAIR ? 2 : 3, PAIR ? 2 : 3)))
@@ -287,9 +287,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
   uint8_t* const mbuf_a = pbuf + kPbufBytes;   // metadata of the batch in vbuf_a / vbuf_b
   uint8_t* const mbuf_b = mbuf_a + kMetaBytes;
-  // PAIR: wavefront 1's record of its share of the long sequence, [G][m, l, acc[128]], and its flag
-  __shared__ float xch[PAIR ? G * (D + 2) : 1];
-  __shared__ int xch_ready;
+  __shared__ int shared_done;                  // PAIR: wavefronts that have left their record of the long sequence
 
   // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
   int nseg = 1;
@@ -297,7 +295,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   int sg_mode[2] = {kSegSplitKV, kSegAlone};
   if (PAIR) {
     const int B = p.batch;
-    if (threadIdx.x == 0) xch_ready = 0;
+    if (threadIdx.x == 0) shared_done = 0;
     __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     const int r_long = blockIdx.z, r_short = B - 1 - r_long;
@@ -309,6 +307,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
     // wavefront 1 pays a second prologue when the long sequence is shared: one batch in its favour
     const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
+    const bool shared = cut < nb_long;
     nseg = 0;
     if (wave == 0) {
       if (nb_long == 0) {                               // empty sequence: zero output row
@@ -316,21 +315,21 @@ void decode_int4_mfma_kernel(DecodeParams p) {
           store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * D + i, 0.f);
       } else {
         sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut);
-        sg_mode[0] = cut < nb_long ? kSegMerge : kSegAlone;
+        sg_mode[0] = shared ? kSegShare : kSegAlone;
         nseg = 1;
       }
     } else {
-      if (cut < nb_long) {
-        sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_mode[0] = kSegProduce;
-        nseg = 1;
-      }
       if (nb_short > 0) {
-        if (nseg == 0) { sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_mode[0] = kSegAlone; }
-        else           { sg_b[1] = b_short; sg_t0[1] = 0; sg_t1[1] = l_short; sg_mode[1] = kSegAlone; }
-        ++nseg;
+        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_mode[0] = kSegAlone;
+        nseg = 1;
       } else if (!self) {
         for (int i = lane; i < G * D; i += 64)
           store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * D + i, 0.f);
+      }
+      if (shared) {                                     // last, so that its record can stay in this wavefront's buffers
+        if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_mode[0] = kSegShare; }
+        else           { sg_b[1] = b_long; sg_t0[1] = 64 * cut; sg_t1[1] = l_long; sg_mode[1] = kSegShare; }
+        ++nseg;
       }
     }
     wave_sync();                                        // the histogram lived in kbuf
@@ -685,11 +684,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
     return;
   }
-  // The range's result as a record in LDS: acc[G][128] (un-normalised, zero-point term removed),
-  // then (max, sum) per head.  A producer writes it to the block's exchange area, everybody
-  // else to its own V buffers (every read of them is done; with G = 8 the (max, sum) pairs land
-  // at the start of the second buffer).
-  float* const fb = (emode == kSegProduce) ? xch : (float*)vbuf_a;
+  // The range's result as a record in this wavefront's V buffers (every read of them is done):
+  // acc[G][128] (un-normalised, zero-point term removed), then (max, sum) per head; with G = 8
+  // the pairs land at the start of the second buffer.
+  float* const fb = (float*)vbuf_a;
   float* const ml = fb + G * D;
   wave_sync();
 #pragma unroll
@@ -704,30 +702,34 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       ml[2 * (head0 + i) + 1] = lsum[i];
     }
   }
-  if (emode == kSegProduce) {
-    // LDS operations of a wavefront complete in order: the record is in place before the flag
+  const float* other = nullptr;                  // the other wavefront's record of the same sequence
+  if (PAIR && emode == kSegShare) {
+    // LDS operations of a wavefront complete in order, so the record is in place before the
+    // count; the wavefront that finds the other already counted does the rest for both.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if (lane == 0) __hip_atomic_store(&xch_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    continue;
+    int before = 0;
+    if (lane == 0) before = __hip_atomic_fetch_add(&shared_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before == 0) return;                     // a shared range is always the wavefront's last
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    other = (const float*)(lds_all + (1 - wave) * kWaveLds + 4 * kTileBytes);
   }
   wave_sync();
-  if (emode == kSegMerge) {
-    // The other wavefront sets the flag without ever waiting for this one, so the wait ends.
-    while (__hip_atomic_load(&xch_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
-      __builtin_amdgcn_s_sleep(8);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  }
-  // normalise (after adding the other wavefront's share of the same sequence, if there is one)
+  // normalise (after adding the other wavefront's share of the same sequence, if there is one;
+  // wavefront 0's record is always the first operand, so the result does not depend on which
+  // of the two happens to come second)
+  const float* const rec0 = (PAIR && other && wave == 1) ? other : fb;
+  const float* const rec1 = (PAIR && other && wave == 1) ? fb : other;
   for (int idx = lane; idx < G * D; idx += 64) {
     const int h = idx >> 7;
-    float l0 = ml[2 * h + 1];
-    float v = fb[idx];
-    if (emode == kSegMerge) {
-      const float m0 = ml[2 * h], m1 = xch[G * D + 2 * h], l1 = xch[G * D + 2 * h + 1];
+    float l0 = rec0[G * D + 2 * h + 1];
+    float v = rec0[idx];
+    if (PAIR && other) {
+      const float m0 = rec0[G * D + 2 * h], m1 = rec1[G * D + 2 * h], l1 = rec1[G * D + 2 * h + 1];
       const float mm = fmaxf(m0, m1);
       const float a0 = fast_exp2(m0 - mm), a1 = fast_exp2(m1 - mm);
-      v = a0 * v + a1 * xch[idx];
-      l0 = a0 * l0 + a1 * l1;
+      v = fmaf(a1, rec1[idx], a0 * v);
+      l0 = fmaf(a1, l1, a0 * l0);
     }
     fb[idx] = v / l0;
   }
