@@ -156,6 +156,40 @@ def store_sweep(saw, dev, iters=30, warmup=5):
     return out
 
 
+def flatten_sweep(saw, dev, iters=30, warmup=5):
+    """Flatten-dequantise of a 32768-token sequence into dense bf16 K and V: tokens/s per Hadamard
+    block size, rotated back (and, for comparison, left in the rotated space = plain dequantise)."""
+    out = {}
+    for name in ("prefill", "prefill_mha"):
+        res = {}
+        base = synth.make_workload(name)
+        T = int(base.seq_lens[0])
+        K, V = synth.gen_kv(base, 0, 0, T, device=dev)
+        pt = torch.from_numpy(base.page_table).to(dev)
+        sl = torch.from_numpy(synth.slots_for(0, 0, T)).to(dev)
+        shape = (T, base.n_kv_heads, base.head_dim)
+        ko = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        vo = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        nbytes = T * base.n_kv_heads * (2 * (base.head_dim // 2 + 8) + 2 * base.head_dim * 2)
+        for h in (1, 16, 32, 64, 128):
+            if h > base.head_dim:
+                res[f"h{h}"] = None
+                continue
+            cache = saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, 3, device=dev)
+            saw.rotate_quant_store(cache, K, V, pt, sl)
+            r = {}
+            for unrot in (True, False):
+                med, mean, p10, p90 = time_calls(lambda: saw.flatten_dequant(cache, pt, 0, 0, T, unrotate=unrot,
+                                                                             k_out=ko, v_out=vo), iters, warmup)
+                r["rotated_back" if unrot else "as_stored"] = {"us": round(med, 2), "Gtok_s": round(T / med / 1e3, 4),
+                                                               "GB_s": round(nbytes / med / 1e3, 1)}
+            r["rotation_cost"] = round(r["rotated_back"]["us"] / r["as_stored"]["us"], 4)
+            res[f"h{h}"] = r
+            del cache
+        out[name] = res
+    return out
+
+
 LLC_BYTES = 256 << 20        # memory-side cache of the chip: smaller working sets are rotated over copies
 
 
@@ -218,6 +252,8 @@ def main():
     ap.add_argument("--num-splits", type=int, default=0, help="split-KV factor (0 = the library's choice)")
     ap.add_argument("--store-sweep-only", action="store_true",
                     help="only run the prefill store sweep (32768-token chunk, every Hadamard block size) and print it")
+    ap.add_argument("--flatten-sweep-only", action="store_true",
+                    help="only run the flatten-dequantise sweep (32768 tokens, every Hadamard block size) and print it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -243,6 +279,10 @@ def main():
     saw.lib()
     if args.store_sweep_only:
         print(json.dumps({"prefill_store_sweep": store_sweep(saw, dev, iters=args.steps, warmup=args.warmup)}))
+        return
+
+    if args.flatten_sweep_only:
+        print(json.dumps({"prefill_flatten_sweep": flatten_sweep(saw, dev, iters=args.steps, warmup=args.warmup)}))
         return
 
     w = synth.make_workload(args.workload)
@@ -330,6 +370,7 @@ def main():
         del kv16, ws16
         torch.cuda.empty_cache()
         ex["prefill_store_sweep"] = store_sweep(saw, dev)
+        ex["prefill_flatten_sweep"] = flatten_sweep(saw, dev)
         del cache
         torch.cuda.empty_cache()
         ceiling = copy_ceiling(dev)

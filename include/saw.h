@@ -7,7 +7,8 @@
  *   2. saw_paged_decode_attn: one decode step o = softmax(q K^T / sqrt(d)) V read
  *      straight from the INT4 pages, with q rotated instead of un-rotating K and the
  *      output rotated back once for V.
- * plus saw_dequant_pages (read-back / flatten), and a 16-bit-KV paged decode
+ * plus saw_dequant_pages (fp32 read-back for inspection), saw_flatten_dequant (the
+ * prefill-side read-back into dense 16-bit buffers), and a 16-bit-KV paged decode
  * (saw_kv16_*) that serves as the same-run unquantised comparison.
  *
  * Conventions for every call
@@ -150,6 +151,26 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
 int saw_dequant_pages(const saw_cache_t* cache, const int32_t* page_table,
                       int32_t max_pages_per_seq, int32_t seq, int32_t pos_begin, int32_t pos_end,
                       int32_t unrotate, float* k_out, float* v_out, saw_stream_t stream);
+
+/*
+ * Flatten-dequantise (the flatten_dequant step of App. B's prefill breakdown; arithmetic of
+ * App. A.1 and A.4): positions [pos_begin, pos_end) of sequence `seq` are gathered from the
+ * INT4 pages into dense buffers for a prefill / chunked-prefill attention consumer,
+ * x^ = s (c - z), multiplied by H_blk once more when unrotate != 0 (tensors the cache holds
+ * rotated return to the original space; with unrotate == 0 they stay in the rotated space).
+ *
+ *   k_out, v_out  device, [pos_end - pos_begin][n_kv_heads][head_dim] of out_dtype
+ *                 (SAW_BF16 | SAW_F16 | SAW_F32), 16-byte aligned, token_stride_elems elements
+ *                 between tokens (>= n_kv_heads*head_dim, multiple of 8).  Either may be NULL.
+ *   Positions whose page-table entry is outside [0, num_pages) are left unwritten.
+ * pos_end == pos_begin is a no-op.  Errors: SAW_EINVAL for a bad range (negative, reversed,
+ * beyond max_pages_per_seq * page_size), dtype, stride or alignment; SAW_ENULL for a null
+ * cache / page table.
+ */
+int saw_flatten_dequant(const saw_cache_t* cache, const int32_t* page_table,
+                        int32_t max_pages_per_seq, int32_t seq, int32_t pos_begin, int32_t pos_end,
+                        int32_t unrotate, int32_t out_dtype, void* k_out, void* v_out,
+                        int64_t token_stride_elems, saw_stream_t stream);
 
 /*
  * 16-bit-KV comparison path (the unquantised cache the paper measures INT4 against):

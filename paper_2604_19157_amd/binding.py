@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
         L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.saw_flatten_dequant.argtypes = [cp, vp, i32, i32, i32, i32, i32, i32, vp, vp, ctypes.c_int64, vp]
         L.saw_kv16_store.argtypes = [cp, vp, vp, i32, vp, vp, i64, i64, vp, i32, i32, vp, vp]
         L.saw_kv16_paged_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32,
                                                  vp, i32, vp, sz, i32, vp]
@@ -152,6 +153,26 @@ def dequant_pages(cache: Cache, page_table, seq, pos_begin, pos_end, unrotate=Fa
     _check(lib().saw_dequant_pages(ctypes.byref(st), _ptr(page_table), page_table.shape[1], seq, pos_begin,
                                    pos_end, int(bool(unrotate)), _ptr(k), _ptr(v), _stream()), "saw_dequant_pages")
     return k, v
+
+
+def flatten_dequant(cache: Cache, page_table, seq, pos_begin, pos_end, unrotate=True, out_dtype=torch.bfloat16,
+                    want_k=True, want_v=True, k_out=None, v_out=None):
+    """saw_flatten_dequant: ``(K^, V^)`` each ``[n][Hkv][d]`` of out_dtype (None if not requested)."""
+    n = pos_end - pos_begin
+    dev = cache.k_codes.device
+    shape = (n, cache.n_kv_heads, cache.head_dim)
+    if want_k and k_out is None:
+        k_out = torch.empty(shape, dtype=out_dtype, device=dev)
+    if want_v and v_out is None:
+        v_out = torch.empty(shape, dtype=out_dtype, device=dev)
+    ref = k_out if k_out is not None else v_out
+    stride = ref.stride(0) if ref is not None and n > 0 else cache.n_kv_heads * cache.head_dim
+    dt = _DT[ref.dtype] if ref is not None else _DT[out_dtype]
+    st = cache.struct()
+    _check(lib().saw_flatten_dequant(ctypes.byref(st), _ptr(page_table), page_table.shape[1], seq, pos_begin,
+                                     pos_end, int(bool(unrotate)), dt, _ptr(k_out), _ptr(v_out), stride,
+                                     _stream()), "saw_flatten_dequant")
+    return k_out, v_out
 
 
 class Kv16Cache:

@@ -9,6 +9,8 @@ namespace saw {
 
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
                  int32_t, int32_t, const int32_t*, hipStream_t);
+int launch_flatten(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, void*, void*, int64_t,
+                   hipStream_t);
 int launch_dequant(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t,
                    float*, float*, hipStream_t);
 int launch_kv16_store(const saw_cache_t*, void*, void*, const void*, const void*, int64_t, int64_t,
@@ -182,6 +184,24 @@ int saw_dequant_pages(const saw_cache_t* c, const int32_t* page_table, int32_t m
   if ((k_out && !aligned16(k_out)) || (v_out && !aligned16(v_out))) return SAW_EINVAL;
   return launch_dequant(c, page_table, max_pages_per_seq, seq, pos_begin, pos_end, unrotate, k_out, v_out,
                         (hipStream_t)stream);
+}
+
+int saw_flatten_dequant(const saw_cache_t* c, const int32_t* page_table, int32_t max_pages_per_seq,
+                        int32_t seq, int32_t pos_begin, int32_t pos_end, int32_t unrotate,
+                        int32_t out_dtype, void* k_out, void* v_out, int64_t token_stride_elems,
+                        saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || !block_ok(c)) return SAW_EINVAL;
+  if (out_dtype != SAW_F16 && out_dtype != SAW_BF16 && out_dtype != SAW_F32) return SAW_EINVAL;
+  if (seq < 0 || pos_begin < 0 || pos_end < pos_begin || max_pages_per_seq < 1) return SAW_EINVAL;
+  if ((int64_t)pos_end > (int64_t)max_pages_per_seq * c->page_size) return SAW_EINVAL;
+  if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems % 8)) return SAW_EINVAL;
+  if (pos_end == pos_begin) return SAW_OK;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !page_table) return SAW_ENULL;
+  if (!k_out && !v_out) return SAW_OK;
+  if ((k_out && !aligned16(k_out)) || (v_out && !aligned16(v_out))) return SAW_EINVAL;
+  return launch_flatten(c, page_table + (int64_t)seq * max_pages_per_seq, pos_begin, pos_end, unrotate,
+                        out_dtype, k_out, v_out, token_stride_elems, (hipStream_t)stream);
 }
 
 int saw_kv16_store(const saw_cache_t* c, void* k_pages, void* v_pages, int32_t dtype, const void* K,

@@ -1,0 +1,197 @@
+// Flatten-dequantise: a range of one sequence's INT4 pages -> a dense [n][kv_heads][d] K and/or V
+// buffer in bf16 / fp16 / fp32, optionally rotated back (App. A.1: x^ = s (c - z); App. A.4:
+// the block-diagonal Hadamard is symmetric and orthonormal, so the same matrix undoes it).
+// This is the prefill-side consumer of the cache (App. B's flatten_dequant row): a chunked
+// prefill attends over earlier chunks through this buffer.
+//
+// One wavefront takes one page (16 tokens) of one (K|V, kv head):
+//   * the code tile (16 x d/2 bytes, contiguous) is read with coalesced 128-bit loads and passed
+//     through LDS once (XOR chunk swizzle, conflict-free both ways) into the MFMA operand
+//     layout, column = token;
+//   * the nibbles become bf16 values 128 + c with one and-or per pair (exact), and the
+//     Walsh-Hadamard transform over 32 contiguous channels is one pair of
+//     v_mfma_f32_16x16x32_bf16 with a +/-1 matrix (block-diagonal for h = 16, identity when
+//     nothing is to be rotated back), so every case runs the same instruction stream; orders
+//     64 / 128 add register-to-register butterflies;
+//   * everything up to here is exact integer arithmetic in fp32; the zero-point is taken out
+//     afterwards: H (c + 128 - (z + 128)) = H (c + 128) - (z + 128) H 1, and H 1 is h at the
+//     first channel of every block and 0 elsewhere, so a large zero-point cancels exactly
+//     instead of through rounding;
+//   * a lane ends up with eight contiguous output channels of one token for every 32-channel
+//     group: one 16-byte (bf16 / fp16) or two 16-byte (fp32) stores each.
+#include "saw_common.h"
+
+namespace saw {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct FlattenParams {
+  const uint8_t* codes[2];
+  const float* meta[2];
+  void* out[2];                 // null: tensor not wanted
+  const int32_t* page_table;    // row of the sequence
+  int64_t token_stride;         // output elements between tokens
+  int32_t pos_begin, pos_end;
+  int32_t first_page;           // pos_begin / 16
+  int32_t num_pages, n_kv_heads, had_block;
+  int32_t unrot[2];             // rotate this tensor back
+};
+
+template <int D, int ODT>
+__global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
+  constexpr int RB = D / 2;              // code bytes of one token's head vector (64 | 32)
+  constexpr int XC = RB / 16;            // 16-byte chunks per vector (4 | 2)
+  constexpr int NA = D / 32;             // 32-channel groups per vector (4 | 2)
+  constexpr int FSH = (D == 128) ? 2 : 3;  // swizzle: chunk x of token t sits at x ^ ((t >> FSH) & (XC-1))
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n16 = lane & 15, rg = lane >> 4;
+  const int kind = blockIdx.y * 4 + wave;                     // (K|V, head)
+  if (kind >= 2 * p.n_kv_heads) return;
+  const int which = kind >= p.n_kv_heads ? 1 : 0;
+  const int head = kind - which * p.n_kv_heads;
+  if (p.out[which] == nullptr) return;
+  const int lp = p.first_page + blockIdx.x;                   // logical page of the sequence
+  const int pid = p.page_table[lp];
+  if (pid < 0 || pid >= p.num_pages) return;                  // unmapped page: nothing written
+  const bool unrot = p.unrot[which] != 0;
+
+  __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][16 * RB];
+  uint8_t* const stage = stage_all[wave];
+
+  const uint8_t* tile = p.codes[which] + ((int64_t)pid * p.n_kv_heads + head) * (16 * RB);
+  const float* mrow = p.meta[which] + ((int64_t)pid * p.n_kv_heads + head) * 32;
+  if (lane < 16 * XC) {
+    const int tok = lane / XC, x = lane % XC;
+    const u32x4 v = *(const u32x4*)(tile + 16 * lane);
+    *(u32x4*)(stage + tok * RB + 16 * (x ^ ((tok >> FSH) & (XC - 1)))) = v;
+  }
+  const float2 sz = *(const float2*)(mrow + 2 * n16);         // (scale, zero) of this lane's token
+
+  // ---- the +/-1 matrix (see the store kernel): A[m][k], lane (m = n16, k-group = rg) ----
+  // k runs over the nibble order the unpack produces: (n0, n4, n1, n5, n2, n6, n3, n7).
+  const int hm = unrot ? min(p.had_block, 32) : 1;            // order handled inside the MFMA
+  u32x4 ha1, ha2;
+  {
+    const int lo1 = 8 * (n16 >> 2) + (n16 & 3), lo2 = lo1 + 4;
+    uint32_t e1[8], e2[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int cl = 8 * rg + ((j & 1) ? 4 + (j >> 1) : (j >> 1));
+      const bool on1 = (((lo1 ^ cl) & ~(hm - 1)) & 31) == 0;
+      const bool on2 = (((lo2 ^ cl) & ~(hm - 1)) & 31) == 0;
+      const uint32_t s1 = (__builtin_popcount(lo1 & cl & (hm - 1)) & 1) ? 0x8000u : 0u;
+      const uint32_t s2 = (__builtin_popcount(lo2 & cl & (hm - 1)) & 1) ? 0x8000u : 0u;
+      e1[j] = on1 ? (0x3F80u | s1) : 0u;
+      e2[j] = on2 ? (0x3F80u | s2) : 0u;
+    }
+    ha1 = u32x4{e1[0] | (e1[1] << 16), e1[2] | (e1[3] << 16), e1[4] | (e1[5] << 16), e1[6] | (e1[7] << 16)};
+    ha2 = u32x4{e2[0] | (e2[1] << 16), e2[2] | (e2[3] << 16), e2[4] | (e2[5] << 16), e2[6] | (e2[7] << 16)};
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  float y[8 * NA];                                             // y[8a + i]: channel 32a + 8rg + i of token n16
+#pragma unroll
+  for (int a = 0; a < NA; ++a) {
+    const uint32_t w = *(const uint32_t*)(stage + n16 * RB + 16 * (a ^ ((n16 >> FSH) & (XC - 1))) + 4 * rg);
+    u32x4 bv;                                                  // eight bf16 values 128 + c
+    bv.x = (w & 0x000F000Fu) | 0x43004300u;
+    bv.y = ((w >> 4) & 0x000F000Fu) | 0x43004300u;
+    bv.z = ((w >> 8) & 0x000F000Fu) | 0x43004300u;
+    bv.w = ((w >> 12) & 0x000F000Fu) | 0x43004300u;
+    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+    const f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ha1), __builtin_bit_cast(bf16x8, bv), zero, 0, 0, 0);
+    const f32x4 d2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ha2), __builtin_bit_cast(bf16x8, bv), zero, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { y[8 * a + i] = d1[i]; y[8 * a + 4 + i] = d2[i]; }
+  }
+  if (unrot && p.had_block >= 64) {
+#pragma unroll
+    for (int a = 0; a < NA; a += 2)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float u = y[8 * a + i], v = y[8 * a + 8 + i];
+        y[8 * a + i] = u + v;
+        y[8 * a + 8 + i] = u - v;
+      }
+  }
+  if (D == 128 && unrot && p.had_block >= 128) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float u = y[8 * a + i], v = y[8 * a + 16 + i];
+        y[8 * a + i] = u + v;
+        y[8 * a + 16 + i] = u - v;
+      }
+  }
+
+  // ---- zero-point and scale ----
+  // un-rotated read-back: every channel carries (z + 128); rotated back: only the first channel
+  // of each Hadamard block carries h (z + 128), the rest cancel exactly.
+  const int h = unrot ? p.had_block : 1;
+  const float zoff = (sz.y + 128.0f) * (float)h;
+  const float sc = sz.x * (unrot ? had_norm(p.had_block) : 1.0f);
+  const int pos = 16 * lp + n16;
+  if (pos < p.pos_begin || pos >= p.pos_end) return;
+  const int64_t obase = (int64_t)(pos - p.pos_begin) * p.token_stride + head * D;
+#pragma unroll
+  for (int a = 0; a < NA; ++a) {
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int ch = 32 * a + 8 * rg + i;
+      const bool carries = (ch & (h - 1)) == 0;
+      o[i] = sc * (carries ? y[8 * a + i] - zoff : y[8 * a + i]);
+    }
+    const int64_t e = obase + 32 * a + 8 * rg;
+    if (ODT == SAW_F32) {
+      float* dst = (float*)p.out[which] + e;
+      *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
+      *(f32x4*)(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+    } else {
+      uint32_t w4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = (ODT == SAW_BF16) ? f32_to_bf16(o[2 * i]) : f32_to_f16(o[2 * i]);
+        const uint32_t hi = (ODT == SAW_BF16) ? f32_to_bf16(o[2 * i + 1]) : f32_to_f16(o[2 * i + 1]);
+        w4[i] = lo | (hi << 16);
+      }
+      *(u32x4*)((uint16_t*)p.out[which] + e) = u32x4{w4[0], w4[1], w4[2], w4[3]};
+    }
+  }
+}
+
+int launch_flatten(const saw_cache_t* c, const int32_t* pt_row, int32_t pos_begin, int32_t pos_end,
+                   int32_t unrotate, int32_t out_dtype, void* k_out, void* v_out, int64_t token_stride,
+                   hipStream_t st) {
+  FlattenParams p;
+  p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
+  p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
+  p.out[0] = k_out;        p.out[1] = v_out;
+  p.page_table = pt_row;
+  p.token_stride = token_stride;
+  p.pos_begin = pos_begin; p.pos_end = pos_end;
+  p.first_page = pos_begin / 16;
+  p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads; p.had_block = c->had_block;
+  const bool rot = unrotate && c->had_block > 1;
+  p.unrot[0] = rot && (c->rotate_mask & SAW_ROT_K);
+  p.unrot[1] = rot && (c->rotate_mask & SAW_ROT_V);
+  const int n_pages = (pos_end + 15) / 16 - p.first_page;
+  dim3 grid(n_pages, (2 * c->n_kv_heads + 3) / 4), block(256);
+#define SAW_FLAT(DD)                                                                              \
+  switch (out_dtype) {                                                                            \
+    case SAW_BF16: flatten_dequant_kernel<DD, SAW_BF16><<<grid, block, 0, st>>>(p); break;         \
+    case SAW_F16: flatten_dequant_kernel<DD, SAW_F16><<<grid, block, 0, st>>>(p); break;           \
+    default: flatten_dequant_kernel<DD, SAW_F32><<<grid, block, 0, st>>>(p); break;                \
+  }
+  if (c->head_dim == 128) { SAW_FLAT(128) } else { SAW_FLAT(64) }
+#undef SAW_FLAT
+  return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
+}
+
+}  // namespace saw

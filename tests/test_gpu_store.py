@@ -121,8 +121,9 @@ def test_out_of_range_slots_are_skipped_and_strided_input(saw):
 @pytest.mark.parametrize("unrotate", [False, True])
 def test_dequant_pages(saw, name, kw, unrotate):
     w = synth.make_workload(name, **kw)
-    cache, _, _, pt = gc.fill_caches(w, saw, with_ref=False)
-    got = gc.cache_to_numpy(cache, w)
+    got = gc.oracle_fill(w)                               # both sides read the bytes the oracle's store wrote
+    cache = gc.upload_cache(got, w, saw)
+    pt = torch.from_numpy(w.page_table).cuda()
     for b in range(w.batch):
         L = int(w.seq_lens[b])
         for (p0, p1) in [(0, L), (5, min(L, 37)), (L - 1, L)]:
