@@ -296,13 +296,17 @@ def main():
     newK = torch.cat([synth.gen_kv(w, b, int(w.seq_lens[b]), int(w.seq_lens[b]) + 1, device=dev)[0] for b in range(B)])
     newV = torch.cat([synth.gen_kv(w, b, int(w.seq_lens[b]), int(w.seq_lens[b]) + 1, device=dev)[1] for b in range(B)])
     new_slots = torch.from_numpy(np.stack([np.arange(B, dtype=np.int32), w.seq_lens.astype(np.int32)], 1)).to(dev)
+    lens0 = w.seq_lens.astype(np.int32)
     lens1 = (w.seq_lens + 1).astype(np.int32)
+    seq_lens0 = torch.from_numpy(lens0).to(dev)
     seq_lens = torch.from_numpy(lens1).to(dev)
+    max_len0 = int(lens0.max())
     max_len = int(lens1.max())
     q = synth.gen_q(w, device=dev)
     out = torch.empty((B, w.n_q_heads, w.head_dim), dtype=torch.float32, device=dev)
     ws = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len, args.num_splits), dtype=torch.uint8, device=dev)
     splits, chunk = saw.decode_plan(cache, B, max_len, args.num_splits)
+    fused = args.num_splits == 0
 
     def store_step():
         saw.rotate_quant_store(cache, newK, newV, pt, new_slots)
@@ -310,17 +314,32 @@ def main():
     def decode_step():
         saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws, num_splits=args.num_splits)
 
+    def fused_step():
+        # one call (one kernel launch for this workload): append the step's tokens and attend over all of them
+        saw.append_decode_attn(cache, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0, out=out, workspace=ws)
+
+    def step():
+        if fused:
+            fused_step()
+        else:
+            store_step()
+            decode_step()
+
     for _ in range(args.warmup):
-        store_step()
-        decode_step()
+        step()
     torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for a, b in ev:
-        store_step()
-        a.record()
-        decode_step()
-        b.record()
+        if fused:
+            a.record()
+            fused_step()
+            b.record()
+        else:
+            store_step()
+            a.record()
+            decode_step()
+            b.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -330,7 +349,8 @@ def main():
     dbytes = decode_bytes(w, lens1)
     sbytes = store_bytes(w, B)
     value = (dbytes + sbytes) / (ms_per_step * 1e-3) / 1e9
-    achieved = dbytes / (dec_mean_us * 1e-6) / 1e9
+    kernel_bytes = dbytes + (sbytes if fused else 0)          # the fused kernel also moves the new tokens
+    achieved = kernel_bytes / (dec_mean_us * 1e-6) / 1e9
 
     result = {
         "metric": "INT4 paged decode attn HBM GB/s (% peak) + rotate-quant-store tokens/s",
@@ -343,11 +363,13 @@ def main():
                    "tokens_cached": int(lens1.sum()), "splits": splits, "chunk_tokens": chunk,
                    "bytes_per_step": dbytes + sbytes},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "roofline": {"bound": "hbm", "kernel": "saw_paged_decode_attn = one launch of decode_int4_mfma_kernel (pair mode)",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("saw_append_decode_attn = one launch of decode_int4_mfma_kernel (pair mode, fused append)"
+                                if fused else "saw_paged_decode_attn (decode_int4_mfma_kernel [+ merge])"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": profiled_traffic() if args.workload == "highconc" else None,
-                     "bytes_per_launch": dbytes, "avg_us": round(dec_mean_us, 2),
+                     "bytes_per_launch": kernel_bytes, "avg_us": round(dec_mean_us, 2),
                      "median_us": round(float(np.median(dec_us)), 2),
                      "p10_us": round(float(np.percentile(dec_us, 10)), 2),
                      "p90_us": round(float(np.percentile(dec_us, 90)), 2)},
@@ -357,13 +379,22 @@ def main():
         ex = {}
         med, mean, p10, p90 = time_calls(store_step, 50, 5)
         ex["decode_step_store_us"] = round(med, 2)
+        med_d, mean, p10, p90 = time_calls(decode_step, 50, 5)
+        ex["decode_only_us"] = round(med_d, 2)
+        t_a = time.perf_counter()
+        for _ in range(50):
+            store_step()
+            decode_step()
+        torch.cuda.synchronize()
+        ex["unfused_step_ms"] = round((time.perf_counter() - t_a) * 1e3 / 50, 5)
+        ex["fused_step_ms"] = round(ms_per_step, 5) if fused else None
         ws16 = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len), dtype=torch.uint8, device=dev)
         med, mean, p10, p90 = time_calls(lambda: saw.kv16_paged_decode_attn(kv16, q, pt, seq_lens, max_seq_len=max_len,
                                                                             out=out, workspace=ws16), 30, 5)
         b16 = kv16_decode_bytes(w, lens1)
         ex["kv16_decode"] = {"us": round(med, 2), "GB_s": round(b16 / med / 1e3, 1),
                              "pct_of_hbm_peak": round(b16 / med / 1e3 / HBM_PEAK_GBS * 100, 2),
-                             "int4_speedup": round(med / float(np.median(dec_us)), 3),
+                             "int4_speedup": round(med / med_d, 3),
                              "bytes_ratio": round(b16 / dbytes, 3),
                              "note": "the 16-bit kernel is an untuned vector-ALU formulation; at equal bandwidth "
                                      "the speed-up would equal bytes_ratio"}

@@ -142,6 +142,34 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
                           saw_stream_t stream);
 
 /*
+ * One whole decode step for a layer in a single call: append this step's K/V token of every
+ * sequence to the cache, then attend over the cache including it (Sec. 4.1: "new KV entries
+ * are rotated, quantised and written" followed by the rotated-space attention).  The result is
+ * that of saw_rotate_quant_store(slots = (b, seq_lens[b])) followed by saw_paged_decode_attn
+ * over seq_lens[b] + 1 tokens.  With head_dim 128 and one partition per sequence (large batches)
+ * both happen in ONE kernel launch: the wavefront that starts a sequence quantises and stores the
+ * new token and seeds its softmax state with it; otherwise the call enqueues the store and the
+ * decode kernels back to back.
+ *
+ *   K_new, V_new device, dense [B][n_kv_heads][head_dim] of kv_dtype (SAW_F16 | SAW_BF16),
+ *               16-byte aligned: token b belongs to sequence b.
+ *   seq_lens    device, [B] int32: tokens cached BEFORE this call; the new token goes to
+ *               position seq_lens[b] (its page must be mapped in page_table; if it is not, the
+ *               token is still attended to but not stored).  Not modified: the caller advances
+ *               its lengths afterwards.
+ *   max_seq_len host-side upper bound on seq_lens (before the append); <= 0 means
+ *               max_pages_per_seq * page_size - 1.  max_seq_len + 1 must fit the page table row.
+ *   workspace   at least saw_decode_workspace_bytes(cache, B, n_q_heads, max_seq_len + 1, 0) bytes.
+ * Everything else as in saw_paged_decode_attn.
+ */
+int saw_append_decode_attn(const saw_cache_t* cache, const void* K_new, const void* V_new,
+                           int32_t kv_dtype, const void* q, int32_t q_dtype, int32_t B,
+                           int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                           const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                           int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                           saw_stream_t stream);
+
+/*
  * Dequantise positions [pos_begin, pos_end) of sequence `seq` into dense fp32
  * [pos_end - pos_begin][n_kv_heads][head_dim] buffers: x^ = s (c - z) (App. A.1).  With
  * unrotate != 0 the rotated tensors are multiplied by H_blk once more, which returns them

@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
         L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.saw_append_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, vp]
         L.saw_flatten_dequant.argtypes = [cp, vp, i32, i32, i32, i32, i32, i32, vp, vp, ctypes.c_int64, vp]
         L.saw_kv16_store.argtypes = [cp, vp, vp, i32, vp, vp, i64, i64, vp, i32, i32, vp, vp]
         L.saw_kv16_paged_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32,
@@ -140,6 +141,29 @@ def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_s
                                        page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
                                        _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
                                        num_splits, _stream()), "saw_paged_decode_attn")
+    return out
+
+
+def append_decode_attn(cache: Cache, K_new, V_new, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,
+                       out_dtype=torch.float32, workspace=None):
+    """saw_append_decode_attn: K_new, V_new ``[B][Hkv][d]`` (token b -> sequence b at position
+    seq_lens[b]), q ``[B][Hq][d]``; stores the tokens and returns ``out [B][Hq][d]`` of the attention
+    over seq_lens[b] + 1 tokens.  seq_lens (tokens cached before the call) is not modified."""
+    B, Hq, d = q.shape
+    assert q.is_contiguous() and K_new.is_contiguous() and V_new.is_contiguous() and K_new.dtype == V_new.dtype
+    assert page_table.is_contiguous() and seq_lens.dtype == torch.int32
+    cap = page_table.shape[1] * cache.page_size
+    after = (max_seq_len if max_seq_len > 0 else cap - 1) + 1
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=out_dtype, device=q.device)
+    need = decode_workspace_bytes(cache, B, Hq, after, 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = cache.struct()
+    _check(lib().saw_append_decode_attn(ctypes.byref(st), _ptr(K_new), _ptr(V_new), _DT[K_new.dtype], _ptr(q),
+                                        _DT[q.dtype], B, Hq, _ptr(page_table), page_table.shape[1], _ptr(seq_lens),
+                                        max_seq_len, float(sm_scale), _ptr(out), _DT[out.dtype], _ptr(workspace),
+                                        workspace.numel(), _stream()), "saw_append_decode_attn")
     return out
 
 

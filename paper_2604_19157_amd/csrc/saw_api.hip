@@ -8,7 +8,7 @@ namespace saw {
 
 
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
-                 int32_t, int32_t, const int32_t*, hipStream_t);
+                 int32_t, int32_t, const int32_t*, const int32_t*, hipStream_t);
 int launch_flatten(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, void*, void*, int64_t,
                    hipStream_t);
 int launch_dequant(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t,
@@ -18,7 +18,8 @@ int launch_kv16_store(const saw_cache_t*, void*, void*, const void*, const void*
 int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void* v_pages, int kv_dtype,
                const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
                const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
-               const SplitPlan& plan, hipStream_t st);
+               const SplitPlan& plan, const void* k_new, const void* v_new, int kv_new_dtype, int len_bias,
+               hipStream_t st);
 
 static bool shape_ok(const saw_cache_t* c) {
   if (c->page_size != 16) return false;
@@ -108,7 +109,7 @@ int saw_rotate_quant_store(const saw_cache_t* c, const void* K, const void* V, i
       (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
     return SAW_EINVAL;
   return launch_store(c, K, V, in_dtype, T, token_stride_elems, page_table, n_seqs, max_pages_per_seq,
-                      slots, (hipStream_t)stream);
+                      slots, nullptr, (hipStream_t)stream);
 }
 
 size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_heads,
@@ -157,7 +158,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
-                    out_dtype, ws, plan, (hipStream_t)stream);
+                    out_dtype, ws, plan, nullptr, nullptr, 0, 0, (hipStream_t)stream);
 }
 
 int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, int32_t B,
@@ -169,6 +170,52 @@ int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, 
   return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
                        max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
                        workspace_bytes, num_splits, stream);
+}
+
+int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
+                           const void* q, int32_t q_dtype, int32_t B, int32_t Hq,
+                           const int32_t* page_table, int32_t max_pages, const int32_t* seq_lens,
+                           int32_t max_seq_len, float sm_scale, void* out, int32_t out_dtype,
+                           void* ws, size_t ws_bytes, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || !block_ok(c)) return SAW_EINVAL;
+  if (kv_dtype != SAW_F16 && kv_dtype != SAW_BF16) return SAW_EINVAL;
+  if (q_dtype != SAW_F16 && q_dtype != SAW_BF16 && q_dtype != SAW_F32) return SAW_EINVAL;
+  if (out_dtype != SAW_F16 && out_dtype != SAW_BF16 && out_dtype != SAW_F32) return SAW_EINVAL;
+  if (B < 1 || Hq < 1 || max_pages < 1 || B > 65535 || c->n_kv_heads > 65535) return SAW_EINVAL;
+  if (Hq % c->n_kv_heads) return SAW_EINVAL;
+  const int G = Hq / c->n_kv_heads;
+  if (!(G == 1 || G == 2 || G == 4 || G == 8)) return SAW_EINVAL;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !K_new || !V_new || !q || !page_table ||
+      !seq_lens || !out || !ws)
+    return SAW_ENULL;
+  if (!aligned16(K_new) || !aligned16(V_new) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
+      !aligned16(ws) || (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
+    return SAW_EINVAL;
+  if (!isfinite(sm_scale) || max_seq_len < 0) return SAW_EINVAL;
+  // the plan covers the lengths after the append (max_seq_len + 1 tokens)
+  const int64_t cap = (int64_t)max_pages * c->page_size;
+  const int64_t after = (max_seq_len <= 0 ? cap - 1 : (int64_t)max_seq_len) + 1;
+  if (after > cap) return SAW_EINVAL;
+  SplitPlan plan;
+  const bool fused_kernel = c->head_dim == 128;
+  if (!make_plan(c, B, max_pages, (int)after, 0, &plan)) return SAW_EINVAL;
+  const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
+  if (ws_bytes < need) return SAW_EWORKSPACE;
+  if (fused_kernel && plan.num_splits == 1) {
+    // one launch: the decode kernel stores the new token itself and attends to it from registers;
+    // the cached range is [0, seq_lens[b]), bounded by max_seq_len as given
+    plan.bound = (int)(after - 1);
+    return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
+                      sm_scale, out, out_dtype, ws, plan, K_new, V_new, kv_dtype, 0, (hipStream_t)stream);
+  }
+  // otherwise two launches from the same call: append (token b -> sequence b at seq_lens[b]),
+  // then decode over seq_lens[b] + 1 tokens
+  const int rc = launch_store(c, K_new, V_new, kv_dtype, B, (int64_t)c->n_kv_heads * c->head_dim, page_table, B,
+                              max_pages, nullptr, seq_lens, (hipStream_t)stream);
+  if (rc != SAW_OK) return rc;
+  return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
+                    sm_scale, out, out_dtype, ws, plan, nullptr, nullptr, 0, 1, (hipStream_t)stream);
 }
 
 int saw_dequant_pages(const saw_cache_t* c, const int32_t* page_table, int32_t max_pages_per_seq,

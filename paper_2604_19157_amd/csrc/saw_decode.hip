@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void decode_int4_kernel(DecodeParams p) {
   constexpr int WPL = CPL / 8;         // dwords per lane
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int L = min(p.seq_lens[b], p.bound);
+  const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int t_begin = split * p.chunk_tokens;
   const int t_end = min(L, t_begin + p.chunk_tokens);
   if (t_begin >= t_end) return;
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void decode_kv16_kernel(DecodeParams p) {
   constexpr int WPL = CPL / 2;         // dwords per lane
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int L = min(p.seq_lens[b], p.bound);
+  const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int t_begin = split * p.chunk_tokens;
   const int t_end = min(L, t_begin + p.chunk_tokens);
   if (t_begin >= t_end) return;
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
   const int j = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = tid % D, g = tid / D;
-  const int L = min(p.seq_lens[b], p.bound);
+  const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int64_t o_idx = ((int64_t)b * p.n_q_heads + j) * D + c;
   if (L <= 0) {
     if (g == 0) store_elem(p.out, p.out_dtype, o_idx, 0.f);
@@ -451,7 +451,8 @@ int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_
 int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void* v_pages, int kv_dtype,
                const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
                const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
-               const SplitPlan& plan, hipStream_t st) {
+               const SplitPlan& plan, const void* k_new, const void* v_new, int kv_new_dtype, int len_bias,
+               hipStream_t st) {
   DecodeParams p;
   p.k_codes = (const uint8_t*)k_pages;
   p.v_codes = (const uint8_t*)v_pages;
@@ -479,6 +480,11 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.waves_per_item = plan.waves_per_item;
   // Pair mode: one partition per sequence, enough (sequence, kv head) items that every compute
   // unit gets several, and at most 16 lengths per lane for the in-kernel ranking.
+  p.k_new = k_new;
+  p.v_new = v_new;
+  p.kv_new_dtype = kv_new_dtype;
+  p.append = k_new != nullptr;
+  p.len_bias = len_bias;
   p.batch = B;
   p.pair = !kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
            (int64_t)B * c->n_kv_heads > 256 && B <= 1024;

@@ -145,7 +145,8 @@ constexpr float kLazyTau = 8.0f;               // reference max may lag the true
 // the LDS-DMA transfers the caller already has in flight into other buffers.
 template <int G, int NH>
 __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&qraw)[2 * G], int lane,
-                                          float* __restrict__ qs, u32x4 (&a_q)[4], float (&qsum)[NH]) {
+                                          float* __restrict__ qs, float* __restrict__ qred, u32x4 (&a_q)[4],
+                                          float (&qsum)[NH], float& qmul_out) {
   constexpr int D = 128;
   constexpr int LO = (G > 4) ? 8 : 4;
   const int row16 = lane & 15, grp = lane >> 4;
@@ -179,12 +180,110 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   qpart += __shfl_xor(qpart, 16, 64);
   qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the limbs it feeds
   wave_sync();
-  if (lane < 16) qs[lane] = qpart;
+  if (lane < 16) qred[lane] = qpart;
   wave_sync();
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
     const int hd = (G > 4) ? (4 * (grp & 1) + i) : i;
-    qsum[i] = qs[hd] + qs[LO + hd];
+    qsum[i] = qred[hd] + qred[LO + hd];
+  }
+  wave_sync();
+  qmul_out = qmul;
+}
+
+// The decode step's own token (fused append, Sec. 4.1's "new KV entries are rotated, quantised
+// and written" folded into the attention launch): rotate, quantise and store the new K and V
+// vectors of (sequence b, kv head kvh) at position L exactly as the store kernel would (Sec. 3
+// eqs. 1-3, App. A.1), and start the softmax state from that token: its logit against the rotated
+// query is the reference maximum, its weight 1 is the running sum, its dequantised V row the
+// accumulator.  The cached tokens [0, L) are then streamed as usual, so nothing this launch
+// writes is read back by it.  One wavefront, two channels per lane.
+//   pid, wk, wv  page id of position L and this lane's two channels of the new K and V vectors,
+//         loaded by the caller early enough that nothing here waits for memory
+//   qrot  LDS, [G][128]: the (rotated) query rows before scaling; qmul their scale
+//   scr   LDS scratch of 144 floats, distinct from qrot
+template <int G, int NH>
+__device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int lane, int L, int pid,
+                                             uint32_t wk, uint32_t wv,
+                                             const float* __restrict__ qrot, float qmul,
+                                             float* __restrict__ scr, f32x4 (&oacc)[8],
+                                             float (&m_ref)[NH], float (&lsum)[NH]) {
+  constexpr int D = 128;
+  const int row16 = lane & 15, grp = lane >> 4;
+  float* const yb = scr;            // [128]: rotation scratch, then the dequantised V row
+  float* const lg = scr + 128;      // [G]: logits of the new token
+  const int slot = L & 15;
+  const bool place = pid >= 0 && pid < p.num_pages;          // otherwise attended to but not stored
+  const int64_t vec = ((int64_t)pid * p.n_kv_heads + kvh) * 16 + slot;
+#pragma unroll 1
+  for (int which = 0; which < 2; ++which) {                  // 0: K, 1: V
+    const bool rot = which ? (p.rot_v != 0) : (p.rot_k != 0);
+    const uint32_t w = which ? wv : wk;
+    float x0, x1;
+    if (p.kv_new_dtype == SAW_BF16) widen2<SAW_BF16>(w, x0, x1); else widen2<SAW_F16>(w, x0, x1);
+    yb[2 * lane] = x0;
+    yb[2 * lane + 1] = x1;
+    wave_sync();
+    float norm = 1.0f;
+    if (rot) {
+      wave_lds_fwht128(yb, 1, p.had_block, lane);
+      norm = had_norm(p.had_block);
+    }
+    const float y0 = yb[2 * lane], y1 = yb[2 * lane + 1];
+    // min and max over the 128 values: one reduction of (max, -min) pairs, rows first (DPP)
+    float mx = row_allmax(fmaxf(y0, y1)), nmn = row_allmax(-fminf(y0, y1));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    nmn = fmaxf(nmn, __shfl_xor(nmn, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    nmn = fmaxf(nmn, __shfl_xor(nmn, 32, 64));
+    const float mn = -nmn;
+    const float range = mx - mn;
+    float inv, zq, s_store, z_store;
+    if (range > 0.0f) {
+      inv = 15.0f / range;
+      s_store = range * (norm * (1.0f / 15.0f));
+      zq = rintf(-mn * inv);
+      z_store = zq;
+    } else {  // constant vector
+      inv = 0.0f;
+      zq = 0.0f;
+      s_store = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
+      z_store = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
+    }
+    const float c0 = __builtin_amdgcn_fmed3f(rintf(y0 * inv) + zq, 0.0f, 15.0f);
+    const float c1 = __builtin_amdgcn_fmed3f(rintf(y1 * inv) + zq, 0.0f, 15.0f);
+    if (place) {
+      uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes);
+      float* meta = const_cast<float*>(which ? p.v_meta : p.k_meta);
+      codes[vec * (D / 2) + lane] = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
+      if (lane == 0) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
+    }
+    const float d0 = s_store * (c0 - z_store), d1 = s_store * (c1 - z_store);
+    wave_sync();                                             // every read of yb above is done
+    if (which == 0) {
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        float part = fmaf(qrot[j * D + 2 * lane], d0, qrot[j * D + 2 * lane + 1] * d1);
+        part = row_allsum(part);
+        part += __shfl_xor(part, 16, 64);
+        part += __shfl_xor(part, 32, 64);
+        if (lane == 0) lg[j] = part * qmul;
+      }
+    } else {
+      yb[2 * lane] = d0;
+      yb[2 * lane + 1] = d1;
+    }
+    wave_sync();
+  }
+  const int head0 = (G > 4) ? 4 * (grp & 1) : 0;
+  const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
+  const bool counts = (G > 4) ? (lane == 0 || lane == 16) : (lane == 0);   // one lane per head group holds the weight
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    m_ref[i] = lg[head0 + i];
+    lsum[i] = counts ? 1.0f : 0.0f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) oacc[c][i] = (writer && i < G) ? yb[16 * c + row16] : 0.0f;
   }
   wave_sync();
 }
@@ -199,7 +298,7 @@ struct LenClasses {
   int V;                     // ceil(B / 64)
 };
 __device__ __forceinline__ int len_class(const DecodeParams& p, int idx, float kscale) {
-  const int nb = (min(p.seq_lens[idx], p.bound) + 63) >> 6;
+  const int nb = (min(p.seq_lens[idx] + p.len_bias, p.bound) + 63) >> 6;
   return 63 - (int)((float)max(nb, 0) * kscale);
 }
 __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* hist) {
@@ -266,7 +365,9 @@ constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes + 2 * kMetaBytes;   // per
 enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 
 template <int G, int NW, bool PAIR>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(PAIR ? 2 : 3, PAIR ? 2 : 3)))
+// (a launch of this kernel puts at most 8 wavefronts on a compute unit, 2 per SIMD: let the
+// register allocator use the 256 registers that leaves each of them)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void decode_int4_mfma_kernel(DecodeParams p) {
   static_assert(!PAIR || NW == 2, "a pair block has two wavefronts");
   constexpr int D = 128;
@@ -293,6 +394,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   int nseg = 1;
   int sg_b[2] = {(int)blockIdx.z, 0}, sg_t0[2] = {split * p.chunk_tokens, 0}, sg_t1[2] = {0, 0};
   int sg_mode[2] = {kSegSplitKV, kSegAlone};
+  int sg_len[2] = {0, 0};                      // PAIR: length of the range's sequence
   if (PAIR) {
     const int B = p.batch;
     if (threadIdx.x == 0) shared_done = 0;
@@ -302,33 +404,35 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
     const int b_long = seq_of_rank(p, B, lane, lc, r_long);
     const int b_short = self ? b_long : seq_of_rank(p, B, lane, lc, r_short);
-    const int l_long = max(min(p.seq_lens[b_long], p.bound), 0);
-    const int l_short = self ? 0 : max(min(p.seq_lens[b_short], p.bound), 0);
+    const int l_long = max(min(p.seq_lens[b_long] + p.len_bias, p.bound), 0);
+    const int l_short = self ? 0 : max(min(p.seq_lens[b_short] + p.len_bias, p.bound), 0);
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
     // wavefront 1 pays a second prologue when the long sequence is shared: one batch in its favour
     const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
     const bool shared = cut < nb_long;
     nseg = 0;
+    // (with a fused append an empty sequence still has its new token to attend to: it gets an
+    // empty range instead of a zero row)
     if (wave == 0) {
-      if (nb_long == 0) {                               // empty sequence: zero output row
+      if (nb_long == 0 && !p.append) {                  // empty sequence: zero output row
         for (int i = lane; i < G * D; i += 64)
           store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * D + i, 0.f);
       } else {
-        sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut);
+        sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut); sg_len[0] = l_long;
         sg_mode[0] = shared ? kSegShare : kSegAlone;
         nseg = 1;
       }
     } else {
-      if (nb_short > 0) {
-        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_mode[0] = kSegAlone;
+      if (nb_short > 0 || (p.append && !self)) {
+        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_len[0] = l_short; sg_mode[0] = kSegAlone;
         nseg = 1;
       } else if (!self) {
         for (int i = lane; i < G * D; i += 64)
           store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * D + i, 0.f);
       }
       if (shared) {                                     // last, so that its record can stay in this wavefront's buffers
-        if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_mode[0] = kSegShare; }
-        else           { sg_b[1] = b_long; sg_t0[1] = 64 * cut; sg_t1[1] = l_long; sg_mode[1] = kSegShare; }
+        if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_len[0] = l_long; sg_mode[0] = kSegShare; }
+        else           { sg_b[1] = b_long; sg_t0[1] = 64 * cut; sg_t1[1] = l_long; sg_len[1] = l_long; sg_mode[1] = kSegShare; }
         ++nseg;
       }
     }
@@ -372,13 +476,14 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   int pidv, pidv_nx;                 // pidv_nx stays unclamped until it becomes pidv
   int window = 0;                    // 16-batch window pidv covers
   SAW_LOAD_PIDS(pidv, pg_first)
-  int t_end;
+  int t_end, seq_len_b;                // seq_len_b: cached tokens of the sequence (= position of an appended token)
   if (PAIR) {
     t_end = seg == 0 ? sg_t1[0] : sg_t1[1];
+    seq_len_b = seg == 0 ? sg_len[0] : sg_len[1];
   } else {
-    const int L = min(p.seq_lens[b], p.bound);
-    t_end = min(L, t_begin + p.chunk_tokens);
-    if (t_begin >= t_end) {            // block-uniform
+    seq_len_b = max(min(p.seq_lens[b] + p.len_bias, p.bound), 0);
+    t_end = min(seq_len_b, t_begin + p.chunk_tokens);
+    if (t_begin >= t_end && !(p.append && t_begin == 0)) {            // block-uniform
       if (p.num_splits == 1)           // empty sequence and no merge pass: the output row is zero
         for (int i = threadIdx.x; i < G * 128; i += 64 * NW)
           store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
@@ -400,7 +505,19 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   }
 
-  const int nb = (t_end - t_begin + 63) >> 6;                     // batches of the partition
+  // fused append: the range that starts the sequence also takes the step's new token (wavefront
+  // 0 of the block when several share the range); its inputs are requested here, with the query
+  const bool takes_new = p.append && t_begin == 0 && first_batch == 0;
+  uint32_t new_wk = 0, new_wv = 0;
+  int new_pid = -1;
+  if (takes_new) {
+    const int64_t e = (((int64_t)b * p.n_kv_heads + kvh) * D) / 2 + lane;
+    new_wk = ((const uint32_t*)p.k_new)[e];
+    new_wv = ((const uint32_t*)p.v_new)[e];
+    if ((seq_len_b >> 4) < p.max_pages) new_pid = p.page_table[pt_row + (seq_len_b >> 4)];
+  }
+
+  const int nb = max(t_end - t_begin + 63, 0) >> 6;               // batches of the range (0: only an appended token)
   // last batch of this wavefront (below first_batch if it has none)
   const int my_last = nb - 1 - ((nb - 1 - first_batch) % STEP + STEP) % STEP;
 
@@ -445,6 +562,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // costs about a microsecond per block before the first transfer leaves)
   u32x4 a_q[4];
   float qsum[NH];
+  float qmul;
   {
     float qraw[2 * G];
     const bool q_is_f32 = p.q_dtype == SAW_F32, q_is_bf16 = p.q_dtype == SAW_BF16;
@@ -455,13 +573,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       const float as_f16 = f16_to_f32(qbits[j] & 0xffffu);
       qraw[j] = q_is_f32 ? as_f32 : (q_is_bf16 ? as_bf16 : as_f16);
     }
-    prepare_q<G, NH>(p, qraw, lane, (float*)vbuf_b, a_q, qsum);
-  }
-  {
-    // issued unconditionally: a wavefront without a batch of its own shadows the last batch
-    const int first = min(first_batch, nb - 1);
-    SAW_FETCH_V(first, vbuf_a, mbuf_a)
-    SAW_FETCH_K(first, kbuf)
+    prepare_q<G, NH>(p, qraw, lane, (float*)vbuf_b, (float*)pbuf, a_q, qsum, qmul);
   }
 
   f32x4 oacc[8];
@@ -470,6 +582,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   float m_ref[NH], lsum[NH], zs[NH];
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
+  if (takes_new)
+    append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (const float*)vbuf_b, qmul,
+                        (float*)kbuf, oacc, m_ref, lsum);
+
+  if (nb > 0) {
+    // issued unconditionally: a wavefront without a batch of its own shadows the last batch
+    const int first = min(first_batch, nb - 1);
+    SAW_FETCH_V(first, vbuf_a, mbuf_a)
+    SAW_FETCH_K(first, kbuf)
+  }
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.

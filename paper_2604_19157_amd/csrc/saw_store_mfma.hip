@@ -33,7 +33,8 @@ struct StoreMfmaParams {
   float* meta[2];
   const void* in[2];
   const int32_t* page_table;
-  const int32_t* slots;
+  const int32_t* slots;         // [T][2] (sequence, position), or null:
+  const int32_t* append_lens;   // then token t goes to sequence t at position append_lens[t]
   int64_t T;
   int64_t token_stride;
   int32_t n_seqs, max_pages, num_pages, n_kv_heads;
@@ -91,7 +92,8 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   // this lane's token (column n16 of the tile) and where it goes
   const int64_t t_mine = t0 + n16;
   int2 slot = make_int2(-1, -1);
-  if (wave_live && t_mine < p.T) slot = *(const int2*)(p.slots + 2 * t_mine);
+  if (wave_live && t_mine < p.T)
+    slot = p.slots ? *(const int2*)(p.slots + 2 * t_mine) : make_int2((int)t_mine, p.append_lens[t_mine]);
 
   // ---- the +/-1 matrix: A[m][k], m = output row, k = input channel (low five bits) ----
   // MFMA #1 row m -> output channel (low five bits) 8*(m/4) + m%4, MFMA #2 row m -> that + 4,
@@ -232,12 +234,13 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
 
 int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                       const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
+                      const int32_t* append_lens,
                       hipStream_t st) {
   StoreMfmaParams p;
   p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
   p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
   p.in[0] = K; p.in[1] = V;
-  p.page_table = pt; p.slots = slots; p.T = T; p.token_stride = stride;
+  p.page_table = pt; p.slots = slots; p.append_lens = append_lens; p.T = T; p.token_stride = stride;
   p.n_seqs = n_seqs; p.max_pages = max_pages; p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads;
   p.had_block = c->had_block;
   p.rot[0] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);

@@ -26,7 +26,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported(saw):
     names = _declared()
-    assert {"saw_rotate_quant_store", "saw_paged_decode_attn", "saw_dequant_pages", "saw_flatten_dequant",
+    assert {"saw_rotate_quant_store", "saw_paged_decode_attn", "saw_dequant_pages", "saw_flatten_dequant", "saw_append_decode_attn",
             "saw_decode_workspace_bytes", "saw_kv16_paged_decode_attn"} <= set(names)
     L = saw.lib()
     for n in names:

@@ -1,0 +1,133 @@
+"""Parity of saw_append_decode_attn (fused decode step: append the new token, attend over the cache
+including it) with the oracle's store followed by the oracle's decode.
+
+The cached tokens are bytes the oracle's store wrote (uploaded); the step's new K/V token is stored by
+the HIP path inside the call, so its codes are checked against the oracle's under the store criterion
+(bit-exact up to the rounding-boundary rule) and the attention output under the 2e-3 criterion - except
+for a sequence whose new token took an exempt boundary code, which moves one value by a whole
+quantisation step and is only held to the loose composed bound."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_cases as gc
+import parity
+from oracle import saw_oracle as O
+from paper_2604_19157_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def saw():
+    from paper_2604_19157_amd import binding
+    binding.lib()
+    return binding
+
+
+def _new_tokens(w):
+    ks, vs = [], []
+    for b in range(w.batch):
+        L = int(w.seq_lens[b])
+        K, V = synth.gen_kv(w, b, L, L + 1)
+        ks.append(K)
+        vs.append(V)
+    return torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
+
+
+def _case(saw, w, out_dtype=torch.float32, unmapped=()):
+    """`unmapped`: sequences whose new token's page is taken out of the page table (attended, not stored)."""
+    B = w.batch
+    ref = gc.oracle_fill(w)
+    cache = gc.upload_cache(ref, w, saw)
+    page_table = w.page_table.copy()
+    for b in unmapped:
+        page_table[b, int(w.seq_lens[b]) >> 4] = -1
+    pt = torch.from_numpy(page_table).cuda()
+    lens = torch.from_numpy(w.seq_lens).cuda()
+    Kn, Vn = _new_tokens(w)
+    q = synth.gen_q(w)
+    out = torch.full((B, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
+    before = gc.cache_to_numpy(cache, w)
+    saw.append_decode_attn(cache, Kn.cuda(), Vn.cuda(), q.cuda(), pt, lens, max_seq_len=int(w.seq_lens.max()), out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(lens.cpu(), torch.from_numpy(w.seq_lens))              # lengths are the caller's to advance
+    got = gc.cache_to_numpy(cache, w)
+
+    # oracle: store the new tokens (into the mapped table: an unmapped token is still attended to), then decode
+    slots = np.stack([np.arange(B, dtype=np.int32), w.seq_lens.astype(np.int32)], 1)
+    rec = O.rotate_quant_store(ref, Kn.float().numpy(), Vn.float().numpy(), w.page_table, slots, w.had_block,
+                               w.rotate_mask, return_prerounding=True)
+    o_ref = O.paged_decode_attn(ref, q.float().numpy(), w.page_table, w.seq_lens + 1, w.had_block, w.rotate_mask)
+
+    # (1) the appended token's bytes
+    page, slot = rec["page"], rec["slot"]
+    exempt = np.zeros(B, bool)
+    written = np.zeros(got["k_codes"].shape[:3], bool)
+    for b in range(B):
+        if b in unmapped:
+            continue
+        written[page[b], :, slot[b]] = True
+        for which in ("k", "v"):
+            n = w.n_kv_heads
+            res = parity.compare_vectors(got[which + "_codes"][page[b], :, slot[b], :], got[which + "_meta"][page[b], :, slot[b], :],
+                                         ref[which + "_codes"][page[b], :, slot[b], :], ref[which + "_meta"][page[b], :, slot[b], :],
+                                         rec[which + "_y"][b].reshape(n, -1), rec[which + "_s"][b].reshape(n),
+                                         rec[which + "_z"][b].reshape(n))
+            parity.assert_store_ok(res)
+            exempt[b] |= bool(res["near_boundary_mismatch"] or res["zero_flip_vectors"])
+    # nothing else in the cache changed
+    for k in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        assert np.array_equal(got[k][~written], before[k][~written]), k
+
+    # (2) the attention output
+    o = out.float().cpu().numpy()
+    assert np.isfinite(o).all()
+    tol = TOL if out_dtype == torch.float32 else TOL + 2.0 ** -8
+    worst = 0.0
+    for b in range(B):
+        err = parity.attn_error(o[b:b + 1], o_ref[b:b + 1])
+        assert err < (5e-2 if exempt[b] else tol), f"[{w.name} seq {b} len {int(w.seq_lens[b])} exempt={exempt[b]}] err={err:.2e}"
+        worst = max(worst, err)
+    print(f"[{w.name} B={B} Hq={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} h={w.had_block} mask={w.rotate_mask}] "
+          f"worst err={worst:.2e} exempt sequences={int(exempt.sum())}", flush=True)
+
+
+def test_small_batch_one_launch(saw):
+    """B*Hkv <= 256: one wavefront per (sequence, kv head), fused in the kernel."""
+    _case(saw, synth.make_workload("tiny"))
+
+
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4)])
+def test_large_ragged_batch_pair_mode(saw, B, Hkv):
+    rng = np.random.default_rng(B)
+    lens = rng.integers(0, 330, size=B)
+    lens[:6] = [0, 329, 1, 16, 15, 64]                       # empty, page boundaries, batch boundary
+    w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv)
+    _case(saw, w)
+
+
+@pytest.mark.parametrize("h,mask", [(1, 3), (16, 3), (32, 3), (64, 3), (128, 3), (64, 1), (64, 2)])
+def test_block_sizes_and_masks(saw, h, mask):
+    _case(saw, synth.make_workload("llama8b", batch=3, seq_lens=[0, 47, 200], had_block=h, rotate_mask=mask))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (64, 8)])
+def test_group_sizes(saw, Hq, Hkv):
+    _case(saw, synth.make_workload("highconc", batch=3, ctx=(20, 150), n_q_heads=Hq, n_kv_heads=Hkv, dtype=torch.float16))
+
+
+def test_split_kv_and_head_dim_64_take_two_launches(saw):
+    _case(saw, synth.make_workload("llama8b", batch=2, ctx=2000))                 # several partitions per sequence
+    _case(saw, synth.make_workload("highconc", batch=3, ctx=(20, 150), n_q_heads=8, n_kv_heads=4, head_dim=64,
+                                   had_block=64))
+
+
+def test_unmapped_page_is_attended_but_not_stored(saw):
+    w = synth.make_workload("tiny", batch=3, seq_lens=[16, 40, 95])
+    _case(saw, w, unmapped=(0,))
+
+
+def test_bf16_output(saw):
+    _case(saw, synth.make_workload("tiny", batch=2, ctx=75), out_dtype=torch.bfloat16)
