@@ -39,8 +39,9 @@ static bool block_ok(const saw_cache_t* c) {
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
 // Split-KV plan.  Partitions are whole multiples of 64 tokens so every wavefront pass
-// starts on a page boundary.  The automatic choice aims at a few thousand work items so
-// that ragged batches balance over 256 compute units, with partitions of 256..1024 tokens.
+// starts on a page boundary.  The automatic choice aims at about 2048 wavefronts (8 per compute
+// unit): one partition per sequence once the batch alone provides them, otherwise partitions of
+// at least 256 tokens, and 2 or 4 wavefronts per partition when even those are too few.
 static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_len, int num_splits,
                       SplitPlan* plan) {
   const int64_t cap = (int64_t)max_pages * c->page_size;

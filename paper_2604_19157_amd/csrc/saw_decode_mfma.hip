@@ -1,12 +1,13 @@
 // INT4 paged decode attention for head_dim 128 on the gfx950 matrix cores.
 // Paper: Sec. 2 (decode step), Sec. 4.1 / App. A.4 (rotated-space attention), App. A.1.
 //
-// One wavefront (a 64-thread block) owns one (sequence, kv head, context partition) and walks
-// it in batches of four pages (64 tokens).  Per batch:
-//   * the four K and four V code tiles (1 KiB each, contiguous in HBM) go straight from
-//     global memory into LDS (global_load_lds_dwordx4, no staging registers): V one batch
-//     ahead into a double buffer, K into a single buffer that is refilled as soon as its
-//     operand reads are done.  Each lane fetches the 16-byte chunk that belongs at its LDS
+// A wavefront walks a range of one (sequence, kv head)'s tokens in batches of four pages (64
+// tokens); which ranges a wavefront gets (a whole partition, every NW-th batch of one, or an even
+// share of a long/short sequence pair) is described at the kernel.  Per batch:
+//   * the four K and four V code tiles (1 KiB each, contiguous in HBM) and the tokens' (scale,
+//     zero) pairs go straight from global memory into LDS (global_load_lds_dwordx4, no staging
+//     registers): V and the metadata one batch ahead into double buffers, K into a single buffer
+//     that is refilled as soon as its operand reads are done.  Each lane fetches the 16-byte chunk that belongs at its LDS
 //     position under the swizzle pos(t, Q) = 4t + ((Q + t/4) & 3), which makes every later
 //     LDS read bank-conflict free while a lane quad still reads one whole 64-byte row;
 //   * nibbles become bf16 operands with two ALU ops per pair: (w >> 4i) & 0x000F000F | 0x43004300
@@ -23,6 +24,8 @@
 //     bf16 hi/lo rows; O[head][channel] accumulates in eight 16x16 tiles.
 // Zero-points never enter the loops:  q~.k^ = s (q~.(c+128) - (z+128) sum q~),
 // sum_t w_t v^_t = sum_t w_t (c_t+128) - sum_t w_t (z_t+128),  w_t = p_t s_t.
+// When one partition covers the sequence the kernel also normalises, rotates the output back and
+// writes it (no merge launch), and it can append the step's new token itself (append_token).
 #include "saw_decode.h"
 
 namespace saw {

@@ -98,6 +98,14 @@ def test_many_sequences_balanced_item_order(saw, B, Hkv):
     _decode_case(saw, w, num_splits=0, end_to_end=False)
 
 
+def test_batch_beyond_the_ranking_limit(saw):
+    """More than 1024 sequences: the in-kernel length ranking is not used (one wavefront per item)."""
+    rng = np.random.default_rng(7)
+    lens = rng.integers(0, 40, size=1100)
+    w = synth.make_workload("highconc", batch=1100, seq_lens=lens, n_q_heads=4, n_kv_heads=2)
+    _decode_case(saw, w, end_to_end=False)
+
+
 def test_long_context_many_splits(saw):
     w = synth.make_workload("longctx1", ctx=9000, n_q_heads=64)
     _decode_case(saw, w, num_splits=0, end_to_end=False)
