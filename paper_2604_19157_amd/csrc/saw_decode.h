@@ -32,6 +32,9 @@ struct DecodeParams {
 // MFMA INT4 decode for head_dim 128 (saw_decode_mfma.hip); grid = (splits, kv heads, batch).
 int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st);
 
+// MFMA 16-bit-KV decode for head_dim 128 and group sizes up to 4 (saw_decode_kv16_mfma.hip); false: not covered.
+bool launch_decode_kv16_mfma(const DecodeParams& p, int G, int kv_dtype, dim3 grid, hipStream_t st);
+
 inline size_t partial_bytes(int B, int Hq, int splits, int D) {
   return (((size_t)B * Hq * splits * (D + 2) * sizeof(float)) + 15) & ~(size_t)15;
 }

@@ -424,6 +424,9 @@ int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_
     if (launch_decode_int4_mfma(p, G, B, p.waves_per_item, grid, st) != SAW_OK) return SAW_EINVAL;
     if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
     if (p.num_splits == 1) return SAW_OK;       // the kernel wrote the output itself
+  } else if (kv16 && D == 128 && launch_decode_kv16_mfma(p, G, kv_dtype, grid, st)) {
+    if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
+    if (p.num_splits == 1) return SAW_OK;       // the kernel wrote the output itself
   } else {
 #define SAW_DISPATCH_G(DD)                                                          \
   switch (G) {                                                                      \

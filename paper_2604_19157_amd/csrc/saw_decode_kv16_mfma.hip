@@ -1,0 +1,298 @@
+// 16-bit-KV paged decode attention for head_dim 128 on the gfx950 matrix cores: the unquantised
+// comparison path (the cache the paper measures INT4 against, Sec. 2), written with the same
+// machinery as the INT4 kernel so that the comparison is between formats, not between efforts.
+//
+// One wavefront owns one (sequence, kv head, partition) and walks it in batches of two pages
+// (32 tokens).  Per batch:
+//   * K needs no staging: lane (token = lane % 16, k-group = lane / 16) of the logit MFMA's B
+//     operand wants 8 consecutive channels of its token, which is one 16-byte global load, so the
+//     eight K operand registers of a batch are loaded straight from HBM one batch ahead;
+//   * V is wanted with tokens along the contraction: its two page tiles (4 KiB each) go HBM -> LDS
+//     directly (global_load_lds_dwordx4) into a double buffer, 16-byte chunks XOR-swizzled by row so
+//     that ds_read_b64_tr_b16 (a 4x16 transpose of 16-bit elements inside each 16-lane group) reads
+//     them without bank conflicts and hands each lane 4 tokens of one channel;
+//   * logits: D[head][token] = q~ (heads x channels) . K (channels x tokens) with
+//     v_mfma_f32_16x16x32, q~ carried as hi + lo 16-bit limbs in separate rows of the tile;
+//   * softmax with a lazily updated reference maximum, P through LDS once as hi/lo rows,
+//     O[head][channel] in eight 16x16 tiles.
+// Group sizes up to 4 (rows: hi limbs of the heads, then lo limbs); larger groups use the
+// vector-ALU kernel.
+#include "saw_decode.h"
+#include "saw_wave_util.h"
+
+namespace saw {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+
+namespace kv16 {
+
+constexpr int kRowBytes = 256;                 // one token's head vector
+constexpr int kPageBytes = 16 * kRowBytes;     // one (page, head) tile
+constexpr int kVbufBytes = 2 * kPageBytes;     // a batch: 32 token rows
+constexpr int kProw = 40;                      // P row stride in 16-bit elements (32 tokens + 8 pad)
+constexpr int kPbufBytes = 8 * kProw * 2;      // hi rows of 4 heads, lo rows of 4 heads
+constexpr int kWaveLds = 2 * kVbufBytes + kPbufBytes;
+constexpr float kLazyTau = 8.0f;
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+  if (DT == SAW_BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// x = hi + lo as two 16-bit values of the cache's type (hi truncated / rounded, lo the rounded rest)
+template <int DT>
+__device__ __forceinline__ void split16(float x, uint32_t& hi16, uint32_t& lo16) {
+  if (DT == SAW_BF16) {
+    float sum;
+    split_bf16(x, hi16, lo16, sum);
+  } else {
+    hi16 = f32_to_f16(x);
+    lo16 = f32_to_f16(x - f16_to_f32(hi16));
+  }
+}
+
+}  // namespace kv16
+
+template <int G, int DT>
+__global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
+  using namespace kv16;
+  constexpr int D = 128;
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x;
+  const int row16 = lane & 15, grp = lane >> 4;
+  const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
+  const int t_begin = split * p.chunk_tokens;
+  const int t_end = min(L, t_begin + p.chunk_tokens);
+  if (t_begin >= t_end) {
+    if (p.num_splits == 1)
+      for (int i = lane; i < G * D; i += 64)
+        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i, 0.f);
+    return;
+  }
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kWaveLds];
+  uint8_t* const vbuf_a = lds;
+  uint8_t* const vbuf_b = lds + kVbufBytes;
+  uint8_t* const pbuf = lds + 2 * kVbufBytes;
+
+  const uint8_t* const kpages = p.k_codes;
+  const uint8_t* const vpages = p.v_codes;
+  const int64_t pt_row = (int64_t)b * p.max_pages;
+  const int64_t page_stride = (int64_t)p.n_kv_heads * kPageBytes;
+  const int64_t head_off = (int64_t)kvh * kPageBytes;
+  const int pg_first = t_begin >> 4;
+  const int nb = (t_end - t_begin + 31) >> 5;                       // batches of 32 tokens
+
+  // ---- q~ = q sm_scale log2(e) as the logit MFMA's A operand: rows 0..3 hi limbs, 4..7 lo limbs ----
+  u32x4 a_q[4];
+  {
+    const bool is_lo = (row16 & 4) != 0;
+    const int qhead = row16 & 3;
+    const bool live = row16 < 8 && qhead < G;
+    const int64_t qbase = ((int64_t)b * p.n_q_heads + kvh * G + (live ? qhead : 0)) * D;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint32_t limb[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float x = live ? load_elem(p.q, p.q_dtype, qbase + 32 * kk + 8 * grp + j) * p.q_scale : 0.f;
+        uint32_t h16, l16;
+        split16<DT>(x, h16, l16);
+        limb[j] = is_lo ? l16 : h16;
+      }
+      a_q[kk] = u32x4{limb[0] | (limb[1] << 16), limb[2] | (limb[3] << 16), limb[4] | (limb[5] << 16), limb[6] | (limb[7] << 16)};
+    }
+  }
+
+  // ---- fetch ----
+  // page ids of a batch: lanes 0 and 1 of `pidv`
+  auto load_pids = [&](int batch) {
+    const int lp = min(pg_first + 2 * batch + (lane & 1), p.max_pages - 1);
+    const int id = p.page_table[pt_row + lp];
+    return (id < 0 || id >= p.num_pages) ? 0 : id;
+  };
+  // K operand registers of a batch: kreg[page][kk] = channels 32kk + 8grp .. +7 of token row16
+  u32x4 kreg[2][4];
+#define KV16_LOAD_K(pid0, pid1)                                                                  \
+  {                                                                                              \
+    const uint8_t* k0 = kpages + (int64_t)(pid0) * page_stride + head_off + row16 * kRowBytes + 16 * grp; \
+    const uint8_t* k1 = kpages + (int64_t)(pid1) * page_stride + head_off + row16 * kRowBytes + 16 * grp; \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                           \
+      kreg[0][kk] = *(const u32x4*)(k0 + 64 * kk);                                               \
+      kreg[1][kk] = *(const u32x4*)(k1 + 64 * kk);                                               \
+    }                                                                                            \
+  }
+  // V tiles of a batch into VDST: transfer j covers token rows 4j .. 4j+3 (1 KiB of LDS); the lane
+  // at chunk position c of row r brings source chunk c ^ (2 (r & 3))
+  const int v_r4 = lane >> 4;                                        // row inside the transfer
+  const int v_src = (v_r4 * kRowBytes) + 16 * ((lane & 15) ^ (2 * v_r4));
+#define KV16_DMA_V(pid0, pid1, VDST)                                                             \
+  {                                                                                              \
+    const uint8_t* v0 = vpages + (int64_t)(pid0) * page_stride + head_off + v_src;               \
+    const uint8_t* v1 = vpages + (int64_t)(pid1) * page_stride + head_off + v_src;               \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                              \
+      __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(v0 + j * 4 * kRowBytes),          \
+                                       (LDS_AS void*)(VDST + j * 1024), 16, 0, 0);               \
+      __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(v1 + j * 4 * kRowBytes),          \
+                                       (LDS_AS void*)(VDST + 4096 + j * 1024), 16, 0, 0);        \
+    }                                                                                            \
+  }
+  int pid_nx;                                                        // ids of the batch after the one in flight
+  {
+    const int pv = load_pids(0);
+    const int a = __builtin_amdgcn_readlane(pv, 0), c = __builtin_amdgcn_readlane(pv, 1);
+    KV16_LOAD_K(a, c)
+    KV16_DMA_V(a, c, vbuf_a)
+    pid_nx = load_pids(min(1, nb - 1));
+  }
+
+  // ---- per-lane constants ----
+  // V transpose reads: source lane (s = row16, g = grp), half h, addresses 4 channels (16c + 4(s&3) ..)
+  // of token row r = 8g + 4h + s/4; the 16-byte chunk 2c + (s&3)/2 of that row sits at chunk position
+  // (2c + (s&3)/2) ^ 2(r&3) = 2(c ^ (r&3)) + (s&3)/2
+  const int v_rho = row16 >> 2;                                     // r & 3, the same for both halves
+  const int vr_base = (8 * grp + v_rho) * kRowBytes + 16 * ((row16 & 3) >> 1) + 8 * (row16 & 1);
+  // P: lane (token tk = lane % 32 of the batch, in lanes 0..31) writes column tk; the A operand read of
+  // lane (row, g) takes tokens 8g .. 8g+7 of row & 7
+  const uint32_t pa_addr = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)pbuf + ((row16 & 7) * kProw + 8 * grp) * 2;
+
+  f32x4 oacc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) oacc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_ref[G], lsum[G];
+#pragma unroll
+  for (int i = 0; i < G; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; }
+
+  auto two_batches = [&](const int bi0, uint8_t* __restrict__ const va, uint8_t* __restrict__ const vb,
+                         uint8_t* __restrict__ const pb) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      if (half == 1 && bi0 + 1 >= nb) break;
+      const int bi = bi0 + half;
+      uint8_t* const vcur = half ? vb : va;
+      uint8_t* const vnext = half ? va : vb;
+      __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): batch bi has landed (K registers, V in LDS)
+      // ---- logits ----
+      f32x4 dq[2];
+#pragma unroll
+      for (int pg = 0; pg < 2; ++pg) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) acc = mfma16<DT>(a_q[kk], kreg[pg][kk], acc);
+        dq[pg] = acc;
+      }
+      // the next batch: K into the registers just consumed, V into the other buffer (unconditional:
+      // the last iteration re-fetches its own batch, which the caches absorb)
+      {
+        const int a = __builtin_amdgcn_readlane(pid_nx, 0), c = __builtin_amdgcn_readlane(pid_nx, 1);
+        KV16_LOAD_K(a, c)
+        KV16_DMA_V(a, c, vnext)
+        pid_nx = load_pids(min(bi + 2, nb - 1));
+      }
+      // ---- gather: lanes 0..15 = tokens of page 0, 16..31 = page 1, registers = heads ----
+      float lg[G];
+      const int tok = t_begin + 32 * bi + (lane & 31);
+      const bool valid = lane < 32 && tok < t_end;
+      bool need = false;
+#pragma unroll
+      for (int i = 0; i < G; ++i) {
+        float hi, lo;
+        swap16(dq[0][i], dq[1][i], hi, lo);                  // hi: rows (p0.hi, p1.hi, ..), lo: rows (p0.lo, p1.lo, ..)
+        lg[i] = valid ? hi + lo : -INFINITY;
+        need |= lg[i] > m_ref[i] + kLazyTau;
+      }
+      if (__any(need)) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+          float mx = row_allmax(lg[i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          const float mnew = fmaxf(m_ref[i], mx);
+          const float alpha = fast_exp2(m_ref[i] - mnew);
+          lsum[i] *= alpha;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) oacc[c][i] *= alpha;
+          m_ref[i] = mnew;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < G; ++i) {
+        const float pr = fast_exp2(lg[i] - m_ref[i]);          // 0 for masked tokens and idle lanes
+        lsum[i] += pr;
+        uint32_t h16, l16;
+        split16<DT>(pr, h16, l16);
+        if (lane < 32) {
+          ((uint16_t*)pb)[i * kProw + lane] = (uint16_t)h16;
+          ((uint16_t*)pb)[(4 + i) * kProw + lane] = (uint16_t)l16;
+        }
+      }
+      wave_sync();
+      // ---- O[row][channel] += P (rows x 32 tokens) . V ----
+      u32x4 pa;
+      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(pa) : "v"(pa_addr) : "memory");
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int voff = vr_base + 32 * (c ^ v_rho);
+        const i16x4 t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS i16x4*)(vcur + voff));
+        const i16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS i16x4*)(vcur + voff + 4 * kRowBytes));
+        const u32x4 bv = u32x4{(uint32_t)(uint16_t)t0[0] | ((uint32_t)(uint16_t)t0[1] << 16),
+                               (uint32_t)(uint16_t)t0[2] | ((uint32_t)(uint16_t)t0[3] << 16),
+                               (uint32_t)(uint16_t)t1[0] | ((uint32_t)(uint16_t)t1[1] << 16),
+                               (uint32_t)(uint16_t)t1[2] | ((uint32_t)(uint16_t)t1[3] << 16)};
+        oacc[c] = mfma16<DT>(pa, bv, oacc[c]);
+      }
+      wave_sync();                                           // P is rewritten by the next batch
+    }
+  };
+  for (int bi = 0; bi < nb; bi += 2) two_batches(bi, vbuf_a, vbuf_b, pbuf);
+  __builtin_amdgcn_s_waitcnt(0x0F70);                        // the trailing re-fetch has landed
+
+  // ---- epilogue ----
+#pragma unroll
+  for (int i = 0; i < G; ++i) {
+    lsum[i] = row_allsum(lsum[i]);
+    lsum[i] += __shfl_xor(lsum[i], 16, 64);
+    lsum[i] += __shfl_xor(lsum[i], 32, 64);
+  }
+  // oacc[c][i] of lane (grp, row16) = O[row 4 grp + i][channel 16c + row16]: rows 0..3 (grp 0) hi, 4..7 (grp 1) lo
+  const bool writer = grp == 0;
+#pragma unroll
+  for (int i = 0; i < G; ++i) {
+    const int head = kvh * G + i;
+    float* part = p.ws + (((int64_t)b * p.n_q_heads + head) * p.num_splits + split) * (D + 2);
+    const float inv = 1.0f / lsum[i];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float o = oacc[c][i] + __shfl_down(oacc[c][i], 16, 64);
+      if (writer) {
+        if (p.num_splits == 1)
+          store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + head) * D + 16 * c + row16, o * inv);
+        else
+          part[2 + 16 * c + row16] = o;
+      }
+    }
+    if (p.num_splits != 1 && writer && row16 == 0) { part[0] = m_ref[i]; part[1] = lsum[i]; }
+  }
+}
+
+#undef KV16_LOAD_K
+#undef KV16_DMA_V
+
+// head_dim 128, group size <= 4; returns false when this kernel does not cover the case.
+bool launch_decode_kv16_mfma(const DecodeParams& p, int G, int kv_dtype, dim3 grid, hipStream_t st) {
+#define KV16_GO(GG)                                                                              \
+  if (kv_dtype == SAW_BF16) decode_kv16_mfma_kernel<GG, SAW_BF16><<<grid, dim3(64), 0, st>>>(p); \
+  else decode_kv16_mfma_kernel<GG, SAW_F16><<<grid, dim3(64), 0, st>>>(p);
+  switch (G) {
+    case 1: KV16_GO(1) return true;
+    case 2: KV16_GO(2) return true;
+    case 4: KV16_GO(4) return true;
+    default: return false;
+  }
+#undef KV16_GO
+}
+
+}  // namespace saw

@@ -27,109 +27,9 @@
 // When one partition covers the sequence the kernel also normalises, rotates the output back and
 // writes it (no merge launch), and it can append the step's new token itself (append_token).
 #include "saw_decode.h"
+#include "saw_wave_util.h"
 
 namespace saw {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-#define LDS_AS __attribute__((address_space(3)))
-#define GLOBAL_AS __attribute__((address_space(1)))
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// Eight packed nibbles -> eight bf16 values 128 + c, in k-order (n0, n4, n1, n5, n2, n6, n3, n7).
-// `k` holds 0x43004300 in a VGPR (see bf16_bias()), which lets each mask-and-bias be one
-// v_and_or_b32 with a single scalar operand.
-__device__ __forceinline__ bf16x8 unpack8(uint32_t w, uint32_t k) {
-  u32x4 r;
-  r.x = (w & 0x000F000Fu) | k;
-  r.y = ((w >> 4) & 0x000F000Fu) | k;
-  r.z = ((w >> 8) & 0x000F000Fu) | k;
-  r.w = ((w >> 12) & 0x000F000Fu) | k;
-  return as_bf16x8(r);
-}
-__device__ __forceinline__ uint32_t bf16_bias() {
-  uint32_t k;
-  asm volatile("v_mov_b32 %0, 0x43004300" : "=v"(k));
-  return k;
-}
-
-__device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-// x = hi + lo with hi a truncated bf16 and lo a rounded bf16 of the remainder.
-__device__ __forceinline__ void split_bf16(float x, uint32_t& hi16, uint32_t& lo16, float& sum) {
-  const uint32_t u = __float_as_uint(x);
-  const float hf = __uint_as_float(u & 0xffff0000u);
-  hi16 = u >> 16;
-  uint32_t r = __float_as_uint(x - hf);
-  r += 0x7fffu + ((r >> 16) & 1u);
-  lo16 = r >> 16;
-  sum = hf + __uint_as_float(r & 0xffff0000u);
-}
-
-// v_permlane16_swap: x <- rows (a0, b0, a2, b2), y <- rows (a1, b1, a3, b3)   (row = 16 lanes)
-__device__ __forceinline__ void swap16(float a, float b, float& x, float& y) {
-  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  x = __uint_as_float(r[0]);
-  y = __uint_as_float(r[1]);
-}
-// v_permlane32_swap: x <- rows (a0, a1, b0, b1), y <- rows (a2, a3, b2, b3)
-__device__ __forceinline__ void swap32(float a, float b, float& x, float& y) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  x = __uint_as_float(r[0]);
-  y = __uint_as_float(r[1]);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-  return __uint_as_float(__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, false));
-}
-// max over the 16 lanes of each row (rotations by 1, 2, 4, 8)
-__device__ __forceinline__ float row_allmax(float v) {
-  v = fmaxf(v, dpp_f<0x121>(v));
-  v = fmaxf(v, dpp_f<0x122>(v));
-  v = fmaxf(v, dpp_f<0x124>(v));
-  v = fmaxf(v, dpp_f<0x128>(v));
-  return v;
-}
-__device__ __forceinline__ float row_allsum(float v) {
-  v += dpp_f<0x121>(v);
-  v += dpp_f<0x122>(v);
-  v += dpp_f<0x124>(v);
-  v += dpp_f<0x128>(v);
-  return v;
-}
-
-// The block is one wavefront: LDS operations of a wave execute in order, so exchanging data
-// between lanes through LDS needs no barrier and no wait, only a point the compiler will not
-// move memory accesses across.  (A workgroup barrier would also wait for every LDS-DMA transfer
-// in flight, which is exactly what the prefetch must not do.)
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// In-place un-normalised block Walsh-Hadamard transform of n_vec vectors of 128 floats in LDS,
-// run by one wavefront.
-__device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int lane) {
-  for (int st = 1; st < h; st <<= 1) {
-    for (int idx = lane; idx < n_vec * 64; idx += 64) {
-      const int v = idx >> 6, r = idx & 63;
-      const int i = v * 128 + (r / st) * 2 * st + (r % st);
-      const float a = x[i], c = x[i + st];
-      x[i] = a + c;
-      x[i + st] = a - c;
-    }
-    wave_sync();
-  }
-}
 
 constexpr int kTileBytes = 1024;               // one (page, head) code tile: 16 tokens x 64 B
 constexpr int kProw = 72;                      // P row stride in bf16 (64 tokens + 8 pad: conflict-free b128 reads)

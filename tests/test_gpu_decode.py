@@ -142,10 +142,12 @@ def test_kv16_comparison_path(saw, dtype, Hq, Hkv, d):
         K, V = synth.gen_kv(w, b, 0, L)
         saw.kv16_store(kc, K.cuda(), V.cuda(), pt, torch.from_numpy(synth.slots_for(b, 0, L)).cuda())
     q = synth.gen_q(w)
-    o = saw.kv16_paged_decode_attn(kc, q.cuda(), pt, torch.from_numpy(w.seq_lens).cuda(), num_splits=2)
-    torch.cuda.synchronize()
     o_ref = O.kv16_paged_decode_attn(kc.k_pages.float().cpu().numpy(), kc.v_pages.float().cpu().numpy(),
                                      q.float().numpy(), w.page_table, w.seq_lens)
-    err = parity.attn_error(o.cpu().numpy(), o_ref)
-    print(f"[kv16 {dtype} Hq={Hq}/{Hkv} d={d}] err={err:.2e}", flush=True)
-    assert err < TOL
+    for splits in (2, 1, 0):
+        o = torch.full((w.batch, Hq, d), float("nan"), device="cuda")
+        saw.kv16_paged_decode_attn(kc, q.cuda(), pt, torch.from_numpy(w.seq_lens).cuda(), num_splits=splits, out=o)
+        torch.cuda.synchronize()
+        err = parity.attn_error(o.cpu().numpy(), o_ref)
+        print(f"[kv16 {dtype} Hq={Hq}/{Hkv} d={d} splits={splits}] err={err:.2e}", flush=True)
+        assert err < TOL
