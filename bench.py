@@ -145,8 +145,12 @@ def store_sweep(saw, dev, iters=30, warmup=5):
                 continue
             cache = saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, 3, device=dev)
             med, mean, p10, p90 = time_calls(lambda: saw.rotate_quant_store(cache, K, V, pt, sl), iters, warmup)
+            # sanity column: quantisation error of K against the unquantised input (read back, rotated back)
+            kq, _ = saw.flatten_dequant(cache, pt, 0, 0, T, unrotate=True, out_dtype=torch.float32, want_v=False)
+            mse = float(((kq - K.float()) ** 2).mean())
+            del kq
             res[f"h{h}"] = {"us": round(med, 2), "Gtok_s": round(T / med / 1e3, 4),
-                            "GB_s": round(store_bytes(base, T) / med / 1e3, 1)}
+                            "GB_s": round(store_bytes(base, T) / med / 1e3, 1), "k_mse": float(f"{mse:.4e}")}
             del cache
         plain = res["h1"]["us"]
         for k, v in res.items():
@@ -226,7 +230,9 @@ def other_decode(saw, dev, name, iters=32, warmup=8, **over):
         saw.paged_decode_attn(c, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
 
     med, mean, p10, p90 = time_calls(call, iters, warmup)
+    overhead = 2 * w.batch * w.n_q_heads * splits * (w.head_dim + 2) * 4 if splits > 1 else 0
     return {"batch": w.batch, "tokens_cached": int(lens.sum()), "splits": splits, "cache_copies_rotated": len(copies),
+            "split_partials_bytes_written_and_read": overhead,
             "us": round(med, 2), "p10_us": round(p10, 2), "p90_us": round(p90, 2),
             "GB_s": round(nbytes / med / 1e3, 1), "pct_of_hbm_peak": round(nbytes / med / 1e3 / HBM_PEAK_GBS * 100, 2)}
 
@@ -419,6 +425,15 @@ def main():
         ex["box_copy_ceiling"] = {"GB_s": round(ceiling, 1), "pct_of_hbm_peak": round(ceiling / HBM_PEAK_GBS * 100, 2),
                                   "decode_pct_of_ceiling": round(achieved / ceiling * 100, 2),
                                   "what": "1 GiB device-to-device copy, read + written bytes per second"}
+        w2 = synth.make_workload("llama8b")
+        c2 = saw.Cache(w2.num_pages, w2.n_kv_heads, w2.head_dim, w2.had_block, w2.rotate_mask, device=dev)
+        K2 = torch.cat([synth.gen_kv(w2, b, 4096, 4097, device=dev)[0] for b in range(w2.batch)])
+        V2 = torch.cat([synth.gen_kv(w2, b, 4096, 4097, device=dev)[1] for b in range(w2.batch)])
+        pt2 = torch.from_numpy(w2.page_table).to(dev)
+        sl2 = torch.from_numpy(np.stack([np.arange(w2.batch, dtype=np.int32), np.full(w2.batch, 4096, np.int32)], 1)).to(dev)
+        med, mean, p10, p90 = time_calls(lambda: saw.rotate_quant_store(c2, K2, V2, pt2, sl2), 50, 5)
+        ex["llama8b_store_16_new_tokens_us"] = round(med, 2)          # launch-latency dominated
+        del c2
         ex["other_decode"] = {
             "highconc_uniform2304": other_decode(saw, dev, "highconc", ctx=2304),
             "llama8b": other_decode(saw, dev, "llama8b"),
