@@ -24,6 +24,7 @@ struct DecodeParams {
   const void* v_new;
   int32_t kv_new_dtype, append;
   int32_t len_bias;     // added to every seq_lens entry (1 when a separate store launch appended a token)
+  int32_t sorted;           // d = 128 path, one block per (sequence, kv head): block z takes the sequence of length rank z
   int32_t pair;             // d = 128 path: two-wavefront blocks over (long, short) sequence pairs
   int32_t batch;
   int32_t waves_per_item;   // d = 128 path: wavefronts sharing one partition (1, 2 or 4)

@@ -489,8 +489,24 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.append = k_new != nullptr;
   p.len_bias = len_bias;
   p.batch = B;
-  p.pair = !kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
-           (int64_t)B * c->n_kv_heads > 256 && B <= 1024;
+  // How the d = 128 INT4 kernel hands out work when one partition covers each sequence and the
+  // batch provides more (sequence, kv head) items than compute units (and at most 16 lengths per
+  // lane for the in-kernel ranking).  A compute unit holds 8 wavefronts of this kernel, 2048 on
+  // the chip:
+  //   * up to 2048 items everything is resident at once and nothing rebalances later, so the
+  //     work is evened out up front: pair mode (two-wavefront blocks over (long, short) pairs);
+  //   * beyond that blocks queue for slots in index order, which is list scheduling: one
+  //     wavefront per item, sequences taken longest first, so the launch ends on the shortest.
+  //     (Measured at 288..512 sequences x 8 heads: 173-270 us against 224-332 us in pair mode,
+  //     whose equal blocks make the last round as long as the others; 2 or 4 wavefronts per item
+  //     were never better.)
+  p.pair = 0;
+  p.sorted = 0;
+  if (!kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
+      (int64_t)B * c->n_kv_heads > 256 && B <= 1024) {
+    if ((int64_t)((B + 1) / 2) * c->n_kv_heads <= 1024) p.pair = 1;
+    else p.sorted = 1;
+  }
   return launch_decode(p, B, c->head_dim, Hq / c->n_kv_heads, kv16, kv_dtype, st);
 }
 

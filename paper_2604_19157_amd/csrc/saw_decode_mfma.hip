@@ -340,6 +340,13 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       }
     }
     wave_sync();                                        // the histogram lived in kbuf
+  } else if (p.sorted) {
+    // one block per (sequence, kv head), more blocks than fit the chip at once: blocks are dispatched
+    // in index order as earlier ones finish, so taking the sequences longest first leaves the
+    // shortest for the end of the launch
+    const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
+    sg_b[0] = seq_of_rank(p, p.batch, lane, lc, blockIdx.z);
+    wave_sync();
   }
 
   const int row16 = lane & 15, grp = lane >> 4;

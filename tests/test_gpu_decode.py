@@ -84,11 +84,11 @@ def test_ragged_lengths_with_empty_and_single(saw):
     assert not o[0].any()                                           # empty sequence -> zero row
 
 
-@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2)])
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (300, 8)])
 def test_many_sequences_balanced_item_order(saw, B, Hkv):
-    """More (sequence, kv head) items than compute units: the kernel deals items out longest first.
-    Every sequence is compared, so an item served twice or never shows up; lengths include empty
-    sequences and many ties."""
+    """More (sequence, kv head) items than compute units: the kernel pairs long with short sequences
+    (everything resident at once) or, beyond 2048 items, takes them longest first.  Every sequence is
+    compared, so an item served twice or never shows up; lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)
     lens[rng.integers(0, B, size=B // 5)] = 64                      # ties
