@@ -48,12 +48,13 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n16 = lane & 15, rg = lane >> 4;
-  const int kind = blockIdx.y * 4 + wave;                     // (K|V, head)
+  const int kind = blockIdx.x * 4 + wave;                     // (K|V, head)
   if (kind >= 2 * p.n_kv_heads) return;
   const int which = kind >= p.n_kv_heads ? 1 : 0;
   const int head = kind - which * p.n_kv_heads;
   if (p.out[which] == nullptr) return;
-  const int lp = p.first_page + blockIdx.x;                   // logical page of the sequence
+  const int lp = p.first_page + blockIdx.z * 65535 + blockIdx.y;   // logical page of the sequence
+  if (16 * lp >= p.pos_end) return;
   const int pid = p.page_table[lp];
   if (pid < 0 || pid >= p.num_pages) return;                  // unmapped page: nothing written
   const bool unrot = p.unrot[which] != 0;
@@ -182,7 +183,9 @@ int launch_flatten(const saw_cache_t* c, const int32_t* pt_row, int32_t pos_begi
   p.unrot[0] = rot && (c->rotate_mask & SAW_ROT_K);
   p.unrot[1] = rot && (c->rotate_mask & SAW_ROT_V);
   const int n_pages = (pos_end + 15) / 16 - p.first_page;
-  dim3 grid(n_pages, (2 * c->n_kv_heads + 3) / 4), block(256);
+  // (K|V, head) groups vary fastest, so blocks that run together write neighbouring pieces of the
+  // same token rows
+  dim3 grid((2 * c->n_kv_heads + 3) / 4, n_pages < 65535 ? n_pages : 65535, (n_pages + 65534) / 65535), block(256);
 #define SAW_FLAT(DD)                                                                              \
   switch (out_dtype) {                                                                            \
     case SAW_BF16: flatten_dequant_kernel<DD, SAW_BF16><<<grid, block, 0, st>>>(p); break;         \
