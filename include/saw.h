@@ -7,9 +7,10 @@
  *   2. saw_paged_decode_attn: one decode step o = softmax(q K^T / sqrt(d)) V read
  *      straight from the INT4 pages, with q rotated instead of un-rotating K and the
  *      output rotated back once for V.
- * plus saw_dequant_pages (fp32 read-back for inspection), saw_flatten_dequant (the
- * prefill-side read-back into dense 16-bit buffers), and a 16-bit-KV paged decode
- * (saw_kv16_*) that serves as the same-run unquantised comparison.
+ * plus saw_append_decode_attn (both stages of a decode step in one call, one kernel launch
+ * for large batches), saw_flatten_dequant (the prefill-side read-back into dense 16-bit
+ * buffers), saw_dequant_pages (fp32 read-back for inspection), and a 16-bit-KV paged
+ * decode (saw_kv16_*) that serves as the same-run unquantised comparison.
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller; the library never
