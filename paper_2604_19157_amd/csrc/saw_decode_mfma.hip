@@ -192,27 +192,44 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
 }
 
 // Longest-first order of the batch's sequences, derived by every block from the same seq_lens:
-// rank by (64 length classes, sequence index).  `build` makes the class histogram in LDS and
-// its prefix sums across lanes (lane c owns class c, class 0 = longest); `seq_of_rank` finds
-// the sequence at a rank with two ballots per 64 sequences.
+// rank by (64 length classes, sequence index).  `build` reads the lengths once (all loads issued
+// together: one memory latency), leaves them clamped in LDS, makes the class histogram and its
+// prefix sums across lanes (lane c owns class c, class 0 = longest); `seq_of_rank` finds the
+// sequence at a rank with two ballots per 64 sequences, from the lengths in LDS.
+// LDS scratch: 64 + B ints, B <= kMaxRanked.
+constexpr int kMaxRanked = 1024;
 struct LenClasses {
   int cnt, start, incl;      // this lane's class: members, ranks [start, incl)
   float kscale;
   int V;                     // ceil(B / 64)
+  const int* lens;           // LDS: the clamped lengths
 };
-__device__ __forceinline__ int len_class(const DecodeParams& p, int idx, float kscale) {
-  const int nb = (min(p.seq_lens[idx] + p.len_bias, p.bound) + 63) >> 6;
-  return 63 - (int)((float)max(nb, 0) * kscale);
+__device__ __forceinline__ int len_class(int len, float kscale) {
+  return 63 - (int)((float)((len + 63) >> 6) * kscale);
 }
-__device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* hist) {
+__device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* scratch) {
   LenClasses lc;
   lc.kscale = 63.0f / (float)((p.bound + 63) >> 6);
   lc.V = (B + 63) >> 6;
+  int* const hist = scratch;
+  int* const lens = scratch + 64;
+  lc.lens = lens;
+  int mine[kMaxRanked / 64];
+#pragma unroll
+  for (int v = 0; v < kMaxRanked / 64; ++v) {
+    const int idx = 64 * v + lane;
+    mine[v] = (idx < B) ? p.seq_lens[idx] : 0;
+  }
   hist[lane] = 0;
   wave_sync();
-  for (int v = 0; v < lc.V; ++v) {
+#pragma unroll
+  for (int v = 0; v < kMaxRanked / 64; ++v) {
     const int idx = 64 * v + lane;
-    if (idx < B) atomicAdd(&hist[len_class(p, idx, lc.kscale)], 1);
+    if (idx < B) {
+      const int len = max(min(mine[v] + p.len_bias, p.bound), 0);
+      lens[idx] = len;
+      atomicAdd(&hist[len_class(len, lc.kscale)], 1);
+    }
   }
   wave_sync();
   lc.cnt = hist[lane];
@@ -226,14 +243,14 @@ __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, i
   lc.start = incl - lc.cnt;
   return lc;
 }
-__device__ __forceinline__ int seq_of_rank(const DecodeParams& p, int B, int lane, const LenClasses& lc, int srank) {
+__device__ __forceinline__ int seq_of_rank(int B, int lane, const LenClasses& lc, int srank) {
   const unsigned long long hit = __ballot(srank >= lc.start && srank < lc.incl);   // exactly one class
   const int cls = __ffsll((long long)hit) - 1;
   int o = srank - __builtin_amdgcn_readlane(lc.start, cls);                        // index inside the class
   int found = 0;
   for (int v = 0; v < lc.V; ++v) {
     const int idx = 64 * v + lane;
-    const bool in = idx < B && len_class(p, idx, lc.kscale) == cls;
+    const bool in = idx < B && len_class(lc.lens[min(idx, B - 1)], lc.kscale) == cls;
     const unsigned long long mask = __ballot(in);
     const int c = __popcll(mask);
     if (o < c) {
@@ -305,10 +322,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     const int r_long = blockIdx.z, r_short = B - 1 - r_long;
     const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
-    const int b_long = seq_of_rank(p, B, lane, lc, r_long);
-    const int b_short = self ? b_long : seq_of_rank(p, B, lane, lc, r_short);
-    const int l_long = max(min(p.seq_lens[b_long] + p.len_bias, p.bound), 0);
-    const int l_short = self ? 0 : max(min(p.seq_lens[b_short] + p.len_bias, p.bound), 0);
+    const int b_long = seq_of_rank(B, lane, lc, r_long);
+    const int b_short = self ? b_long : seq_of_rank(B, lane, lc, r_short);
+    const int l_long = lc.lens[b_long];
+    const int l_short = self ? 0 : lc.lens[b_short];
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
     // wavefront 1 pays a second prologue when the long sequence is shared: one batch in its favour
     const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
@@ -339,13 +356,13 @@ void decode_int4_mfma_kernel(DecodeParams p) {
         ++nseg;
       }
     }
-    wave_sync();                                        // the histogram lived in kbuf
+    wave_sync();                                        // the ranking's scratch lived in kbuf (and on into vbuf_a)
   } else if (p.sorted) {
     // one block per (sequence, kv head), more blocks than fit the chip at once: blocks are dispatched
     // in index order as earlier ones finish, so taking the sequences longest first leaves the
     // shortest for the end of the launch
     const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
-    sg_b[0] = seq_of_rank(p, p.batch, lane, lc, blockIdx.z);
+    sg_b[0] = seq_of_rank(p.batch, lane, lc, blockIdx.z);
     wave_sync();
   }
 
@@ -466,10 +483,17 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }                                                                                           \
   }
 
-  // ---- the q~ operands, then the first transfers ----
-  // (q~ first: its LDS scratch traffic would otherwise be made to wait for the transfers by the
-  // compiler's conservative LDS-DMA ordering; the query loads were issued further up, so this
-  // costs about a microsecond per block before the first transfer leaves)
+  // ---- the first transfers, then the q~ operands ----
+  // The first batch's tiles leave as soon as the page ids are here, so that their trip overlaps the
+  // wait for the query and the q~ preparation (whose LDS scratch is other buffers: the compiler's
+  // conservative LDS-DMA ordering makes that scratch traffic wait until the transfers have landed,
+  // which costs nothing while the query itself is still on its way).
+  if (nb > 0) {
+    // issued unconditionally: a wavefront without a batch of its own shadows the last batch
+    const int first = min(first_batch, nb - 1);
+    SAW_FETCH_V(first, vbuf_a, mbuf_a)
+    SAW_FETCH_K(first, kbuf)
+  }
   u32x4 a_q[4];
   float qsum[NH];
   float qmul;
@@ -494,14 +518,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
   if (takes_new)
     append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (const float*)vbuf_b, qmul,
-                        (float*)kbuf, oacc, m_ref, lsum);
-
-  if (nb > 0) {
-    // issued unconditionally: a wavefront without a batch of its own shadows the last batch
-    const int first = min(first_batch, nb - 1);
-    SAW_FETCH_V(first, vbuf_a, mbuf_a)
-    SAW_FETCH_K(first, kbuf)
-  }
+                        (float*)pbuf, oacc, m_ref, lsum);
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.
