@@ -121,10 +121,11 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
     const uint8_t* k0 = kpages + (int64_t)(pid0) * page_stride + head_off + row16 * kRowBytes + 16 * grp; \
     const uint8_t* k1 = kpages + (int64_t)(pid1) * page_stride + head_off + row16 * kRowBytes + 16 * grp; \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                           \
-      kreg[0][kk] = *(const u32x4*)(k0 + 64 * kk);                                               \
-      kreg[1][kk] = *(const u32x4*)(k1 + 64 * kk);                                               \
+      kreg[0][kk] = __builtin_nontemporal_load((const u32x4*)(k0 + 64 * kk));                    \
+      kreg[1][kk] = __builtin_nontemporal_load((const u32x4*)(k1 + 64 * kk));                    \
     }                                                                                            \
   }
+  // (all K and V reads are marked streaming, cache policy "nt", as in the INT4 kernel)
   // V tiles of a batch into VDST: transfer j covers token rows 4j .. 4j+3 (1 KiB of LDS); the lane
   // at chunk position c of row r brings source chunk c ^ (2 (r & 3))
   const int v_r4 = lane >> 4;                                        // row inside the transfer
@@ -135,9 +136,9 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
     const uint8_t* v1 = vpages + (int64_t)(pid1) * page_stride + head_off + v_src;               \
     _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                              \
       __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(v0 + j * 4 * kRowBytes),          \
-                                       (LDS_AS void*)(VDST + j * 1024), 16, 0, 0);               \
+                                       (LDS_AS void*)(VDST + j * 1024), 16, 0, 2);               \
       __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(v1 + j * 4 * kRowBytes),          \
-                                       (LDS_AS void*)(VDST + 4096 + j * 1024), 16, 0, 0);        \
+                                       (LDS_AS void*)(VDST + 4096 + j * 1024), 16, 0, 2);        \
     }                                                                                            \
   }
   int pid_nx;                                                        // ids of the batch after the one in flight

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     const int off = r * 1024 + 16 * lane;                      // byte offset in the dense 16 x D tile
     const int tok = off / ROWB, x = (off % ROWB) / 16;
     const int64_t t = min(t0 + tok, p.T - 1);                  // tokens past the end shadow the last one; never stored
-    ld[r] = *(const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * D + 8 * x);
+    // (the input is read once and the cache written once: both are marked streaming, "nt")
+    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * D + 8 * x));
   }
   // this lane's token (column n16 of the tile) and where it goes
   const int64_t t_mine = t0 + n16;
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (lane < 16 * (D / 2) / 16)
-      *(u32x4*)(p.codes[which] + vec0 * (D / 2) + 16 * lane) = *(const u32x4*)(stage + 16 * lane);
+      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(p.codes[which] + vec0 * (D / 2) + 16 * lane));
     if (rg == 0) *(float2*)(p.meta[which] + (vec0 + n16) * 2) = make_float2(s_store, z_store);
     return;
   }
