@@ -19,6 +19,7 @@ HIPCC_FLAGS = [
 EXTRA_FLAGS = {
     # MFMA results stay in ordinary VGPRs (no accumulator-register copies around the matrix ops)
     "saw_store_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "saw_flatten.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

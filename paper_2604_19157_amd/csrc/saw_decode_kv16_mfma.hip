@@ -185,9 +185,8 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
         for (int kk = 0; kk < 4; ++kk) acc = mfma16<DT>(a_q[kk], kreg[pg][kk], acc);
         dq[pg] = acc;
       }
-      // the next batch: K into the registers just consumed, V into the other buffer (unconditional:
-      // the last iteration re-fetches its own batch, which the caches absorb)
-      {
+      // the next batch, if there is one: K into the registers just consumed, V into the other buffer
+      if (bi + 1 < nb) {
         const int a = __builtin_amdgcn_readlane(pid_nx, 0), c = __builtin_amdgcn_readlane(pid_nx, 1);
         KV16_LOAD_K(a, c)
         KV16_DMA_V(a, c, vnext)
@@ -249,7 +248,7 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
     }
   };
   for (int bi = 0; bi < nb; bi += 2) two_batches(bi, vbuf_a, vbuf_b, pbuf);
-  __builtin_amdgcn_s_waitcnt(0x0F70);                        // the trailing re-fetch has landed
+  __builtin_amdgcn_s_waitcnt(0x0F70);                        // nothing this wavefront requested is still on its way
 
   // ---- epilogue ----
 #pragma unroll

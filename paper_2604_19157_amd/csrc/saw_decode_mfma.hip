@@ -546,13 +546,14 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) kw[q] = *(const u32x4*)(kb + q * kTileBytes + kr_off);
     __builtin_amdgcn_s_waitcnt(0xC07F);                    // lgkmcnt(0): ... and they have returned: kb is free
-    // The next batch is fetched unconditionally (the last iteration re-fetches its own batch,
-    // which the caches absorb): a fetch under a branch would make the number of transfers in
-    // flight path-dependent and force conservative vmcnt(0) waits further down.  vnext was last
-    // read two batches ago.
+    // The next batch of this wavefront, if it has one (the branch is wavefront-uniform and the
+    // wait at the top of a batch is a full vmcnt(0), so the number of transfers in flight may
+    // depend on the path).  vnext was last read two batches ago.
     const int nxt = min(bi + STEP, my_last);
-    SAW_FETCH_V(nxt, vnext, mnext)
-    SAW_FETCH_K(nxt, kb)
+    if (bi + STEP <= my_last) {
+      SAW_FETCH_V(nxt, vnext, mnext)
+      SAW_FETCH_K(nxt, kb)
+    }
 
     // ---- logits: D_q[head][token of page q] ----
     f32x4 dq[4];
@@ -662,9 +663,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     if (bi + STEP < nb) body(bi + STEP, kbuf, vbuf_b, vbuf_a, pbuf, mbuf_b, mbuf_a);
   }
 
-  // The last iteration re-fetched its own batch into kbuf and one of the V buffers.  Everything
-  // below reuses those buffers as scratch, so that transfer has to have landed first: without this
-  // wait it can arrive after the scratch has been written and overwrite it.
+  // A wavefront without a batch of its own (first_batch >= nb) still has the prologue's transfers of
+  // the last batch in flight.  Everything below reuses those buffers as scratch, so they have to
+  // have landed first: without this wait a transfer can arrive after the scratch has been written
+  // and overwrite it.
   __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
 
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----

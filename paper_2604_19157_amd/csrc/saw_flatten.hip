@@ -18,7 +18,8 @@
 //     first channel of every block and 0 elsewhere, so a large zero-point cancels exactly
 //     instead of through rounding;
 //   * a lane ends up with eight contiguous output channels of one token for every 32-channel
-//     group: one 16-byte (bf16 / fp16) or two 16-byte (fp32) stores each.
+//     group; 16-bit outputs are regrouped through LDS so that a store instruction writes whole
+//     token rows (4 x 256 B for d = 128), fp32 outputs go out as two 16-byte stores per group.
 #include "saw_common.h"
 
 namespace saw {
@@ -26,6 +27,9 @@ namespace saw {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 struct FlattenParams {
   const uint8_t* codes[2];
@@ -60,6 +64,7 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   const bool unrot = p.unrot[which] != 0;
 
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][16 * RB];
+  __shared__ __attribute__((aligned(16))) uint8_t otile_all[(ODT == SAW_F32) ? 1 : 4][(ODT == SAW_F32) ? 16 : 16 * 2 * D];   // 16-bit outputs: a tile of output rows
   uint8_t* const stage = stage_all[wave];
 
   const uint8_t* tile = p.codes[which] + ((int64_t)pid * p.n_kv_heads + head) * (16 * RB);
@@ -138,32 +143,68 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   const float zoff = (sz.y + 128.0f) * (float)h;
   const float sc = sz.x * (unrot ? had_norm(p.had_block) : 1.0f);
   const int pos = 16 * lp + n16;
-  if (pos < p.pos_begin || pos >= p.pos_end) return;
-  const int64_t obase = (int64_t)(pos - p.pos_begin) * p.token_stride + head * D;
+  // Channel 32a + 8rg + i carries the zero-point term iff it is the first of its Hadamard block:
+  // every channel when nothing is rotated back (h = 1), otherwise only i = 0 can be.
+  if (ODT == SAW_F32) {
+    if (pos < p.pos_begin || pos >= p.pos_end) return;
+    const int64_t obase = (int64_t)(pos - p.pos_begin) * p.token_stride + head * D;
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+      float o[8];
+      if (h == 1) {                                            // wavefront-uniform
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = sc * (y[8 * a + i] - zoff);
+      } else {
+        const bool first = ((32 * a + 8 * rg) & (h - 1)) == 0;
+        o[0] = sc * (y[8 * a] - (first ? zoff : 0.0f));
+#pragma unroll
+        for (int i = 1; i < 8; ++i) o[i] = sc * y[8 * a + i];
+      }
+      float* dst = (float*)p.out[which] + obase + 32 * a + 8 * rg;
+      *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
+      *(f32x4*)(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+    }
+    return;
+  }
+  // 16-bit outputs: the tile's rows (one token's D values = 2 D bytes, contiguous in the output) are
+  // put together in LDS, chunk c of row r at position c ^ (r & (NC - 1)), so that every store
+  // instruction writes whole rows: 64 lanes x 16 bytes = 1 KiB = 1024 / (2 D) token rows.
+  constexpr int NC = D / 8;                                    // 16-byte chunks per output row (16 | 8)
+  constexpr int RPI = 64 / NC;                                 // rows per store instruction (4 | 8)
+  uint8_t* const orow = otile_all[wave];
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
     float o[8];
+    if (h == 1) {                                              // wavefront-uniform
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int ch = 32 * a + 8 * rg + i;
-      const bool carries = (ch & (h - 1)) == 0;
-      o[i] = sc * (carries ? y[8 * a + i] - zoff : y[8 * a + i]);
-    }
-    const int64_t e = obase + 32 * a + 8 * rg;
-    if (ODT == SAW_F32) {
-      float* dst = (float*)p.out[which] + e;
-      *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
-      *(f32x4*)(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+      for (int i = 0; i < 8; ++i) o[i] = sc * (y[8 * a + i] - zoff);
     } else {
-      uint32_t w4[4];
+      const bool first = ((32 * a + 8 * rg) & (h - 1)) == 0;
+      o[0] = sc * (y[8 * a] - (first ? zoff : 0.0f));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t lo = (ODT == SAW_BF16) ? f32_to_bf16(o[2 * i]) : f32_to_f16(o[2 * i]);
-        const uint32_t hi = (ODT == SAW_BF16) ? f32_to_bf16(o[2 * i + 1]) : f32_to_f16(o[2 * i + 1]);
-        w4[i] = lo | (hi << 16);
-      }
-      *(u32x4*)((uint16_t*)p.out[which] + e) = u32x4{w4[0], w4[1], w4[2], w4[3]};
+      for (int i = 1; i < 8; ++i) o[i] = sc * y[8 * a + i];
     }
+    // round-to-nearest-even pairs: v_cvt_pk_bf16_f32, or two v_cvt_f16_f32 and a pack
+    uint32_t w4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x2 pr = f32x2{o[2 * i], o[2 * i + 1]};
+      if (ODT == SAW_BF16) w4[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+      else w4[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, f16x2));
+    }
+    const int c = 4 * a + rg;
+    *(u32x4*)(orow + n16 * (2 * D) + 16 * (c ^ (n16 & (NC - 1)))) = u32x4{w4[0], w4[1], w4[2], w4[3]};
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int j = 0; j < 16 / RPI; ++j) {
+    const int r = RPI * j + lane / NC, c = lane % NC;
+    const int rpos = 16 * lp + r;
+    const u32x4 v = *(const u32x4*)(orow + r * (2 * D) + 16 * (c ^ (r & (NC - 1))));
+    if (rpos >= p.pos_begin && rpos < p.pos_end)
+      *(u32x4*)((uint16_t*)p.out[which] + (int64_t)(rpos - p.pos_begin) * p.token_stride + head * D + 8 * c) = v;
   }
 }
 
