@@ -20,6 +20,10 @@ What it follows (paper sections / equations, restated in code):
   ``Score = softmax((q H) dequant(K~)^T / sqrt(d))`` and
   ``Output = Score dequant(V~) H``; Sec. 2 gives the decode step as
   ``o = softmax(q K^T / sqrt(d)) V``.
+* Randomised Hadamard -- Sec. 3 says the transforms used in practice are
+  randomised; the standard construction (a fixed +/-1 diagonal in front of the
+  Hadamard matrix) is taken: ``R = diag(sigma) H_blk``, still orthonormal,
+  ``R^-1 = R^T = H_blk diag(sigma)``.  ``signs=None`` is the plain matrix.
 * Paged cache -- Sec. 2 ("Paged Memory Layouts"): fixed-size pages of one
   uniform type reached through a page table, token-wise metadata only.
 
@@ -80,12 +84,34 @@ def block_hadamard(d: int, h: int) -> np.ndarray:
     return out
 
 
-def rotate(x: np.ndarray, h: int) -> np.ndarray:
-    """``x H_blk`` along the last axis, dense mat-vec in fp64.  ``h == 1`` is the identity."""
+def rotation_matrix(d: int, h: int, signs=None) -> np.ndarray:
+    """``R = diag(sigma) H_blk`` (Sec. 3: randomised Hadamard; ``signs`` = sigma, d entries of +/-1;
+    None = all +1, the plain block Hadamard)."""
+    R = block_hadamard(d, h)
+    if signs is not None:
+        sg = np.asarray(signs, np.float64)
+        if sg.shape != (d,) or not np.all(np.abs(sg) == 1.0):
+            raise ValueError("signs must be d values of +1 or -1")
+        R = np.diag(sg) @ R
+    return R
+
+
+def rotate(x: np.ndarray, h: int, signs=None) -> np.ndarray:
+    """``x R`` along the last axis, dense mat-vec in fp64.  ``h == 1`` is the identity (signs ignored:
+    they are part of the rotation)."""
     x = np.asarray(x, dtype=np.float64)
     if h == 1:
         return x.copy()
-    return x @ block_hadamard(x.shape[-1], h)
+    return x @ rotation_matrix(x.shape[-1], h, signs)
+
+
+def unrotate(y: np.ndarray, h: int, signs=None) -> np.ndarray:
+    """``y R^T`` along the last axis: the inverse of ``rotate`` (App. A.4: the transpose undoes an
+    orthonormal rotation; for the plain symmetric Hadamard this is the same matrix again)."""
+    y = np.asarray(y, dtype=np.float64)
+    if h == 1:
+        return y.copy()
+    return y @ rotation_matrix(y.shape[-1], h, signs).T
 
 
 # --------------------------------------------------------------------------
@@ -145,15 +171,15 @@ def new_cache(num_pages: int, n_kv_heads: int, page_size: int, head_dim: int) ->
     }
 
 
-def _encode(x: np.ndarray, h: int, rot: bool):
-    y = rotate(x, h) if rot else np.asarray(x, np.float64)
+def _encode(x: np.ndarray, h: int, rot: bool, signs=None):
+    y = rotate(x, h, signs) if rot else np.asarray(x, np.float64)
     codes, s, z = quantize(y)
     return pack_nibbles(codes), s, z, y
 
 
 def rotate_quant_store(cache: dict, K: np.ndarray, V: np.ndarray, page_table: np.ndarray,
                        slots: np.ndarray, had_block: int, rotate_mask: int = ROT_K | ROT_V,
-                       return_prerounding: bool = False):
+                       return_prerounding: bool = False, signs=None):
     """Rotate, quantise and place ``T`` new tokens (Sec. 3 eq. 1-3 then App. A.1).
 
     ``K, V``: ``[T][Hkv][d]`` (any float dtype, widened exactly to fp64).
@@ -167,8 +193,8 @@ def rotate_quant_store(cache: dict, K: np.ndarray, V: np.ndarray, page_table: np
     K = np.asarray(K, np.float64)
     V = np.asarray(V, np.float64)
     h = int(had_block)
-    kp, ks, kz, ky = _encode(K, h, bool(rotate_mask & ROT_K) and h > 1)
-    vp, vs, vz, vy = _encode(V, h, bool(rotate_mask & ROT_V) and h > 1)
+    kp, ks, kz, ky = _encode(K, h, bool(rotate_mask & ROT_K) and h > 1, signs)
+    vp, vs, vz, vy = _encode(V, h, bool(rotate_mask & ROT_V) and h > 1, signs)
     seq = slots[:, 0].astype(np.int64)
     pos = slots[:, 1].astype(np.int64)
     page = np.asarray(page_table)[seq, pos // P].astype(np.int64)
@@ -197,19 +223,20 @@ def _gather(cache: dict, which: str, page_table_row: np.ndarray, pos_begin: int,
 
 
 def dequant_pages(cache: dict, page_table: np.ndarray, seq: int, pos_begin: int, pos_end: int,
-                  had_block: int, rotate_mask: int = ROT_K | ROT_V, unrotate: bool = False):
+                  had_block: int, rotate_mask: int = ROT_K | ROT_V, unrotate: bool = False, signs=None):
     """Read back positions ``[pos_begin, pos_end)`` of one sequence as fp64 ``(K^, V^)``.
 
-    ``unrotate`` multiplies by ``H_blk`` once more (``H`` is symmetric and
-    orthonormal, so that is the inverse rotation, App. A.4).
+    ``unrotate`` applies the inverse rotation ``R^T`` (App. A.4; for the plain
+    Hadamard, symmetric and orthonormal, that is the same matrix once more).
     """
     k = _gather(cache, "k", page_table[seq], pos_begin, pos_end)
     v = _gather(cache, "v", page_table[seq], pos_begin, pos_end)
     if unrotate and had_block > 1:
+        Rt = rotation_matrix(cache["head_dim"], had_block, signs).T
         if rotate_mask & ROT_K:
-            k = rotate(k, had_block)
+            k = k @ Rt
         if rotate_mask & ROT_V:
-            v = rotate(v, had_block)
+            v = v @ Rt
     return k, v
 
 
@@ -224,12 +251,12 @@ def _softmax_rows(logits: np.ndarray) -> np.ndarray:
 
 def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_lens: np.ndarray,
                       had_block: int, rotate_mask: int = ROT_K | ROT_V,
-                      sm_scale: float | None = None) -> np.ndarray:
-    """One decode step over the INT4 cache as stored: ``o = softmax(q~ K^^T / sqrt(d)) V^ [H]``.
+                      sm_scale: float | None = None, signs=None) -> np.ndarray:
+    """One decode step over the INT4 cache as stored: ``o = softmax(q~ K^^T / sqrt(d)) V^ [R^T]``.
 
-    ``q``: ``[B][Hq][d]``.  ``q~ = q H_blk`` when K is rotated, else ``q``;
-    the result is multiplied by ``H_blk`` when V is rotated.  A sequence of
-    length 0 gives a zero row.
+    ``q``: ``[B][Hq][d]``.  ``q~ = q R`` when K is rotated, else ``q``; the
+    result is multiplied by ``R^T`` when V is rotated (``R = diag(signs) H_blk``;
+    without signs ``R^T = R = H_blk``).  A sequence of length 0 gives a zero row.
     """
     q = np.asarray(q, np.float64)
     B, Hq, d = q.shape
@@ -239,7 +266,7 @@ def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_le
     scale = (1.0 / np.sqrt(np.float64(d))) if (sm_scale is None or sm_scale <= 0) else float(sm_scale)
     rot_k = bool(rotate_mask & ROT_K) and h > 1
     rot_v = bool(rotate_mask & ROT_V) and h > 1
-    Hb = block_hadamard(d, h) if (rot_k or rot_v) else None
+    Hb = rotation_matrix(d, h, signs) if (rot_k or rot_v) else None
     out = np.zeros((B, Hq, d), np.float64)
     for b in range(B):
         L = int(seq_lens[b])
@@ -253,7 +280,7 @@ def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_le
             logits = (qt @ khat[:, g, :].T) * scale        # [G][L]
             p = _softmax_rows(logits)
             o = p @ vhat[:, g, :]                          # [G][d]
-            out[b, g * G:(g + 1) * G, :] = o @ Hb if rot_v else o
+            out[b, g * G:(g + 1) * G, :] = o @ Hb.T if rot_v else o
     return out
 
 

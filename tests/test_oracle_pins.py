@@ -345,3 +345,111 @@ def test_kv16_baseline_matches_plain_attention():
         vp[pt[0, t // P], :, t % P] = V[t]
     o = O.kv16_paged_decode_attn(kp, vp, q, pt, np.array([L]))
     assert np.allclose(o[0], O.attention_plain(q[0], K, V), atol=1e-13)
+
+
+# ---------------------------------------------------------------- randomised Hadamard (sign diagonal)
+def _signs(d, seed):
+    return np.where(np.random.default_rng(seed).random(d) < 0.5, -1.0, 1.0)
+
+
+@pytest.mark.parametrize("d,h", [(16, 4), (64, 16), (128, 32), (128, 128)])
+def test_signed_rotation_is_orthonormal_and_entrywise_closed_form(d, h):
+    sg = _signs(d, 7 + h)
+    R = O.rotation_matrix(d, h, sg)
+    assert np.allclose(R @ R.T, np.eye(d), atol=1e-12) and np.allclose(R.T @ R, np.eye(d), atol=1e-12)
+    # entry (i, j): sigma_i (-1)^popcount(i & j within the block) / sqrt(h) inside a block, 0 outside
+    for i in range(0, d, max(1, d // 8)):
+        for j in range(d):
+            want = 0.0 if i // h != j // h else sg[i] * (-1.0) ** bin((i % h) & (j % h)).count("1") / math.sqrt(h)
+            assert R[i, j] == pytest.approx(want, abs=1e-15)
+    x = RNG.standard_normal((5, d))
+    y = RNG.standard_normal((5, d))
+    assert np.allclose(O.rotate(x, h, sg) @ O.rotate(y, h, sg).T, x @ y.T, atol=1e-11)      # (qR)(kR)^T = q k^T
+    assert np.allclose(O.unrotate(O.rotate(x, h, sg), h, sg), x, atol=1e-12)
+    assert np.allclose(np.linalg.norm(O.rotate(x, h, sg), axis=-1), np.linalg.norm(x, axis=-1))
+    # all +1 is the plain matrix; the transform is NOT symmetric any more once a sign differs
+    assert np.array_equal(O.rotation_matrix(d, h, np.ones(d)), O.block_hadamard(d, h))
+    if (sg < 0).any() and (sg > 0).any():
+        assert not np.allclose(R, R.T)
+    # a one-hot input picks out the signed Hadamard row
+    e = np.zeros(d); e[3] = 2.0
+    assert np.allclose(O.rotate(e, h, sg), 2.0 * sg[3] * O.block_hadamard(d, h)[3])
+
+
+def test_signed_store_equals_plain_store_of_prerotated_input():
+    """Storing x with (h, signs) must give the very bytes that a no-rotation store of x R gives,
+    R built here as an explicit dense matrix (fp64 product rounded the same way: inputs are small
+    integers over a power of two, so x R is exact in both routes)."""
+    d, h, Hkv, T, P = 32, 16, 2, 20, 16
+    sg = _signs(d, 99)
+    R = np.diag(sg) @ scipy.linalg.block_diag(*[scipy.linalg.hadamard(h) / math.sqrt(h)] * (d // h))
+    K = RNG.integers(-64, 64, size=(T, Hkv, d)).astype(np.float64) / 8.0
+    V = RNG.integers(-64, 64, size=(T, Hkv, d)).astype(np.float64) / 8.0
+    pt = np.array([[2, 0]], np.int32)
+    sl = np.stack([np.zeros(T, np.int32), np.arange(T, dtype=np.int32)], 1)
+    a = O.new_cache(3, Hkv, P, d)
+    b = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(a, K, V, pt, sl, h, O.ROT_K | O.ROT_V, signs=sg)
+    O.rotate_quant_store(b, K @ R, V @ R, pt, sl, 1)
+    for key in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        assert np.array_equal(a[key], b[key]), key
+    # and K-only rotation leaves V unsigned
+    c = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(c, K, V, pt, sl, h, O.ROT_K, signs=sg)
+    e = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(e, K, V, pt, sl, 1)
+    assert np.array_equal(c["v_codes"], e["v_codes"]) and np.array_equal(c["k_codes"], a["k_codes"])
+    # read-back with the inverse rotation returns to the input within the quantiser's bound
+    kq, vq = O.dequant_pages(a, pt, 0, 0, T, h, unrotate=True, signs=sg)
+    s_k = a["k_meta"][[2] * 16 + [0] * 4, :, list(range(16)) + list(range(4)), 0].astype(np.float64)   # [T][Hkv]
+    err = np.linalg.norm(kq - K, axis=-1)
+    assert np.all(err <= 0.5 * s_k * math.sqrt(d) * (1 + 1e-6))
+
+
+@pytest.mark.parametrize("mask", [3, 1, 2])
+def test_signed_decode_attention_vs_dense_matrix_route(mask):
+    """Attention with (h, signs) over a cache stored with (h, signs) equals, to rounding, plain
+    softmax attention over the cache read back through the explicit dense R^T, and the brute-force
+    loop over a no-rotation cache of pre-rotated tokens gives the same rotated-space result."""
+    d, h, Hq, Hkv, P = 16, 8, 4, 2, 16
+    sg = _signs(d, 5)
+    R = np.diag(sg) @ scipy.linalg.block_diag(*[scipy.linalg.hadamard(h) / math.sqrt(h)] * (d // h))
+    L = np.array([7, 21], np.int32)
+    pt = np.array([[3, 1], [0, 2]], np.int32)
+    cache = O.new_cache(4, Hkv, P, d)
+    plain = O.new_cache(4, Hkv, P, d)
+    Ks, Vs = [], []
+    for b in range(2):
+        K = RNG.integers(-32, 32, size=(L[b], Hkv, d)).astype(np.float64) / 4.0
+        V = RNG.integers(-32, 32, size=(L[b], Hkv, d)).astype(np.float64) / 4.0
+        sl = np.stack([np.full(L[b], b, np.int32), np.arange(L[b], dtype=np.int32)], 1)
+        O.rotate_quant_store(cache, K, V, pt, sl, h, mask, signs=sg)
+        O.rotate_quant_store(plain, K @ R if mask & 1 else K, V @ R if mask & 2 else V, pt, sl, 1)
+        Ks.append(K); Vs.append(V)
+    q = RNG.standard_normal((2, Hq, d))
+    o = O.paged_decode_attn(cache, q, pt, L, h, mask, signs=sg)
+    # route 2: no-rotation cache of pre-rotated tokens, query rotated here, output rotated back here
+    q2 = q @ R if mask & 1 else q
+    o2 = _brute_force(plain, q2, pt, L, 1, 0)
+    if mask & 2:
+        o2 = o2 @ R.T
+    assert np.allclose(o, o2, rtol=0, atol=1e-12)
+    # route 3: library SDPA on the cache read back in the original space
+    for b in range(2):
+        kq, vq = O.dequant_pages(cache, pt, b, 0, int(L[b]), h, mask, unrotate=True, signs=sg)
+        for j in range(Hq):
+            g = j // (Hq // Hkv)
+            ref = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(q[b, j][None, None]), torch.from_numpy(kq[:, g][None]),
+                torch.from_numpy(vq[:, g][None])).numpy()[0, 0]
+            assert np.allclose(o[b, j], ref, atol=1e-10)
+    # all +1 signs reproduce the unsigned path bit for bit
+    un = O.new_cache(4, Hkv, P, d)
+    for b in range(2):
+        sl = np.stack([np.full(L[b], b, np.int32), np.arange(L[b], dtype=np.int32)], 1)
+        O.rotate_quant_store(un, Ks[b], Vs[b], pt, sl, h, mask, signs=np.ones(d))
+    ref_un = O.new_cache(4, Hkv, P, d)
+    for b in range(2):
+        sl = np.stack([np.full(L[b], b, np.int32), np.arange(L[b], dtype=np.int32)], 1)
+        O.rotate_quant_store(ref_un, Ks[b], Vs[b], pt, sl, h, mask)
+    assert np.array_equal(un["k_codes"], ref_un["k_codes"]) and np.array_equal(un["v_meta"], ref_un["v_meta"])
