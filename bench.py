@@ -165,32 +165,36 @@ def store_sweep(saw, dev, iters=30, warmup=5, same_buffers=True):
         Vs = [V] + [V.clone() for _ in range(SWEEP_SETS - 1)]
         pt = torch.from_numpy(base.page_table).to(dev)
         sl = torch.from_numpy(synth.slots_for(0, 0, T)).to(dev)
-        hs = [h for h in (1, 16, 32, 64, 128) if h <= base.head_dim]
+        # variants: every block size, plus the largest one with a random +/-1 diagonal in front of the
+        # Hadamard matrix (randomised Hadamard, Sec. 3); all timed in turn (plain, 16, 32, ..., plain, 16, ...),
+        # each call on the next buffer set
+        hmax = min(128, base.head_dim)
+        variants = [(f"h{h}", h, None) for h in (1, 16, 32, 64, 128) if h <= base.head_dim]
+        variants.append((f"h{hmax}_signs", hmax, synth.random_signs(base.head_dim, 1)))
         for h in (1, 16, 32, 64, 128):
             if h > base.head_dim:
                 res[f"h{h}"] = None
-        # all block sizes are timed in turn (plain, 16, 32, ..., plain, 16, ...), each on the next buffer set
-        caches = {h: [saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, 3, device=dev)
-                      for _ in range(SWEEP_SETS)] for h in hs}
-        turn = [0]
+        caches = {key: [saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, 3, device=dev, signs=sg)
+                        for _ in range(SWEEP_SETS)] for key, h, sg in variants}
+        def make_call(key):
+            turn = [0]                                          # every variant walks all its buffer sets
 
-        def make_call(h):
             def call():
                 i = turn[0] % SWEEP_SETS
                 turn[0] += 1
-                saw.rotate_quant_store(caches[h][i], Ks[i], Vs[i], pt, sl)
+                saw.rotate_quant_store(caches[key][i], Ks[i], Vs[i], pt, sl)
             return call
 
-        meds = time_interleaved([make_call(h) for h in hs], iters, warmup)
-        sames = (time_interleaved([(lambda h=h: saw.rotate_quant_store(caches[h][0], K, V, pt, sl)) for h in hs], iters, warmup)
-                 if same_buffers else [None] * len(hs))
-        for h, med, same in zip(hs, meds, sames):
+        meds = time_interleaved([make_call(key) for key, _, _ in variants], iters, warmup)
+        sames = (time_interleaved([(lambda key=key: saw.rotate_quant_store(caches[key][0], K, V, pt, sl)) for key, _, _ in variants],
+                                  iters, warmup) if same_buffers else [None] * len(variants))
+        for (key, h, sg), med, same in zip(variants, meds, sames):
             # sanity column: quantisation error of K against the unquantised input (read back, rotated back)
-            kq, _ = saw.flatten_dequant(caches[h][0], pt, 0, 0, T, unrotate=True, out_dtype=torch.float32, want_v=False)
+            kq, _ = saw.flatten_dequant(caches[key][0], pt, 0, 0, T, unrotate=True, out_dtype=torch.float32, want_v=False)
             mse = float(((kq - K.float()) ** 2).mean())
             del kq
-            res[f"h{h}"] = {"us": round(med, 2), "us_same_buffers": None if same is None else round(same, 2), "Gtok_s": round(T / med / 1e3, 4),
-                            "GB_s": round(store_bytes(base, T) / med / 1e3, 1), "k_mse": float(f"{mse:.4e}")}
+            res[key] = {"us": round(med, 2), "us_same_buffers": None if same is None else round(same, 2), "Gtok_s": round(T / med / 1e3, 4),
+                        "GB_s": round(store_bytes(base, T) / med / 1e3, 1), "k_mse": float(f"{mse:.4e}")}
         del caches
         plain = res["h1"]["us"]
         for k, v in res.items():

@@ -73,6 +73,10 @@ typedef struct saw_cache {
   int32_t  head_dim;    /* 64 | 128 */
   int32_t  had_block;   /* h of BDR-h (Sec. 3 eq. 2-3): 1 | 16 | 32 | 64 | 128 */
   int32_t  rotate_mask; /* SAW_ROT_K | SAW_ROT_V */
+  uint32_t sign_bits[4]; /* randomised Hadamard (Sec. 3): bit c (word c / 32, bit c % 32) set = channel c is
+                            negated before the block Hadamard, i.e. R = diag(sigma) H_blk; every rotated
+                            tensor uses R, the query R as well, outputs and read-backs R^T.  All zero = the
+                            plain Hadamard.  Bits at or above head_dim must be zero (SAW_EINVAL). */
 } saw_cache_t;
 
 int saw_version(void);

@@ -24,7 +24,8 @@ class SawCacheStruct(ctypes.Structure):
                 ("k_meta", ctypes.c_void_p), ("v_meta", ctypes.c_void_p),
                 ("num_pages", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("page_size", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("had_block", ctypes.c_int32), ("rotate_mask", ctypes.c_int32)]
+                ("had_block", ctypes.c_int32), ("rotate_mask", ctypes.c_int32),
+                ("sign_bits", ctypes.c_uint32 * 4)]
 
 
 class SawError(RuntimeError):
@@ -80,7 +81,7 @@ class Cache:
     """One layer's INT4 paged cache: device tensors plus the shape/rotation descriptor."""
 
     def __init__(self, num_pages, n_kv_heads, head_dim, had_block, rotate_mask=ROT_K | ROT_V,
-                 page_size=16, device="cuda", zero=True):
+                 page_size=16, device="cuda", zero=True, signs=None):
         alloc = torch.zeros if zero else torch.empty
         self.k_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
         self.v_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
@@ -88,11 +89,19 @@ class Cache:
         self.v_meta = alloc((num_pages, n_kv_heads, page_size, 2), dtype=torch.float32, device=device)
         self.num_pages, self.n_kv_heads, self.page_size = num_pages, n_kv_heads, page_size
         self.head_dim, self.had_block, self.rotate_mask = head_dim, had_block, rotate_mask
+        # signs: head_dim values of +1 / -1 (the diagonal in front of the Hadamard matrix), or None
+        self.sign_bits = [0, 0, 0, 0]
+        if signs is not None:
+            assert len(signs) == head_dim
+            for c, v in enumerate(signs):
+                if v < 0:
+                    self.sign_bits[c // 32] |= 1 << (c % 32)
 
     def struct(self) -> SawCacheStruct:
         return SawCacheStruct(self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_meta.data_ptr(),
                               self.v_meta.data_ptr(), self.num_pages, self.n_kv_heads, self.page_size,
-                              self.head_dim, self.had_block, self.rotate_mask)
+                              self.head_dim, self.had_block, self.rotate_mask,
+                              (ctypes.c_uint32 * 4)(*self.sign_bits))
 
     def nbytes(self) -> int:
         return sum(t.numel() * t.element_size() for t in (self.k_codes, self.v_codes, self.k_meta, self.v_meta))

@@ -33,6 +33,8 @@ static bool block_ok(const saw_cache_t* c) {
   if (!(h == 1 || h == 16 || h == 32 || h == 64 || h == 128)) return false;
   if (h > c->head_dim) return false;
   if (c->rotate_mask & ~(SAW_ROT_K | SAW_ROT_V)) return false;
+  // sign bits exist for the head's channels only
+  if (c->head_dim == 64 && (c->sign_bits[2] | c->sign_bits[3])) return false;
   return true;
 }
 

@@ -51,6 +51,25 @@ __device__ __forceinline__ void store_elem(void* p, int dtype, int64_t i, float 
   else ((uint16_t*)p)[i] = f32_to_f16(v);
 }
 
+// Randomised Hadamard (Sec. 3): R = diag(sigma) H_blk, sigma given as one bit per channel (set =
+// negated).  sign_pairs<T>(bits, c0) turns the 8 bits of channels c0 .. c0+7 into four dwords whose
+// bits 15 and 31 flip the signs of eight packed 16-bit floats (bf16 or fp16 alike); sign_of(bits, c)
+// is +1 or -1 for one channel.
+struct SignBits { uint32_t w[4]; };
+__device__ __forceinline__ void sign_pairs(const SignBits& sb, int c0, uint32_t (&x)[4]) {
+  const uint32_t word = (c0 >> 5) == 0 ? sb.w[0] : (c0 >> 5) == 1 ? sb.w[1] : (c0 >> 5) == 2 ? sb.w[2] : sb.w[3];
+  const uint32_t m8 = (word >> (c0 & 31)) & 0xffu;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) x[i] = (((m8 >> (2 * i)) & 1u) << 15) | (((m8 >> (2 * i + 1)) & 1u) << 31);
+}
+__device__ __forceinline__ uint32_t sign_flip32(const SignBits& sb, int c) {      // 0x80000000 if channel c is negated
+  const uint32_t word = (c >> 5) == 0 ? sb.w[0] : (c >> 5) == 1 ? sb.w[1] : (c >> 5) == 2 ? sb.w[2] : sb.w[3];
+  return ((word >> (c & 31)) & 1u) << 31;
+}
+__device__ __forceinline__ float apply_sign(const SignBits& sb, int c, float v) {
+  return __uint_as_float(__float_as_uint(v) ^ sign_flip32(sb, c));
+}
+
 // 1/sqrt(h) for the supported Hadamard orders (correctly rounded constants).
 __device__ __forceinline__ float had_norm(int h) {
   return h == 16 ? 0.25f : h == 32 ? 0.17677669529663687f : h == 64 ? 0.125f

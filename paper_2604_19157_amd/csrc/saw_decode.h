@@ -28,6 +28,8 @@ struct DecodeParams {
   int32_t pair;             // d = 128 path: two-wavefront blocks over (long, short) sequence pairs
   int32_t batch;
   int32_t waves_per_item;   // d = 128 path: wavefronts sharing one partition (1, 2 or 4)
+  int32_t has_signs;        // any bit of `signs` set
+  SignBits signs;           // R = diag(sigma) H_blk for every rotated tensor and the query; outputs take R^T
 };
 
 // MFMA INT4 decode for head_dim 128 (saw_decode_mfma.hip); grid = (splits, kv heads, batch).

@@ -48,8 +48,10 @@ __global__ __launch_bounds__(256) void decode_int4_kernel(DecodeParams p) {
   __shared__ float red[4][G][D + 4];
 
   // ---- q~ = (q H_blk) * sm_scale * log2 e ----
-  for (int i = tid; i < G * D; i += 256)
-    qs[i] = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+  for (int i = tid; i < G * D; i += 256) {
+    const float v = load_elem(p.q, p.q_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i);
+    qs[i] = (p.rot_k && p.has_signs) ? apply_sign(p.signs, i % D, v) : v;       // q diag(sigma), then H_blk
+  }
   __syncthreads();
   float qmul = p.q_scale;
   if (p.rot_k) {
@@ -400,6 +402,7 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
       __syncthreads();
     }
     o = x[c] * had_norm(p.had_block);
+    if (p.has_signs) o = apply_sign(p.signs, c, o);             // (o~ H_blk) diag(sigma) = o~ R^T
   }
   if (g != 0) return;
   store_elem(p.out, p.out_dtype, o_idx, o);
@@ -477,6 +480,8 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.had_block = c->had_block;
   p.rot_k = !kv16 && c->had_block > 1 && (c->rotate_mask & SAW_ROT_K);
   p.rot_v = !kv16 && c->had_block > 1 && (c->rotate_mask & SAW_ROT_V);
+  for (int i = 0; i < 4; ++i) p.signs.w[i] = kv16 ? 0u : c->sign_bits[i];
+  p.has_signs = (p.signs.w[0] | p.signs.w[1] | p.signs.w[2] | p.signs.w[3]) != 0;
   p.num_splits = plan.num_splits;
   p.chunk_tokens = plan.chunk_tokens;
   p.bound = plan.bound;

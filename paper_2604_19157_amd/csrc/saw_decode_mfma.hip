@@ -124,6 +124,10 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     const uint32_t w = which ? wv : wk;
     float x0, x1;
     if (p.kv_new_dtype == SAW_BF16) widen2<SAW_BF16>(w, x0, x1); else widen2<SAW_F16>(w, x0, x1);
+    if (rot && p.has_signs) {                                // x diag(sigma), as the store kernel does
+      x0 = apply_sign(p.signs, 2 * lane, x0);
+      x1 = apply_sign(p.signs, 2 * lane + 1, x1);
+    }
     yb[2 * lane] = x0;
     yb[2 * lane + 1] = x1;
     wave_sync();
@@ -508,6 +512,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       const float as_bf16 = __uint_as_float(qbits[j] << 16);
       const float as_f16 = f16_to_f32(qbits[j] & 0xffffu);
       qraw[j] = q_is_f32 ? as_f32 : (q_is_bf16 ? as_bf16 : as_f16);
+      // randomised Hadamard: q diag(sigma) first (element lane + 64 j is channel lane + 64 (j & 1))
+      if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, lane + 64 * (j & 1), qraw[j]);
     }
     prepare_q<G, NH>(p, qraw, lane, (float*)vbuf_b, (float*)pbuf, a_q, qsum, qmul);
   }
@@ -794,7 +800,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     onorm = had_norm(p.had_block);
   }
   const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
-  for (int i = lane; i < G * D; i += 64) store_elem(p.out, p.out_dtype, obase + i, fb[i] * onorm);
+  for (int i = lane; i < G * D; i += 64) {
+    float o = fb[i] * onorm;
+    if (p.rot_v && p.has_signs) o = apply_sign(p.signs, i & (D - 1), o);       // (o~ H_blk) diag(sigma) = o~ R^T
+    store_elem(p.out, p.out_dtype, obase + i, o);
+  }
   wave_sync();                                   // the next range's prologue reuses these buffers
   }  // ranges of this wavefront
 }

@@ -41,6 +41,8 @@ struct FlattenParams {
   int32_t first_page;           // pos_begin / 16
   int32_t num_pages, n_kv_heads, had_block;
   int32_t unrot[2];             // rotate this tensor back
+  int32_t has_signs;            // any bit of `signs` set
+  SignBits signs;               // R = diag(sigma) H_blk: rotating back ends with the signs
 };
 
 template <int D, int ODT>
@@ -160,6 +162,10 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
 #pragma unroll
         for (int i = 1; i < 8; ++i) o[i] = sc * y[8 * a + i];
       }
+      if (p.has_signs && unrot) {                              // wavefront-uniform
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = apply_sign(p.signs, 32 * a + 8 * rg + i, o[i]);
+      }
       float* dst = (float*)p.out[which] + obase + 32 * a + 8 * rg;
       *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
       *(f32x4*)(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
@@ -192,6 +198,12 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
       if (ODT == SAW_BF16) w4[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
       else w4[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, f16x2));
     }
+    if (p.has_signs && unrot) {                                // wavefront-uniform
+      uint32_t sx[4];
+      sign_pairs(p.signs, 32 * a + 8 * rg, sx);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w4[i] ^= sx[i];
+    }
     const int c = 4 * a + rg;
     *(u32x4*)(orow + n16 * (2 * D) + 16 * (c ^ (n16 & (NC - 1)))) = u32x4{w4[0], w4[1], w4[2], w4[3]};
   }
@@ -223,6 +235,8 @@ int launch_flatten(const saw_cache_t* c, const int32_t* pt_row, int32_t pos_begi
   const bool rot = unrotate && c->had_block > 1;
   p.unrot[0] = rot && (c->rotate_mask & SAW_ROT_K);
   p.unrot[1] = rot && (c->rotate_mask & SAW_ROT_V);
+  for (int i = 0; i < 4; ++i) p.signs.w[i] = c->sign_bits[i];
+  p.has_signs = (c->sign_bits[0] | c->sign_bits[1] | c->sign_bits[2] | c->sign_bits[3]) != 0;
   const int n_pages = (pos_end + 15) / 16 - p.first_page;
   // (K|V, head) groups vary fastest, so blocks that run together write neighbouring pieces of the
   // same token rows

@@ -52,6 +52,7 @@ struct DequantParams {
   int32_t seq, pos_begin, n_tokens;
   int32_t had_block;
   int32_t unrot[2];
+  SignBits signs;
 };
 
 template <int D>
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256) void dequant_pages_kernel(DequantParams p) {
     fwht<LPV>(e, sub, p.had_block);
     const float norm = had_norm(p.had_block);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] *= norm;
+    for (int i = 0; i < 8; ++i) e[i] = apply_sign(p.signs, 8 * sub + i, e[i] * norm);   // y H_blk diag(sigma) = y R^T
   }
   if (!ok) return;
   float* dst = p.out[which] + ((int64_t)t * p.n_kv_heads + head) * D + sub * 8;
@@ -148,6 +149,7 @@ int launch_dequant(const saw_cache_t* c, const int32_t* pt, int32_t max_pages, i
   p.had_block = c->had_block;
   p.unrot[0] = unrotate && (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);
   p.unrot[1] = unrotate && (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
+  for (int i = 0; i < 4; ++i) p.signs.w[i] = c->sign_bits[i];
   const int D = c->head_dim;
   const int vpb = 256 / (D / 8);
   const int64_t n_vec = (int64_t)p.n_tokens * c->n_kv_heads;

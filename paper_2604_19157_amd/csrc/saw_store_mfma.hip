@@ -40,6 +40,8 @@ struct StoreMfmaParams {
   int32_t n_seqs, max_pages, num_pages, n_kv_heads;
   int32_t had_block;
   int32_t rot[2];
+  int32_t has_signs;            // any bit of `signs` set
+  SignBits signs;               // diagonal in front of the Hadamard matrix (rotated tensors only)
 };
 
 template <int DT>
@@ -124,11 +126,19 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   // ---- through LDS into the B-operand layout: column = token, k-group rg = chunk 4a + rg ----
   // chunk x of token tok sits at chunk position x ^ ((tok / RP) & (XC-1)): both the row-wise
   // writes and the column-wise reads below touch every bank once.
+  // Randomised Hadamard: x . diag(sigma) is a sign flip of the 16-bit inputs (exact), applied here
+  // because a lane's chunk index (lane % (ROWB / 16)) is the same for all of its loads: one mask.
+  u32x4 sflip = u32x4{0u, 0u, 0u, 0u};
+  if (p.has_signs && rot) {                                     // wavefront-uniform
+    uint32_t sx[4];
+    sign_pairs(p.signs, 8 * (lane % (ROWB / 16)), sx);
+    sflip = u32x4{sx[0], sx[1], sx[2], sx[3]};
+  }
 #pragma unroll
   for (int r = 0; r < NLD; ++r) {
     const int off = r * 1024 + 16 * lane;
     const int tok = off / ROWB, x = (off % ROWB) / 16;
-    *(u32x4*)(stage + tok * ROWB + 16 * (x ^ ((tok / RP) & (XC - 1)))) = ld[r];
+    *(u32x4*)(stage + tok * ROWB + 16 * (x ^ ((tok / RP) & (XC - 1)))) = ld[r] ^ sflip;
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -246,6 +256,8 @@ int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt
   p.had_block = c->had_block;
   p.rot[0] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);
   p.rot[1] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
+  for (int i = 0; i < 4; ++i) p.signs.w[i] = c->sign_bits[i];
+  p.has_signs = (c->sign_bits[0] | c->sign_bits[1] | c->sign_bits[2] | c->sign_bits[3]) != 0;
   const int D = c->head_dim;
   const int64_t tblocks = (T + 15) / 16;
   if (tblocks > 0x7fffffffLL) return SAW_EINVAL;

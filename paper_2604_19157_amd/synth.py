@@ -36,6 +36,7 @@ class Workload:
     k_chan_scale: np.ndarray        # [Hkv][d] float32
     v_chan_scale: np.ndarray        # [Hkv][d] float32
     rotate_mask: int = 3
+    signs: np.ndarray | None = None     # [d] of +1 / -1: diagonal in front of the Hadamard matrix (None: plain)
     extra: dict = field(default_factory=dict)
 
     @property
@@ -131,7 +132,13 @@ def make_workload(name: str, rep: int = 0, **over) -> Workload:
     vs = _chan_scale(rng, kind, Hkv, d)
     return Workload(name=name, seed=seed, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_size=P,
                     had_block=h, dtype=dtype, seq_lens=seq_lens, page_table=pt, num_pages=num_pages,
-                    k_chan_scale=ks, v_chan_scale=vs, rotate_mask=over.get("rotate_mask", 3))
+                    k_chan_scale=ks, v_chan_scale=vs, rotate_mask=over.get("rotate_mask", 3),
+                    signs=random_signs(d, over["sign_seed"]) if "sign_seed" in over else None)
+
+
+def random_signs(d: int, seed: int) -> np.ndarray:
+    """d values of +1 / -1, half of them negative on average (the diagonal of a randomised Hadamard)."""
+    return np.where(np.random.default_rng(int(seed)).random(d) < 0.5, -1.0, 1.0)
 
 
 def _gen(seed: int, device) -> torch.Generator:

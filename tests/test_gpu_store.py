@@ -128,7 +128,8 @@ def test_dequant_pages(saw, name, kw, unrotate):
         L = int(w.seq_lens[b])
         for (p0, p1) in [(0, L), (5, min(L, 37)), (L - 1, L)]:
             k, v = saw.dequant_pages(cache, pt, b, p0, p1, unrotate=unrotate)
-            kr, vr = O.dequant_pages(got, w.page_table, b, p0, p1, w.had_block, w.rotate_mask, unrotate=unrotate)
+            kr, vr = O.dequant_pages(got, w.page_table, b, p0, p1, w.had_block, w.rotate_mask, unrotate=unrotate,
+                                     signs=w.signs)
             for a, r in ((k, kr), (v, vr)):
                 a = a.cpu().numpy().astype(np.float64)
                 assert np.abs(a - r).max() <= 2e-6 * np.abs(r).max()
