@@ -31,6 +31,9 @@
  *   - Query head j reads kv head j / (n_q_heads / n_kv_heads).
  *   - Supported: page_size 16; head_dim 64 or 128; had_block 1 (no rotation), 16, 32,
  *     64 or 128 with had_block <= head_dim; n_q_heads / n_kv_heads in {1, 2, 4, 8}.
+ *   - Randomised Hadamard (Sec. 3): with sign_bits set in the cache descriptor the rotation of
+ *     every rotated tensor is R = diag(sigma) H_blk (sigma = +/-1 per channel, one vector for all
+ *     heads); the query is multiplied by R as well, outputs and rotated-back read-backs by R^T.
  */
 #ifndef SAW_H_
 #define SAW_H_
