@@ -109,3 +109,41 @@ def test_store_full_size(saw, name):
     res = gc.compare_store(gc.cache_to_numpy(cache, w), ref, recs)
     print(f"[{name}] {res}", flush=True)
     parity.assert_store_ok(res)
+
+
+@pytest.mark.parametrize("name", ["prefill", "prefill_mha"])
+def test_flatten_full_size_sampled(saw, name):
+    """32k-token flatten in the launch shape the bench times (whole sequence, bf16 out, rotated back):
+    sampled token ranges against the oracle's read-back of the oracle-written bytes (only the sampled
+    pages are uploaded, the rest of the device cache is the HIP store's), every output row written,
+    repeated launches identical."""
+    import test_gpu_flatten as TF
+    w = synth.make_workload(name)
+    T = int(w.seq_lens[0])
+    cache, _, _, pt = gc.fill_caches(w, saw, chunk=32768, with_ref=False)
+    rng = np.random.default_rng(11)
+    starts = sorted({0, T - 40, *[int(x) for x in rng.integers(0, T - 64, size=6)]})
+    ranges = [(p0, min(T, p0 + 40)) for p0 in starts]
+    # oracle bytes for the sampled positions: store those chunks with the oracle, upload their pages
+    ref = O.new_cache(w.num_pages, w.n_kv_heads, w.page_size, w.head_dim)
+    pages = set()
+    for p0, p1 in ranges:
+        a, b = (p0 // 16) * 16, min(T, ((p1 + 15) // 16) * 16)
+        K, V = synth.gen_kv(w, 0, a, b)
+        O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), w.page_table, synth.slots_for(0, a, b),
+                                w.had_block, w.rotate_mask)
+        pages.update(int(w.page_table[0, p // 16]) for p in range(a, b, 16))
+    gc.upload_cache(ref, w, saw, into=cache, pages=sorted(pages))
+    k = torch.full((T, w.n_kv_heads, w.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v = torch.full_like(k, float("nan"))
+    saw.flatten_dequant(cache, pt, 0, 0, T, unrotate=True, k_out=k, v_out=v)
+    torch.cuda.synchronize()
+    assert torch.isfinite(k.float()).all() and torch.isfinite(v.float()).all()      # every row written
+    for p0, p1 in ranges:
+        kr, vr = O.dequant_pages(ref, w.page_table, 0, p0, p1, w.had_block, w.rotate_mask, unrotate=True)
+        TF._check(k[p0:p1], kr, torch.bfloat16, f"[{name} full size [{p0},{p1})] K")
+        TF._check(v[p0:p1], vr, torch.bfloat16, f"[{name} full size [{p0},{p1})] V")
+    k2 = torch.empty_like(k)
+    v2 = torch.empty_like(v)
+    saw.flatten_dequant(cache, pt, 0, 0, T, unrotate=True, k_out=k2, v_out=v2)
+    assert torch.equal(k, k2) and torch.equal(v, v2)
