@@ -262,13 +262,15 @@ def clone_cache(saw, c, dev):
     return n
 
 
-def other_decode(saw, dev, name, iters=32, warmup=8, **over):
+def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, **over):
     """Decode latency and bandwidth of another workload of the paper's table (cache filled by the HIP
     store).  A cache smaller than the chip's 256 MB memory-side cache would be served from it on
-    repeated calls, so such workloads rotate over enough identical copies to exceed 4x that size."""
+    repeated calls, so such workloads rotate over enough identical copies to exceed 4x that size.
+    `with_kv16` adds the 16-bit-KV decode of the same workload, timed in turn with the INT4 one."""
     w = synth.make_workload(name, **over)
     cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, device=dev)
-    pt = fill(w, saw, dev, cache)
+    kv16 = saw.Kv16Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.dtype, device=dev) if with_kv16 else None
+    pt = fill(w, saw, dev, cache, kv16)
     lens = w.seq_lens.astype(np.int32)
     nbytes = decode_bytes(w, lens)
     copies = [cache]
@@ -287,12 +289,27 @@ def other_decode(saw, dev, name, iters=32, warmup=8, **over):
         turn[0] += 1
         saw.paged_decode_attn(c, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
 
-    med, mean, p10, p90 = time_calls(call, iters, warmup)
+    res16 = None
+    if with_kv16:
+        def call16():
+            saw.kv16_paged_decode_attn(kv16, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
+        med, med16 = time_interleaved([call, call16], iters, warmup)
+        p10 = p90 = float("nan")
+        b16 = kv16_decode_bytes(w, lens)
+        res16 = {"us": round(med16, 2), "GB_s": round(b16 / med16 / 1e3, 1), "int4_speedup": round(med16 / med, 3),
+                 "bytes_ratio": round(b16 / nbytes, 3)}
+    else:
+        med, mean, p10, p90 = time_calls(call, iters, warmup)
     overhead = 2 * w.batch * w.n_q_heads * splits * (w.head_dim + 2) * 4 if splits > 1 else 0
-    return {"batch": w.batch, "tokens_cached": int(lens.sum()), "splits": splits, "cache_copies_rotated": len(copies),
-            "split_partials_bytes_written_and_read": overhead,
-            "us": round(med, 2), "p10_us": round(p10, 2), "p90_us": round(p90, 2),
-            "GB_s": round(nbytes / med / 1e3, 1), "pct_of_hbm_peak": round(nbytes / med / 1e3 / HBM_PEAK_GBS * 100, 2)}
+    r = {"batch": w.batch, "tokens_cached": int(lens.sum()), "splits": splits, "cache_copies_rotated": len(copies),
+         "split_partials_bytes_written_and_read": overhead,
+         "us": round(med, 2), "GB_s": round(nbytes / med / 1e3, 1),
+         "pct_of_hbm_peak": round(nbytes / med / 1e3 / HBM_PEAK_GBS * 100, 2)}
+    if res16 is None:
+        r.update(p10_us=round(p10, 2), p90_us=round(p90, 2))
+    else:
+        r["kv16_decode"] = res16
+    return r
 
 
 def copy_ceiling(dev, nbytes=1 << 30, iters=10):
@@ -509,7 +526,8 @@ def main():
         ex["llama8b_store_16_new_tokens_us"] = round(med, 2)          # launch-latency dominated
         del c2
         ex["other_decode"] = {
-            "highconc_uniform2304": other_decode(saw, dev, "highconc", ctx=2304),
+            # equal lengths: neither kernel needs balancing, so the 16-bit comparison isolates the format
+            "highconc_uniform2304": other_decode(saw, dev, "highconc", ctx=2304, with_kv16=True),
             "llama8b": other_decode(saw, dev, "llama8b"),
             "longctx1": other_decode(saw, dev, "longctx1"),
             "longctx4": other_decode(saw, dev, "longctx4"),
