@@ -422,7 +422,6 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   }
   SAW_LOAD_PIDS(pidv_nx, pg_first + 64)
-  pidv = SAW_CLAMP_PID(pidv);
   // this lane's share of the G query vectors (element lane + 64 j), issued ahead of the code transfers
   uint32_t qbits[2 * G];
   {
@@ -448,6 +447,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     if ((seq_len_b >> 4) < p.max_pages) new_pid = p.page_table[pt_row + (seq_len_b >> 4)];
   }
 
+  // (first use of the page ids: only here, so that the query and new-token loads above are in
+  // flight while this waits for them)
+  pidv = SAW_CLAMP_PID(pidv);
   const int nb = max(t_end - t_begin + 63, 0) >> 6;               // batches of the range (0: only an appended token)
   // last batch of this wavefront (below first_batch if it has none)
   const int my_last = nb - 1 - ((nb - 1 - first_batch) % STEP + STEP) % STEP;
