@@ -80,8 +80,8 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
     }
     a_q[kk] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
   }
-  qpart += __shfl_xor(qpart, 16, 64);
-  qpart += __shfl_xor(qpart, 32, 64);            // every lane of row m: sum of the limbs it feeds
+  qpart = add_xor16(qpart);
+  qpart = add_xor32(qpart);            // every lane of row m: sum of the limbs it feeds
   wave_sync();
   if (lane < 16) qred[lane] = qpart;
   wave_sync();
@@ -139,10 +139,10 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     const float y0 = yb[2 * lane], y1 = yb[2 * lane + 1];
     // min and max over the 128 values: one reduction of (max, -min) pairs, rows first (DPP)
     float mx = row_allmax(fmaxf(y0, y1)), nmn = row_allmax(-fminf(y0, y1));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    nmn = fmaxf(nmn, __shfl_xor(nmn, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    nmn = fmaxf(nmn, __shfl_xor(nmn, 32, 64));
+    mx = max_xor16(mx);
+    nmn = max_xor16(nmn);
+    mx = max_xor32(mx);
+    nmn = max_xor32(nmn);
     const float mn = -nmn;
     const float range = mx - mn;
     float inv, zq, s_store, z_store;
@@ -172,8 +172,8 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
       for (int j = 0; j < G; ++j) {
         float part = fmaf(qrot[j * D + 2 * lane], d0, qrot[j * D + 2 * lane + 1] * d1);
         part = row_allsum(part);
-        part += __shfl_xor(part, 16, 64);
-        part += __shfl_xor(part, 32, 64);
+        part = add_xor16(part);
+        part = add_xor32(part);
         if (lane == 0) lg[j] = part * qmul;
       }
     } else {
@@ -197,23 +197,27 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
 
 // Longest-first order of the batch's sequences, derived by every block from the same seq_lens:
 // rank by (64 length classes, sequence index).  `build` reads the lengths once (all loads issued
-// together: one memory latency), leaves them clamped in LDS, makes the class histogram and its
-// prefix sums across lanes (lane c owns class c, class 0 = longest); `seq_of_rank` finds the
-// sequence at a rank with two ballots per 64 sequences, from the lengths in LDS.
+// together: one memory latency), leaves them clamped in LDS and their classes in registers, makes
+// the class histogram (LDS atomics) and its prefix sums across lanes (lane c owns class c, class
+// 0 = longest); `seq_of_rank` finds the sequence at a rank with two ballots per 64 sequences.
 // LDS scratch: 64 + B ints, B <= kMaxRanked.
 constexpr int kMaxRanked = 1024;
 struct LenClasses {
   int cnt, start, incl;      // this lane's class: members, ranks [start, incl)
-  float kscale;
   int V;                     // ceil(B / 64)
   const int* lens;           // LDS: the clamped lengths
+  int cls[kMaxRanked / 64];  // class of sequence 64 v + lane (-1 past the batch)
 };
 __device__ __forceinline__ int len_class(int len, float kscale) {
   return 63 - (int)((float)((len + 63) >> 6) * kscale);
 }
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ int dpp_i0(int v) {               // lanes without a source (or outside ROWMASK) read 0
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROWMASK, 0xf, false);
+}
 __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* scratch) {
   LenClasses lc;
-  lc.kscale = 63.0f / (float)((p.bound + 63) >> 6);
+  const float kscale = 63.0f / (float)((p.bound + 63) >> 6);
   lc.V = (B + 63) >> 6;
   int* const hist = scratch;
   int* const lens = scratch + 64;
@@ -229,41 +233,49 @@ __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, i
 #pragma unroll
   for (int v = 0; v < kMaxRanked / 64; ++v) {
     const int idx = 64 * v + lane;
+    lc.cls[v] = -1;
     if (idx < B) {
       const int len = max(min(mine[v] + p.len_bias, p.bound), 0);
       lens[idx] = len;
-      atomicAdd(&hist[len_class(len, lc.kscale)], 1);
+      lc.cls[v] = len_class(len, kscale);
+      atomicAdd(&hist[lc.cls[v]], 1);
     }
   }
   wave_sync();
   lc.cnt = hist[lane];
+  // inclusive prefix sum over the 64 lanes in registers: four shifted adds inside each row of 16
+  // lanes, then each row's last lane is broadcast into the rows after it
   int incl = lc.cnt;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int t = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += t;
-  }
+  incl += dpp_i0<0x111, 0xf>(incl);      // row_shr:1
+  incl += dpp_i0<0x112, 0xf>(incl);      // row_shr:2
+  incl += dpp_i0<0x114, 0xf>(incl);      // row_shr:4
+  incl += dpp_i0<0x118, 0xf>(incl);      // row_shr:8
+  incl += dpp_i0<0x142, 0xa>(incl);      // row_bcast:15 into rows 1 and 3
+  incl += dpp_i0<0x143, 0xc>(incl);      // row_bcast:31 into rows 2 and 3
   lc.incl = incl;
   lc.start = incl - lc.cnt;
   return lc;
 }
-__device__ __forceinline__ int seq_of_rank(int B, int lane, const LenClasses& lc, int srank) {
+__device__ __forceinline__ int seq_of_rank(int lane, const LenClasses& lc, int srank) {
   const unsigned long long hit = __ballot(srank >= lc.start && srank < lc.incl);   // exactly one class
   const int cls = __ffsll((long long)hit) - 1;
   int o = srank - __builtin_amdgcn_readlane(lc.start, cls);                        // index inside the class
   int found = 0;
-  for (int v = 0; v < lc.V; ++v) {
-    const int idx = 64 * v + lane;
-    const bool in = idx < B && len_class(lc.lens[min(idx, B - 1)], lc.kscale) == cls;
-    const unsigned long long mask = __ballot(in);
-    const int c = __popcll(mask);
-    if (o < c) {
-      const int myrank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-      const unsigned long long me = __ballot(in && myrank == o);
-      found = 64 * v + __ffsll((long long)me) - 1;
-      break;
+  bool done = false;
+#pragma unroll
+  for (int v = 0; v < kMaxRanked / 64; ++v) {
+    if (v < lc.V && !done) {                                                       // wavefront-uniform
+      const bool in = lc.cls[v] == cls;
+      const unsigned long long mask = __ballot(in);
+      const int c = __popcll(mask);
+      if (o < c) {
+        const int myrank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+        const unsigned long long me = __ballot(in && myrank == o);
+        found = 64 * v + __ffsll((long long)me) - 1;
+        done = true;
+      }
+      o -= c;
     }
-    o -= c;
   }
   return __builtin_amdgcn_readfirstlane(found);
 }
@@ -326,8 +338,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     const int r_long = blockIdx.z, r_short = B - 1 - r_long;
     const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
-    const int b_long = seq_of_rank(B, lane, lc, r_long);
-    const int b_short = self ? b_long : seq_of_rank(B, lane, lc, r_short);
+    const int b_long = seq_of_rank(lane, lc, r_long);
+    const int b_short = self ? b_long : seq_of_rank(lane, lc, r_short);
     const int l_long = lc.lens[b_long];
     const int l_short = self ? 0 : lc.lens[b_short];
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
@@ -366,7 +378,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // in index order as earlier ones finish, so taking the sequences longest first leaves the
     // shortest for the end of the launch
     const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
-    sg_b[0] = seq_of_rank(p.batch, lane, lc, blockIdx.z);
+    sg_b[0] = seq_of_rank(lane, lc, blockIdx.z);
     wave_sync();
   }
 
@@ -617,10 +629,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
         if (NS > 1) mx = fmaxf(mx, lg[NS - 1][i]);
         mx = row_allmax(mx);
         if (G > 4) {
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));      // lanes 32 apart share the head group
+          mx = max_xor32(mx);      // lanes 32 apart share the head group
         } else {
-          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          mx = max_xor16(mx);
+          mx = max_xor32(mx);
         }
         const float mnew = fmaxf(m_ref[i], mx);
         const float alpha = fast_exp2(m_ref[i] - mnew);      // 0 on the first batch
@@ -718,16 +730,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     lsum[i] = row_allsum(lsum[i]);
     zs[i] = row_allsum(zs[i]);
     if (G > 4) {
-      lsum[i] += __shfl_xor(lsum[i], 32, 64);
-      zs[i] += __shfl_xor(zs[i], 32, 64);
+      lsum[i] = add_xor32(lsum[i]);
+      zs[i] = add_xor32(zs[i]);
     } else {
-      lsum[i] += __shfl_xor(lsum[i], 16, 64);
-      lsum[i] += __shfl_xor(lsum[i], 32, 64);
-      zs[i] += __shfl_xor(zs[i], 16, 64);
-      zs[i] += __shfl_xor(zs[i], 32, 64);
+      lsum[i] = add_xor16(lsum[i]);
+      lsum[i] = add_xor32(lsum[i]);
+      zs[i] = add_xor16(zs[i]);
+      zs[i] = add_xor32(zs[i]);
     }
   }
-  constexpr int LOSHIFT = (G > 4) ? 32 : 16;     // lanes holding the lo rows sit this far above the hi rows
+  // (the lanes holding the lo rows sit 16 lanes above the hi rows, 32 for G = 8)
   const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
   const int emode = PAIR ? mode : (p.num_splits == 1 ? (int)kSegAlone : (int)kSegSplitKV);
   if (emode == kSegSplitKV) {
@@ -738,7 +750,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (D + 2);
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
-        const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
+        const float o = (G > 4) ? add_xor32(oacc[c][i]) : add_xor16(oacc[c][i]);   // hi rows + lo rows
         if (writer && i < G) dst[2 + 16 * c + row16] = o - zs[i];
       }
       if (writer && row16 == 0 && i < G) { dst[0] = m_ref[i]; dst[1] = lsum[i]; }
@@ -755,7 +767,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   for (int i = 0; i < NH; ++i) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const float o = oacc[c][i] + __shfl_down(oacc[c][i], LOSHIFT, 64);
+      const float o = (G > 4) ? add_xor32(oacc[c][i]) : add_xor16(oacc[c][i]);   // hi rows + lo rows
       if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = o - zs[i];
     }
     if (writer && row16 == 0 && i < G) {

@@ -63,6 +63,29 @@ __device__ __forceinline__ void swap32(float a, float b, float& x, float& y) {
   y = __uint_as_float(r[1]);
 }
 
+// v + (v of the lane 16 / 32 away, index xor), as two register permutes instead of a trip through
+// the LDS crossbar (ds_bpermute)
+__device__ __forceinline__ float add_xor16(float v) {
+  float x, y;
+  swap16(v, v, x, y);              // x rows (v0, v0, v2, v2), y rows (v1, v1, v3, v3)
+  return x + y;
+}
+__device__ __forceinline__ float add_xor32(float v) {
+  float x, y;
+  swap32(v, v, x, y);              // x rows (v0, v1, v0, v1), y rows (v2, v3, v2, v3)
+  return x + y;
+}
+__device__ __forceinline__ float max_xor16(float v) {
+  float x, y;
+  swap16(v, v, x, y);
+  return fmaxf(x, y);
+}
+__device__ __forceinline__ float max_xor32(float v) {
+  float x, y;
+  swap32(v, v, x, y);
+  return fmaxf(x, y);
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xf, 0xf, false));
@@ -93,16 +116,47 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// In-place un-normalised block Walsh-Hadamard transform of n_vec vectors of 128 floats in LDS,
-// run by one wavefront.
+// In-place un-normalised block Walsh-Hadamard transform (block size h = 16, 32, 64 or 128) of n_vec
+// vectors of 128 floats in LDS (16-byte aligned), run by one wavefront.  Three passes with eight
+// values per lane in registers: strides 1-2-4 inside chunks of eight contiguous values, strides
+// 8-16-32 over values eight apart (as far as h reaches), and stride 64 when h = 128.
 __device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int lane) {
-  for (int st = 1; st < h; st <<= 1) {
+  for (int ch = lane; ch < n_vec * 16; ch += 64) {
+    f32x4* const p = (f32x4*)(x + 8 * ch);
+    const f32x4 a = p[0], b = p[1];
+    float e[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int st = 1; st < 8; st <<= 1)
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (!(k & st)) { const float u = e[k], v = e[k + st]; e[k] = u + v; e[k + st] = u - v; }
+    p[0] = f32x4{e[0], e[1], e[2], e[3]};
+    p[1] = f32x4{e[4], e[5], e[6], e[7]};
+  }
+  wave_sync();
+  for (int g = lane; g < n_vec * 16; g += 64) {
+    float* const p = x + (g >> 4) * 128 + ((g >> 3) & 1) * 64 + (g & 7);
+    float e[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) e[k] = p[8 * k];
+#pragma unroll
+    for (int st = 1; st < 8; st <<= 1) {
+      if (8 * st < h) {                                      // wavefront-uniform
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (!(k & st)) { const float u = e[k], v = e[k + st]; e[k] = u + v; e[k + st] = u - v; }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) p[8 * k] = e[k];
+  }
+  wave_sync();
+  if (h > 64) {
     for (int idx = lane; idx < n_vec * 64; idx += 64) {
-      const int v = idx >> 6, r = idx & 63;
-      const int i = v * 128 + (r / st) * 2 * st + (r % st);
-      const float a = x[i], c = x[i + st];
+      const int i = (idx >> 6) * 128 + (idx & 63);
+      const float a = x[i], c = x[i + 64];
       x[i] = a + c;
-      x[i + st] = a - c;
+      x[i + 64] = a - c;
     }
     wave_sync();
   }
