@@ -208,8 +208,8 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
 #pragma unroll
         for (int i = 0; i < G; ++i) {
           float mx = row_allmax(lg[i]);
-          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          mx = max_xor16(mx);
+          mx = max_xor32(mx);
           const float mnew = fmaxf(m_ref[i], mx);
           const float alpha = fast_exp2(m_ref[i] - mnew);
           lsum[i] *= alpha;
@@ -254,8 +254,8 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < G; ++i) {
     lsum[i] = row_allsum(lsum[i]);
-    lsum[i] += __shfl_xor(lsum[i], 16, 64);
-    lsum[i] += __shfl_xor(lsum[i], 32, 64);
+    lsum[i] = add_xor16(lsum[i]);
+    lsum[i] = add_xor32(lsum[i]);
   }
   // oacc[c][i] of lane (grp, row16) = O[row 4 grp + i][channel 16c + row16]: rows 0..3 (grp 0) hi, 4..7 (grp 1) lo
   const bool writer = grp == 0;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
     const float inv = 1.0f / lsum[i];
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const float o = oacc[c][i] + __shfl_down(oacc[c][i], 16, 64);
+      const float o = add_xor16(oacc[c][i]);       // hi rows + lo rows
       if (writer) {
         if (p.num_splits == 1)
           store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + head) * D + 16 * c + row16, o * inv);
