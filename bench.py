@@ -78,8 +78,21 @@ def fill(w, saw, dev, cache, kv16=None, chunk=8192):
     return pt
 
 
-def time_calls(fn, iters, warmup):
+SETTLE_S = 0.15              # untimed calls before every measurement: after an idle gap the clocks need ~0.1 s to come back up
+
+
+def _settle(fns, seconds):
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            for fn in fns:
+                fn()
+        torch.cuda.synchronize()
+
+
+def time_calls(fn, iters, warmup, settle=SETTLE_S):
     """Median / mean of per-call durations measured with events on the current stream."""
+    _settle([fn], settle)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -93,9 +106,10 @@ def time_calls(fn, iters, warmup):
     return float(np.median(ts)), float(ts.mean()), float(np.percentile(ts, 10)), float(np.percentile(ts, 90))
 
 
-def time_interleaved(fns, iters, warmup):
+def time_interleaved(fns, iters, warmup, settle=SETTLE_S):
     """Median per-call duration (us) of each of several callables, called in turn (a, b, c, a, b, c ...)
     so that clock drift over the run hits all of them alike and their ratios stay meaningful."""
+    _settle(fns, settle)
     for _ in range(warmup):
         for fn in fns:
             fn()
