@@ -8,6 +8,7 @@
 //   sum_t p_t v^_t = sum_t (p_t s_t) c_t - sum_t p_t s_t z_t
 // Logits are kept in base-2 units (log2 e folded into q~) so the softmax uses exp2.
 #include "saw_decode.h"
+#include "saw_wave_util.h"
 
 namespace saw {
 
@@ -347,29 +348,23 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
     return;
   }
   __shared__ float wgt[1024];
-  __shared__ float red[NG][D];
+  __shared__ __attribute__((aligned(16))) float red[NG][D];
   __shared__ float wred[2][NW];
   const int ns = (L + p.chunk_tokens - 1) / p.chunk_tokens;
   const float* base = p.ws + ((int64_t)b * p.n_q_heads + j) * p.num_splits * (D + 2);
-  // reference maximum over the splits
-  float mm = -INFINITY;
-  for (int s = tid; s < ns; s += NT) mm = fmaxf(mm, base[s * (D + 2)]);
-#pragma unroll
-  for (int mk = 1; mk < 64; mk <<= 1) mm = fmaxf(mm, __shfl_xor(mm, mk, SAW_WAVE));
+  // Every split's (max, sum) pair is read once, by thread s (the launch gives the block at least as
+  // many threads as there are splits): reference maximum, then weights and the denominator.
+  float2 ml = make_float2(-INFINITY, 0.f);
+  if (tid < ns) ml = *(const float2*)(base + (int64_t)tid * (D + 2));
+  float mm = max_xor32(max_xor16(row_allmax(ml.x)));
   if (lane == 0) wred[0][wave] = mm;
   __syncthreads();
   mm = wred[0][0];
 #pragma unroll
   for (int k = 1; k < NW; ++k) mm = fmaxf(mm, wred[0][k]);
-  // per-split weights and the denominator
-  float den = 0.f;
-  for (int s = tid; s < ns; s += NT) {
-    const float a = fast_exp2(base[s * (D + 2)] - mm);
-    wgt[s] = a;
-    den = fmaf(a, base[s * (D + 2) + 1], den);
-  }
-#pragma unroll
-  for (int mk = 1; mk < 64; mk <<= 1) den += __shfl_xor(den, mk, SAW_WAVE);
+  const float a_mine = (tid < ns) ? fast_exp2(ml.x - mm) : 0.f;
+  if (tid < ns) wgt[tid] = a_mine;
+  float den = add_xor32(add_xor16(row_allsum(a_mine * ml.y)));
   if (lane == 0) wred[1][wave] = den;
   __syncthreads();
   den = wred[1][0];
@@ -392,14 +387,19 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
     __syncthreads();                  // every read of red[][] above is done
     if (g == 0) x[c] = o;
     __syncthreads();
-    for (int st = 1; st < p.had_block; st <<= 1) {
-      if (tid < D / 2) {              // each butterfly pair is owned by one thread
-        const int i = (tid / st) * 2 * st + (tid % st);
-        const float a = x[i], bb = x[i + st];
-        x[i] = a + bb;
-        x[i + st] = a - bb;
-      }
+    if (D == 128) {                   // one wavefront, three register passes, no block barriers in between
+      if (wave == 0) wave_lds_fwht128(x, 1, p.had_block, lane);
       __syncthreads();
+    } else {
+      for (int st = 1; st < p.had_block; st <<= 1) {
+        if (tid < D / 2) {            // each butterfly pair is owned by one thread
+          const int i = ((tid & ~(st - 1)) << 1) | (tid & (st - 1));
+          const float a = x[i], bb = x[i + st];
+          x[i] = a + bb;
+          x[i + st] = a - bb;
+        }
+        __syncthreads();
+      }
     }
     o = x[c] * had_norm(p.had_block);
     if (p.has_signs) o = apply_sign(p.signs, c, o);             // (o~ H_blk) diag(sigma) = o~ R^T
