@@ -60,9 +60,15 @@ __device__ __forceinline__ float dppf(float v) {
 // XS = number of register-to-register butterfly stages after the MFMA (0: h <= 32 or no rotation,
 // 1: h = 64, 2: h = 128) when K and V agree; XS = -1 decides per wavefront at run time (K-only
 // or V-only rotation).
-template <int D, int DT, int XS>
+// HP = 2 ("head pair", for head_dim 64 with an even number of kv heads): the wavefront takes two
+// neighbouring heads of 64 channels as one row of D = 128 values (they are contiguous in the input
+// and their code tiles and metadata are contiguous in the cache), so that loads, staging and the
+// matrix products run exactly as for head_dim 128; only the min/max, the scales and the addresses
+// are per head.
+template <int D, int DT, int XS, int HP = 1>
 __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaParams p) {
-  constexpr int ROWB = D * 2;            // bytes of one token's head vector
+  constexpr int DH = D / HP;             // channels of one head (D itself unless HP = 2: then 64)
+  constexpr int ROWB = D * 2;            // bytes of one token's head vector (or head pair)
   constexpr int XC = ROWB / 16;          // 16-byte chunks per vector (16 | 8)
   constexpr int NA = D / 32;             // 32-channel groups per vector (4 | 2)
   constexpr int RP = 256 / ROWB;         // token rows per 256 bytes of LDS (1 | 2)
@@ -70,12 +76,13 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   constexpr int NV = 8 * NA;             // output values per lane
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
-  const int n_kinds = 2 * p.n_kv_heads;                       // (K|V, head) combinations
+  const int n_heads_w = p.n_kv_heads / HP;                    // heads (or head pairs) a tensor has
+  const int n_kinds = 2 * n_heads_w;                          // (K|V, head or head pair) combinations
   const int kind_raw = blockIdx.y * 4 + __builtin_amdgcn_readfirstlane(wave);
   const bool wave_live = kind_raw < n_kinds;                  // wave-uniform
   const int kind = wave_live ? kind_raw : 0;                  // an idle wavefront shadows kind 0 and stores nothing
-  const int which = kind >= p.n_kv_heads ? 1 : 0;
-  const int head = kind - which * p.n_kv_heads;
+  const int which = kind >= n_heads_w ? 1 : 0;
+  const int head = (kind - which * n_heads_w) * HP;           // (first) head of this wavefront
   const int64_t t0 = (int64_t)blockIdx.x * 16;
   const bool rot = p.rot[which] != 0;
 
@@ -90,7 +97,7 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     const int tok = off / ROWB, x = (off % ROWB) / 16;
     const int64_t t = min(t0 + tok, p.T - 1);                  // tokens past the end shadow the last one; never stored
     // (the input is read once and the cache written once: both are marked streaming, "nt")
-    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * D + 8 * x));
+    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * DH + 8 * x));
   }
   // this lane's token (column n16 of the tile) and where it goes
   const int64_t t_mine = t0 + n16;
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   u32x4 sflip = u32x4{0u, 0u, 0u, 0u};
   if (p.has_signs && rot) {                                     // wavefront-uniform
     uint32_t sx[4];
-    sign_pairs(p.signs, 8 * (lane % (ROWB / 16)), sx);
+    sign_pairs(p.signs, (8 * (lane % (ROWB / 16))) % DH, sx);
     sflip = u32x4{sx[0], sx[1], sx[2], sx[3]};
   }
 #pragma unroll
@@ -177,38 +184,43 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   }
   const float norm = rot ? had_norm(p.had_block) : 1.0f;
 
-  // ---- token-wise min / max: in-lane, then the four rows holding the same token ----
-  float mn = y[0], mx = y[0];
-#pragma unroll
-  for (int i = 1; i < NV; ++i) { mn = fminf(mn, y[i]); mx = fmaxf(mx, y[i]); }
-  mn = fminf(mn, __shfl_xor(mn, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-  mn = fminf(mn, __shfl_xor(mn, 32, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-
-  // ---- scale / zero (App. A.1), quantise, pack ----
-  const float range = mx - mn;
-  float inv, zq, s_store, z_store;
-  if (range > 0.0f) {
-    inv = 15.0f / range;
-    s_store = range * (norm * (1.0f / 15.0f));
-    zq = rintf(-mn * inv);
-    z_store = zq;
-  } else {  // constant vector
-    inv = 0.0f;
-    zq = 0.0f;
-    s_store = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
-    z_store = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
-  }
+  // ---- token-wise min / max per head: in-lane, then the four rows holding the same token ----
+  constexpr int NVH = NV / HP;                                // this lane's values of one head
+  float s_store[HP], z_store[HP];
   uint32_t packed[NA];
 #pragma unroll
-  for (int a = 0; a < NA; ++a) {
-    uint32_t w = 0;
+  for (int hh = 0; hh < HP; ++hh) {
+    float mn = y[NVH * hh], mx = y[NVH * hh];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float c = rintf(y[8 * a + i] * inv) + zq;
-      c = __builtin_amdgcn_fmed3f(c, 0.0f, 15.0f);
-      w |= ((uint32_t)c) << (4 * i);
+    for (int i = 1; i < NVH; ++i) { mn = fminf(mn, y[NVH * hh + i]); mx = fmaxf(mx, y[NVH * hh + i]); }
+    mn = fminf(mn, __shfl_xor(mn, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mn = fminf(mn, __shfl_xor(mn, 32, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+    // ---- scale / zero (App. A.1), quantise, pack ----
+    const float range = mx - mn;
+    float inv, zq;
+    if (range > 0.0f) {
+      inv = 15.0f / range;
+      s_store[hh] = range * (norm * (1.0f / 15.0f));
+      zq = rintf(-mn * inv);
+      z_store[hh] = zq;
+    } else {  // constant vector
+      inv = 0.0f;
+      zq = 0.0f;
+      s_store[hh] = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
+      z_store[hh] = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
     }
-    packed[a] = w;                                              // dword 4a + rg of the token's code row
+#pragma unroll
+    for (int a = (NA / HP) * hh; a < (NA / HP) * (hh + 1); ++a) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float c = rintf(y[8 * a + i] * inv) + zq;
+        c = __builtin_amdgcn_fmed3f(c, 0.0f, 15.0f);
+        w |= ((uint32_t)c) << (4 * i);
+      }
+      packed[a] = w;                                            // dword 4 (a % (NA / HP)) + rg of the token's code row of head hh
+    }
   }
   if (!wave_live) return;
 
@@ -221,26 +233,33 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   const int seq0 = __builtin_amdgcn_readfirstlane(slot.x);
   const int pos0 = __builtin_amdgcn_readfirstlane(slot.y);
   const bool aligned = __all(ok && slot.x == seq0 && slot.y == pos0 + n16) && ((pos0 & 15) == 0);
+  constexpr int NAH = NA / HP;                                // 32-channel groups of one head
   if (aligned) {
     const int page0 = __builtin_amdgcn_readfirstlane(page);
     const int64_t vec0 = ((int64_t)page0 * p.n_kv_heads + head) * 16;
     // transpose the code dwords through LDS so that every lane writes 16 contiguous bytes
-    uint32_t* const ob = (uint32_t*)stage;                     // [token][D/8 dwords]
+    // (a head pair's two tiles follow each other in the cache, so they leave as one run)
+    uint32_t* const ob = (uint32_t*)stage;                     // [head of the pair][token][DH/8 dwords]
 #pragma unroll
-    for (int a = 0; a < NA; ++a) ob[n16 * (D / 8) + 4 * a + rg] = packed[a];
+    for (int a = 0; a < NA; ++a) ob[(a / NAH) * (16 * DH / 8) + n16 * (DH / 8) + 4 * (a % NAH) + rg] = packed[a];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (lane < 16 * (D / 2) / 16)
-      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(p.codes[which] + vec0 * (D / 2) + 16 * lane));
-    if (rg == 0) *(float2*)(p.meta[which] + (vec0 + n16) * 2) = make_float2(s_store, z_store);
+      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(p.codes[which] + vec0 * (DH / 2) + 16 * lane));
+#pragma unroll
+    for (int hh = 0; hh < HP; ++hh)
+      if (rg == hh) *(float2*)(p.meta[which] + (vec0 + 16 * hh + n16) * 2) = make_float2(s_store[hh], z_store[hh]);
     return;
   }
   if (!ok) return;
-  const int64_t vec = ((int64_t)page * p.n_kv_heads + head) * 16 + (slot.y & 15);
 #pragma unroll
-  for (int a = 0; a < NA; ++a) ((uint32_t*)(p.codes[which] + vec * (D / 2)))[4 * a + rg] = packed[a];
-  if (rg == 0) *(float2*)(p.meta[which] + vec * 2) = make_float2(s_store, z_store);
+  for (int hh = 0; hh < HP; ++hh) {
+    const int64_t vec = ((int64_t)page * p.n_kv_heads + head + hh) * 16 + (slot.y & 15);
+#pragma unroll
+    for (int a = NAH * hh; a < NAH * (hh + 1); ++a) ((uint32_t*)(p.codes[which] + vec * (DH / 2)))[4 * (a % NAH) + rg] = packed[a];
+    if (rg == hh) *(float2*)(p.meta[which] + vec * 2) = make_float2(s_store[hh], z_store[hh]);
+  }
 }
 
 int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
@@ -261,7 +280,8 @@ int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt
   const int D = c->head_dim;
   const int64_t tblocks = (T + 15) / 16;
   if (tblocks > 0x7fffffffLL) return SAW_EINVAL;
-  const int kblocks = (2 * c->n_kv_heads + 3) / 4;
+  const bool pair64 = D == 64 && (c->n_kv_heads % 2) == 0;      // two 64-channel heads per wavefront
+  const int kblocks = (2 * (c->n_kv_heads / (pair64 ? 2 : 1)) + 3) / 4;
   if (kblocks > 65535) return SAW_EINVAL;
   dim3 grid((unsigned)tblocks, kblocks), block(256);
   const int h = c->had_block;
@@ -274,11 +294,20 @@ int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt
     case 2: rotate_quant_store_mfma_kernel<DD, TT, (DD == 128 ? 2 : 1)><<<grid, block, 0, st>>>(p); break; \
     default: rotate_quant_store_mfma_kernel<DD, TT, -1><<<grid, block, 0, st>>>(p); break;             \
   }
-  if (D == 128 && dt == SAW_BF16) { SAW_LAUNCH(128, SAW_BF16) }
+#define SAW_LAUNCH_PAIR(TT)                                                                             \
+  switch (xs) {                                                                                        \
+    case 0: rotate_quant_store_mfma_kernel<128, TT, 0, 2><<<grid, block, 0, st>>>(p); break;           \
+    case 1: case 2: rotate_quant_store_mfma_kernel<128, TT, 1, 2><<<grid, block, 0, st>>>(p); break;   \
+    default: rotate_quant_store_mfma_kernel<128, TT, -1, 2><<<grid, block, 0, st>>>(p); break;         \
+  }
+  if (pair64 && dt == SAW_BF16) { SAW_LAUNCH_PAIR(SAW_BF16) }
+  else if (pair64) { SAW_LAUNCH_PAIR(SAW_F16) }
+  else if (D == 128 && dt == SAW_BF16) { SAW_LAUNCH(128, SAW_BF16) }
   else if (D == 128) { SAW_LAUNCH(128, SAW_F16) }
   else if (dt == SAW_BF16) { SAW_LAUNCH(64, SAW_BF16) }
   else { SAW_LAUNCH(64, SAW_F16) }
 #undef SAW_LAUNCH
+#undef SAW_LAUNCH_PAIR
   return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
 }
 

@@ -133,7 +133,7 @@ def make_workload(name: str, rep: int = 0, **over) -> Workload:
     return Workload(name=name, seed=seed, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_size=P,
                     had_block=h, dtype=dtype, seq_lens=seq_lens, page_table=pt, num_pages=num_pages,
                     k_chan_scale=ks, v_chan_scale=vs, rotate_mask=over.get("rotate_mask", 3),
-                    signs=random_signs(d, over["sign_seed"]) if "sign_seed" in over else None)
+                    signs=random_signs(d, over["sign_seed"]) if over.get("sign_seed") is not None else None)
 
 
 def random_signs(d: int, seed: int) -> np.ndarray:

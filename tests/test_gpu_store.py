@@ -57,6 +57,17 @@ def test_rotate_mask(saw, mask):
     _run(saw, w)
 
 
+@pytest.mark.parametrize("Hkv", [1, 2, 3, 6])
+@pytest.mark.parametrize("h,mask", [(64, 3), (16, 1), (32, 2), (1, 3)])
+def test_d64_head_pairs_and_odd_head_counts(saw, Hkv, h, mask):
+    """head_dim 64: an even head count takes the two-heads-per-wavefront path, an odd one the
+    one-head path; whole pages, ragged ends and shuffled token order (per-token placement)."""
+    w = synth.make_workload("prefill_mha", batch=2, seq_lens=[83, 16], n_kv_heads=Hkv, n_q_heads=Hkv,
+                            had_block=h, rotate_mask=mask, sign_seed=3 if h == 32 else None)
+    _run(saw, w)
+    _run(saw, w, order_rng=np.random.default_rng(Hkv))
+
+
 def test_heavy_tailed_ragged_batch(saw):
     w = synth.make_workload("highconc", batch=9, ctx=(1, 300))
     _run(saw, w, order_rng=np.random.default_rng(5))
