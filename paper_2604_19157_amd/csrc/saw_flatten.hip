@@ -45,19 +45,25 @@ struct FlattenParams {
   SignBits signs;               // R = diag(sigma) H_blk: rotating back ends with the signs
 };
 
-template <int D, int ODT>
+// HP = 2 ("head pair", for head_dim 64 with an even number of kv heads): the wavefront takes two
+// neighbouring heads as one row of D = 128 values.  Their two code tiles are contiguous in the cache
+// and their output rows are contiguous in the dense buffer; the tiles are re-ordered token-major
+// on their way into LDS, after which everything runs as for head_dim 128 with per-head (scale, zero).
+template <int D, int ODT, int HP = 1>
 __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
-  constexpr int RB = D / 2;              // code bytes of one token's head vector (64 | 32)
+  constexpr int DH = D / HP;             // channels of one head
+  constexpr int RB = D / 2;              // code bytes of one token's head vector or head pair (64 | 32)
   constexpr int XC = RB / 16;            // 16-byte chunks per vector (4 | 2)
   constexpr int NA = D / 32;             // 32-channel groups per vector (4 | 2)
   constexpr int FSH = (D == 128) ? 2 : 3;  // swizzle: chunk x of token t sits at x ^ ((t >> FSH) & (XC-1))
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n16 = lane & 15, rg = lane >> 4;
-  const int kind = blockIdx.x * 4 + wave;                     // (K|V, head)
-  if (kind >= 2 * p.n_kv_heads) return;
-  const int which = kind >= p.n_kv_heads ? 1 : 0;
-  const int head = kind - which * p.n_kv_heads;
+  const int n_heads_w = p.n_kv_heads / HP;                    // heads (or head pairs) of a tensor
+  const int kind = blockIdx.x * 4 + wave;                     // (K|V, head or head pair)
+  if (kind >= 2 * n_heads_w) return;
+  const int which = kind >= n_heads_w ? 1 : 0;
+  const int head = (kind - which * n_heads_w) * HP;           // (first) head of this wavefront
   if (p.out[which] == nullptr) return;
   const int lp = p.first_page + blockIdx.z * 65535 + blockIdx.y;   // logical page of the sequence
   if (16 * lp >= p.pos_end) return;
@@ -69,14 +75,21 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   __shared__ __attribute__((aligned(16))) uint8_t otile_all[(ODT == SAW_F32) ? 1 : 4][(ODT == SAW_F32) ? 16 : 16 * 2 * D];   // 16-bit outputs: a tile of output rows
   uint8_t* const stage = stage_all[wave];
 
-  const uint8_t* tile = p.codes[which] + ((int64_t)pid * p.n_kv_heads + head) * (16 * RB);
+  const uint8_t* tile = p.codes[which] + ((int64_t)pid * p.n_kv_heads + head) * (16 * (DH / 2));
   const float* mrow = p.meta[which] + ((int64_t)pid * p.n_kv_heads + head) * 32;
   if (lane < 16 * XC) {
-    const int tok = lane / XC, x = lane % XC;
+    // 16-byte chunk `lane` of the tile(s): token tok, chunk x of the token's (pair) row
+    int tok = lane / XC, x = lane % XC;
+    if (HP == 2) {                                            // [head][token][32 B] -> token-major
+      tok = (lane % 32) / 2;
+      x = 2 * (lane / 32) + (lane % 2);
+    }
     const u32x4 v = *(const u32x4*)(tile + 16 * lane);
     *(u32x4*)(stage + tok * RB + 16 * (x ^ ((tok >> FSH) & (XC - 1)))) = v;
   }
-  const float2 sz = *(const float2*)(mrow + 2 * n16);         // (scale, zero) of this lane's token
+  float2 szh[HP];                                             // (scale, zero) of this lane's token, per head
+#pragma unroll
+  for (int hh = 0; hh < HP; ++hh) szh[hh] = *(const float2*)(mrow + 32 * hh + 2 * n16);
 
   // ---- the +/-1 matrix (see the store kernel): A[m][k], lane (m = n16, k-group = rg) ----
   // k runs over the nibble order the unpack produces: (n0, n4, n1, n5, n2, n6, n3, n7).
@@ -142,16 +155,22 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   // un-rotated read-back: every channel carries (z + 128); rotated back: only the first channel
   // of each Hadamard block carries h (z + 128), the rest cancel exactly.
   const int h = unrot ? p.had_block : 1;
-  const float zoff = (sz.y + 128.0f) * (float)h;
-  const float sc = sz.x * (unrot ? had_norm(p.had_block) : 1.0f);
+  float zoff_h[HP], sc_h[HP];
+#pragma unroll
+  for (int hh = 0; hh < HP; ++hh) {
+    zoff_h[hh] = (szh[hh].y + 128.0f) * (float)h;
+    sc_h[hh] = szh[hh].x * (unrot ? had_norm(p.had_block) : 1.0f);
+  }
+  constexpr int NAH = NA / HP;                                // 32-channel groups of one head
   const int pos = 16 * lp + n16;
   // Channel 32a + 8rg + i carries the zero-point term iff it is the first of its Hadamard block:
   // every channel when nothing is rotated back (h = 1), otherwise only i = 0 can be.
   if (ODT == SAW_F32) {
     if (pos < p.pos_begin || pos >= p.pos_end) return;
-    const int64_t obase = (int64_t)(pos - p.pos_begin) * p.token_stride + head * D;
+    const int64_t obase = (int64_t)(pos - p.pos_begin) * p.token_stride + head * DH;
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
+      const float zoff = zoff_h[a / NAH], sc = sc_h[a / NAH];
       float o[8];
       if (h == 1) {                                            // wavefront-uniform
 #pragma unroll
@@ -164,7 +183,7 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
       }
       if (p.has_signs && unrot) {                              // wavefront-uniform
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = apply_sign(p.signs, 32 * a + 8 * rg + i, o[i]);
+        for (int i = 0; i < 8; ++i) o[i] = apply_sign(p.signs, (32 * a + 8 * rg + i) % DH, o[i]);
       }
       float* dst = (float*)p.out[which] + obase + 32 * a + 8 * rg;
       *(f32x4*)dst = f32x4{o[0], o[1], o[2], o[3]};
@@ -180,6 +199,7 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
   uint8_t* const orow = otile_all[wave];
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
+    const float zoff = zoff_h[a / NAH], sc = sc_h[a / NAH];
     float o[8];
     if (h == 1) {                                              // wavefront-uniform
 #pragma unroll
@@ -200,7 +220,7 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
     }
     if (p.has_signs && unrot) {                                // wavefront-uniform
       uint32_t sx[4];
-      sign_pairs(p.signs, 32 * a + 8 * rg, sx);
+      sign_pairs(p.signs, (32 * a + 8 * rg) % DH, sx);
 #pragma unroll
       for (int i = 0; i < 4; ++i) w4[i] ^= sx[i];
     }
@@ -216,7 +236,7 @@ __global__ __launch_bounds__(256) void flatten_dequant_kernel(FlattenParams p) {
     const int rpos = 16 * lp + r;
     const u32x4 v = *(const u32x4*)(orow + r * (2 * D) + 16 * (c ^ (r & (NC - 1))));
     if (rpos >= p.pos_begin && rpos < p.pos_end)
-      *(u32x4*)((uint16_t*)p.out[which] + (int64_t)(rpos - p.pos_begin) * p.token_stride + head * D + 8 * c) = v;
+      *(u32x4*)((uint16_t*)p.out[which] + (int64_t)(rpos - p.pos_begin) * p.token_stride + head * DH + 8 * c) = v;
   }
 }
 
@@ -240,14 +260,15 @@ int launch_flatten(const saw_cache_t* c, const int32_t* pt_row, int32_t pos_begi
   const int n_pages = (pos_end + 15) / 16 - p.first_page;
   // (K|V, head) groups vary fastest, so blocks that run together write neighbouring pieces of the
   // same token rows
-  dim3 grid((2 * c->n_kv_heads + 3) / 4, n_pages < 65535 ? n_pages : 65535, (n_pages + 65534) / 65535), block(256);
-#define SAW_FLAT(DD)                                                                              \
+  const bool pair64 = c->head_dim == 64 && (c->n_kv_heads % 2) == 0;   // two 64-channel heads per wavefront
+  dim3 grid((2 * (c->n_kv_heads / (pair64 ? 2 : 1)) + 3) / 4, n_pages < 65535 ? n_pages : 65535, (n_pages + 65534) / 65535), block(256);
+#define SAW_FLAT(DD, HH)                                                                          \
   switch (out_dtype) {                                                                            \
-    case SAW_BF16: flatten_dequant_kernel<DD, SAW_BF16><<<grid, block, 0, st>>>(p); break;         \
-    case SAW_F16: flatten_dequant_kernel<DD, SAW_F16><<<grid, block, 0, st>>>(p); break;           \
-    default: flatten_dequant_kernel<DD, SAW_F32><<<grid, block, 0, st>>>(p); break;                \
+    case SAW_BF16: flatten_dequant_kernel<DD, SAW_BF16, HH><<<grid, block, 0, st>>>(p); break;     \
+    case SAW_F16: flatten_dequant_kernel<DD, SAW_F16, HH><<<grid, block, 0, st>>>(p); break;       \
+    default: flatten_dequant_kernel<DD, SAW_F32, HH><<<grid, block, 0, st>>>(p); break;            \
   }
-  if (c->head_dim == 128) { SAW_FLAT(128) } else { SAW_FLAT(64) }
+  if (pair64) { SAW_FLAT(128, 2) } else if (c->head_dim == 128) { SAW_FLAT(128, 1) } else { SAW_FLAT(64, 1) }
 #undef SAW_FLAT
   return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
 }

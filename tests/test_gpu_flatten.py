@@ -108,3 +108,14 @@ def test_full_size_prefill_range(saw, name, dtype):
     """32768 tokens, every element compared (the size the benchmark times)."""
     w = synth.make_workload(name)
     _case(saw, w, True, dtype, ranges=[(0, 32768)])
+
+
+@pytest.mark.parametrize("Hkv", [1, 2, 3, 6])
+@pytest.mark.parametrize("h,mask", [(64, 3), (16, 1), (32, 2), (1, 3)])
+def test_d64_head_pairs_and_odd_head_counts(saw, Hkv, h, mask):
+    """head_dim 64: an even head count takes the two-heads-per-wavefront path, an odd one the one-head path."""
+    w = synth.make_workload("prefill_mha", batch=2, seq_lens=[83, 16], n_kv_heads=Hkv, n_q_heads=Hkv,
+                            had_block=h, rotate_mask=mask, sign_seed=3 if h == 32 else None)
+    _case(saw, w, True, torch.bfloat16)
+    _case(saw, w, True, torch.float32, ranges=[(3, 70)])
+    _case(saw, w, False, torch.float16)
