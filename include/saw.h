@@ -154,10 +154,11 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
  * sequence to the cache, then attend over the cache including it (Sec. 4.1: "new KV entries
  * are rotated, quantised and written" followed by the rotated-space attention).  The result is
  * that of saw_rotate_quant_store(slots = (b, seq_lens[b])) followed by saw_paged_decode_attn
- * over seq_lens[b] + 1 tokens.  With head_dim 128 and one partition per sequence (large batches)
- * both happen in ONE kernel launch: the wavefront that starts a sequence quantises and stores the
- * new token and seeds its softmax state with it; otherwise the call enqueues the store and the
- * decode kernels back to back.
+ * over seq_lens[b] + 1 tokens.  With head_dim 128 the decode kernel does the append itself: the
+ * wavefront that starts a sequence quantises and stores the new token and seeds its softmax state
+ * with it, which makes the step ONE kernel launch when there is one partition per sequence (large
+ * batches), and the decode and merge kernels otherwise.  With head_dim 64 the call enqueues the
+ * store and the decode kernels back to back.
  *
  *   K_new, V_new device, dense [B][n_kv_heads][head_dim] of kv_dtype (SAW_F16 | SAW_BF16),
  *               16-byte aligned: token b belongs to sequence b.

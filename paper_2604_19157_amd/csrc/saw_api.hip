@@ -205,14 +205,15 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
   if (!make_plan(c, B, max_pages, (int)after, 0, &plan)) return SAW_EINVAL;
   const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
-  if (fused_kernel && plan.num_splits == 1) {
-    // one launch: the decode kernel stores the new token itself and attends to it from registers;
+  if (fused_kernel) {
+    // the decode kernel stores the new token itself and attends to it from registers (with several
+    // partitions per sequence the one that starts the sequence does, and the merge kernel follows);
     // the cached range is [0, seq_lens[b]), bounded by max_seq_len as given
     plan.bound = (int)(after - 1);
     return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
                       sm_scale, out, out_dtype, ws, plan, K_new, V_new, kv_dtype, 0, (hipStream_t)stream);
   }
-  // otherwise two launches from the same call: append (token b -> sequence b at seq_lens[b]),
+  // head_dim 64: two launches from the same call: append (token b -> sequence b at seq_lens[b]),
   // then decode over seq_lens[b] + 1 tokens
   const int rc = launch_store(c, K_new, V_new, kv_dtype, B, (int64_t)c->n_kv_heads * c->head_dim, page_table, B,
                               max_pages, nullptr, seq_lens, (hipStream_t)stream);

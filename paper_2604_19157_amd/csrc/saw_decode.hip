@@ -343,14 +343,16 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
   const int c = tid % D, g = tid / D;
   const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int64_t o_idx = ((int64_t)b * p.n_q_heads + j) * D + c;
-  if (L <= 0) {
+  // partitions that ran: those that start inside the cached tokens, and with a fused append the
+  // first one in any case (it carries the step's own token)
+  const int ns = max((max(L, 0) + p.chunk_tokens - 1) / p.chunk_tokens, p.append ? 1 : 0);
+  if (ns == 0) {
     if (g == 0) store_elem(p.out, p.out_dtype, o_idx, 0.f);
     return;
   }
   __shared__ float wgt[1024];
   __shared__ __attribute__((aligned(16))) float red[NG][D];
   __shared__ float wred[2][NW];
-  const int ns = (L + p.chunk_tokens - 1) / p.chunk_tokens;
   const float* base = p.ws + ((int64_t)b * p.n_q_heads + j) * p.num_splits * (D + 2);
   // Every split's (max, sum) pair is read once, by thread s (the launch gives the block at least as
   // many threads as there are splits): reference maximum, then weights and the denominator.

@@ -119,7 +119,7 @@ def test_group_sizes(saw, Hq, Hkv):
     _case(saw, synth.make_workload("highconc", batch=3, ctx=(20, 150), n_q_heads=Hq, n_kv_heads=Hkv, dtype=torch.float16))
 
 
-def test_split_kv_and_head_dim_64_take_two_launches(saw):
+def test_split_kv_and_head_dim_64(saw):
     _case(saw, synth.make_workload("llama8b", batch=2, ctx=2000))                 # several partitions per sequence
     _case(saw, synth.make_workload("highconc", batch=3, ctx=(20, 150), n_q_heads=8, n_kv_heads=4, head_dim=64,
                                    had_block=64))
@@ -132,3 +132,17 @@ def test_unmapped_page_is_attended_but_not_stored(saw):
 
 def test_bf16_output(saw):
     _case(saw, synth.make_workload("tiny", batch=2, ctx=75), out_dtype=torch.bfloat16)
+
+
+def test_several_partitions_with_lengths_on_partition_boundaries(saw):
+    """The append inside the split-KV path: the partition that starts a sequence carries the new token
+    and the merge takes exactly the partitions that ran -- also when the cached length is zero, sits
+    exactly on a partition boundary, or one past it."""
+    w0 = synth.make_workload("tiny", batch=6, seq_lens=[0, 1, 192, 193, 384, 513])
+    cache = saw.Cache(w0.num_pages, w0.n_kv_heads, w0.head_dim, w0.had_block, w0.rotate_mask)
+    splits, chunk = saw.decode_plan(cache, w0.batch, int(w0.seq_lens.max()) + 1)
+    assert splits > 1
+    lens = [0, 1, chunk - 1, chunk, chunk + 1, 2 * chunk, min(2 * chunk + 1, 513)]
+    w = synth.make_workload("tiny", batch=len(lens), seq_lens=lens)
+    _case(saw, w)
+    _case(saw, synth.make_workload("longctx1", batch=2, seq_lens=[700, 0], had_block=64))     # G = 8
