@@ -390,7 +390,7 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
     if (g == 0) x[c] = o;
     __syncthreads();
     if (D == 128) {                   // one wavefront, three register passes, no block barriers in between
-      if (wave == 0) wave_lds_fwht128(x, 1, p.had_block, lane);
+      if (wave == 0) wave_lds_fwht128<1>(x, p.had_block, lane);
       __syncthreads();
     } else {
       for (int st = 1; st < p.had_block; st <<= 1) {

@@ -58,7 +58,7 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   wave_sync();
   float qmul = p.q_scale;
   if (p.rot_k) {
-    wave_lds_fwht128(qs, G, p.had_block, lane);
+    wave_lds_fwht128<G>(qs, p.had_block, lane);
     qmul *= had_norm(p.had_block);
   }
   const bool is_lo = row16 >= LO;
@@ -133,7 +133,7 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     wave_sync();
     float norm = 1.0f;
     if (rot) {
-      wave_lds_fwht128(yb, 1, p.had_block, lane);
+      wave_lds_fwht128<1>(yb, p.had_block, lane);
       norm = had_norm(p.had_block);
     }
     const float y0 = yb[2 * lane], y1 = yb[2 * lane + 1];
@@ -281,7 +281,11 @@ __device__ __forceinline__ int seq_of_rank(int lane, const LenClasses& lc, int s
 }
 
 constexpr int kMetaBytes = 1024;              // one batch's (scale, zero) pairs: K 4 pages x 128 B, then V
-constexpr int kWaveLds = 12 * kTileBytes + kPbufBytes + 2 * kMetaBytes;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
+// The P buffer is never a transfer target.  Up to G = 4 it also serves, at the start of a range, as the
+// query preparation's scratch (rotated query rows, 2 KB, next to 16 + 144 floats), so that this work
+// touches no memory a transfer may be writing.
+template <int G> constexpr int kPbufAlloc = (G <= 4 && (G * 128 + 16 + 144) * 4 > kPbufBytes) ? (G * 128 + 16 + 144) * 4 : kPbufBytes;
+template <int G> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc<G> + 2 * kMetaBytes;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
 
 // Two ways of giving wavefronts their work.
 //
@@ -317,14 +321,19 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int first_batch = PAIR ? 0 : wave;     // first batch of this wavefront inside its range
 
-  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds];
+  constexpr int kWaveLds = kWaveLdsG<G>;
+  // One shared array for everything, the pair counter included: with a single LDS object the
+  // compiler keeps the restrict scopes of the helpers' pointer arguments, which is what lets their LDS
+  // accesses proceed while transfers are in flight (with two objects it replaces those scopes by
+  // per-object ones and then orders every LDS access behind every transfer).
+  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds + 16];
   uint8_t* const kbuf = lds_all + wave * kWaveLds;
   uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
   uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
-  uint8_t* const mbuf_a = pbuf + kPbufBytes;   // metadata of the batch in vbuf_a / vbuf_b
+  uint8_t* const mbuf_a = pbuf + kPbufAlloc<G>;   // metadata of the batch in vbuf_a / vbuf_b
   uint8_t* const mbuf_b = mbuf_a + kMetaBytes;
-  __shared__ int shared_done;                  // PAIR: wavefronts that have left their record of the long sequence
+  int* const shared_done_p = (int*)(lds_all + NW * kWaveLds);   // PAIR: wavefronts that have left their record of the long sequence
 
   // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
   int nseg = 1;
@@ -333,7 +342,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   int sg_len[2] = {0, 0};                      // PAIR: length of the range's sequence
   if (PAIR) {
     const int B = p.batch;
-    if (threadIdx.x == 0) shared_done = 0;
+    if (threadIdx.x == 0) *shared_done_p = 0;
     __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     const int r_long = blockIdx.z, r_short = B - 1 - r_long;
@@ -504,16 +513,24 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   }
 
   // ---- the first transfers, then the q~ operands ----
-  // The first batch's tiles leave as soon as the page ids are here, so that their trip overlaps the
-  // wait for the query and the q~ preparation (whose LDS scratch is other buffers: the compiler's
-  // conservative LDS-DMA ordering makes that scratch traffic wait until the transfers have landed,
-  // which costs nothing while the query itself is still on its way).
+  // The first batch's tiles leave as soon as the page ids are here, and the q~ preparation runs while
+  // they travel.  For that, two things must hold.  Every load issued so far (page ids, query, new
+  // token) is waited for before the transfers go out: the ids are needed now anyway, and with nothing
+  // else outstanding no later wait for one of these loads can fall on the transfers.  And the
+  // preparation's LDS scratch is memory no transfer of the first batch targets, reached through
+  // restrict-qualified pointers: the compiler then orders none of its LDS accesses behind them.
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
   if (nb > 0) {
     // issued unconditionally: a wavefront without a batch of its own shadows the last batch
     const int first = min(first_batch, nb - 1);
     SAW_FETCH_V(first, vbuf_a, mbuf_a)
     SAW_FETCH_K(first, kbuf)
   }
+  // query scratch: up to G = 4 in the P buffer (no transfer ever targets it), else the second V
+  // buffer for the rows (first written by the second batch's transfers, which leave after this)
+  float* const qrows = (G <= 4) ? (float*)pbuf : (float*)vbuf_b;
+  float* const qred = (G <= 4) ? (float*)pbuf + G * 128 : (float*)pbuf;
   u32x4 a_q[4];
   float qsum[NH];
   float qmul;
@@ -529,7 +546,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       // randomised Hadamard: q diag(sigma) first (element lane + 64 j is channel lane + 64 (j & 1))
       if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, lane + 64 * (j & 1), qraw[j]);
     }
-    prepare_q<G, NH>(p, qraw, lane, (float*)vbuf_b, (float*)pbuf, a_q, qsum, qmul);
+    prepare_q<G, NH>(p, qraw, lane, qrows, qred, a_q, qsum, qmul);
   }
 
   f32x4 oacc[8];
@@ -539,8 +556,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
   if (takes_new)
-    append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (const float*)vbuf_b, qmul,
-                        (float*)pbuf, oacc, m_ref, lsum);
+    append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
+                        qred + 16, oacc, m_ref, lsum);
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.
@@ -781,7 +798,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // count; the wavefront that finds the other already counted does the rest for both.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     int before = 0;
-    if (lane == 0) before = __hip_atomic_fetch_add(&shared_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (lane == 0) before = __hip_atomic_fetch_add(shared_done_p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     before = __builtin_amdgcn_readfirstlane(before);
     if (before == 0) return;                     // a shared range is always the wavefront's last
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -810,7 +827,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // rotate back once for V (App. A.4), write the output
   float onorm = 1.0f;
   if (p.rot_v) {
-    wave_lds_fwht128(fb, G, p.had_block, lane);
+    wave_lds_fwht128<G>(fb, p.had_block, lane);
     onorm = had_norm(p.had_block);
   }
   const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;

@@ -116,47 +116,58 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// In-place un-normalised block Walsh-Hadamard transform (block size h = 16, 32, 64 or 128) of n_vec
+// In-place un-normalised block Walsh-Hadamard transform (block size h = 16, 32, 64 or 128) of NVEC
 // vectors of 128 floats in LDS (16-byte aligned), run by one wavefront.  Three passes with eight
 // values per lane in registers: strides 1-2-4 inside chunks of eight contiguous values, strides
 // 8-16-32 over values eight apart (as far as h reaches), and stride 64 when h = 128.
-__device__ __forceinline__ void wave_lds_fwht128(float* x, int n_vec, int h, int lane) {
-  for (int ch = lane; ch < n_vec * 16; ch += 64) {
-    f32x4* const p = (f32x4*)(x + 8 * ch);
-    const f32x4 a = p[0], b = p[1];
-    float e[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+template <int NVEC>
+__device__ __forceinline__ void wave_lds_fwht128(float* x, int h, int lane) {
+  // (compile-time trip counts: every loop below is unrolled, there is no loop-carried address)
 #pragma unroll
-    for (int st = 1; st < 8; st <<= 1)
+  for (int it = 0; it < (NVEC * 16 + 63) / 64; ++it) {
+    const int ch = lane + 64 * it;
+    if (NVEC * 16 % 64 == 0 || ch < NVEC * 16) {
+      f32x4* const p = (f32x4*)(x + 8 * ch);
+      const f32x4 a = p[0], b = p[1];
+      float e[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (!(k & st)) { const float u = e[k], v = e[k + st]; e[k] = u + v; e[k + st] = u - v; }
-    p[0] = f32x4{e[0], e[1], e[2], e[3]};
-    p[1] = f32x4{e[4], e[5], e[6], e[7]};
-  }
-  wave_sync();
-  for (int g = lane; g < n_vec * 16; g += 64) {
-    float* const p = x + (g >> 4) * 128 + ((g >> 3) & 1) * 64 + (g & 7);
-    float e[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) e[k] = p[8 * k];
-#pragma unroll
-    for (int st = 1; st < 8; st <<= 1) {
-      if (8 * st < h) {                                      // wavefront-uniform
+      for (int st = 1; st < 8; st <<= 1)
 #pragma unroll
         for (int k = 0; k < 8; ++k)
           if (!(k & st)) { const float u = e[k], v = e[k + st]; e[k] = u + v; e[k + st] = u - v; }
-      }
+      p[0] = f32x4{e[0], e[1], e[2], e[3]};
+      p[1] = f32x4{e[4], e[5], e[6], e[7]};
     }
+  }
+  wave_sync();
 #pragma unroll
-    for (int k = 0; k < 8; ++k) p[8 * k] = e[k];
+  for (int it = 0; it < (NVEC * 16 + 63) / 64; ++it) {
+    const int g = lane + 64 * it;
+    if (NVEC * 16 % 64 == 0 || g < NVEC * 16) {
+      float* const p = x + (g >> 4) * 128 + ((g >> 3) & 1) * 64 + (g & 7);
+      float e[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) e[k] = p[8 * k];
+#pragma unroll
+      for (int st = 1; st < 8; st <<= 1) {
+        if (8 * st < h) {                                    // wavefront-uniform
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            if (!(k & st)) { const float u = e[k], v = e[k + st]; e[k] = u + v; e[k + st] = u - v; }
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) p[8 * k] = e[k];
+    }
   }
   wave_sync();
   if (h > 64) {
-    for (int idx = lane; idx < n_vec * 64; idx += 64) {
-      const int i = (idx >> 6) * 128 + (idx & 63);
-      const float a = x[i], c = x[i + 64];
-      x[i] = a + c;
-      x[i + 64] = a - c;
+#pragma unroll
+    for (int v = 0; v < NVEC; ++v) {
+      float* const b = x + lane;
+      const float a = b[v * 128], c = b[v * 128 + 64];
+      b[v * 128] = a + c;
+      b[v * 128 + 64] = a - c;
     }
     wave_sync();
   }
