@@ -54,7 +54,7 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
   const int units = (bound + 63) / 64;                    // 64-token units
   int S = num_splits;
   if (S == 0) {
-    const int64_t items = (int64_t)B * c->n_kv_heads;
+    const int64_t items = (int64_t)B * decode_items_per_seq(c->head_dim, c->n_kv_heads);
     int64_t s = (2048 + items - 1) / items;                // one wavefront per item, ~8 per compute unit
     const int64_t max_by_min_chunk = (units + 3) / 4;      // partitions of >= 256 tokens
     if (s > max_by_min_chunk) s = max_by_min_chunk;
@@ -70,7 +70,7 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
   plan->bound = bound;
   // wavefronts per partition: only when the partitions alone cannot fill the chip (about 2560
   // wavefront slots), and while every wavefront keeps at least 8 batches (512 tokens) of its own
-  const int64_t blocks = (int64_t)B * c->n_kv_heads * plan->num_splits;
+  const int64_t blocks = (int64_t)B * decode_items_per_seq(c->head_dim, c->n_kv_heads) * plan->num_splits;
   int nw = 1;
   while (nw < 4 && blocks * nw * 2 <= 2560 && plan->chunk_tokens / (nw * 2) >= 512) nw *= 2;
   plan->waves_per_item = nw;

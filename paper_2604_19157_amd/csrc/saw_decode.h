@@ -24,16 +24,27 @@ struct DecodeParams {
   const void* v_new;
   int32_t kv_new_dtype, append;
   int32_t len_bias;     // added to every seq_lens entry (1 when a separate store launch appended a token)
-  int32_t sorted;           // d = 128 path, one block per (sequence, kv head): block z takes the sequence of length rank z
-  int32_t pair;             // d = 128 path: two-wavefront blocks over (long, short) sequence pairs
+  int32_t sorted;           // matrix-core path, one block per (sequence, kv head): block z takes the sequence of length rank z
+  int32_t pair;             // matrix-core path: two-wavefront blocks over (long, short) sequence pairs
   int32_t batch;
-  int32_t waves_per_item;   // d = 128 path: wavefronts sharing one partition (1, 2 or 4)
+  int32_t waves_per_item;   // matrix-core path: wavefronts sharing one partition (1, 2 or 4)
   int32_t has_signs;        // any bit of `signs` set
   SignBits signs;           // R = diag(sigma) H_blk for every rotated tensor and the query; outputs take R^T
 };
 
-// MFMA INT4 decode for head_dim 128 (saw_decode_mfma.hip); grid = (splits, kv heads, batch).
-int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st);
+// MFMA INT4 decode (saw_decode_mfma.hip) for head_dim 128, grid = (splits, kv heads, batch), and
+// with `head_pairs` for head_dim 64, grid = (splits, kv heads / 2, batch): see decode_head_pairs().
+int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, bool head_pairs, dim3 grid, hipStream_t st);
+
+// head_dim 64 runs on the matrix cores when the kv heads can be taken two at a time (rows of 128
+// channels again) and the pair's query heads fit the 16-row tile as hi and lo limbs.
+inline bool decode_head_pairs(int head_dim, int n_kv_heads, int G) {
+  return head_dim == 64 && n_kv_heads % 2 == 0 && (G == 1 || G == 2 || G == 4);
+}
+// (sequence, kv head) work items per sequence as the INT4 decode kernels see them
+inline int decode_items_per_seq(int head_dim, int n_kv_heads) {
+  return (head_dim == 64 && n_kv_heads % 2 == 0) ? n_kv_heads / 2 : n_kv_heads;
+}
 
 // MFMA 16-bit-KV decode for head_dim 128 and group sizes up to 4 (saw_decode_kv16_mfma.hip); false: not covered.
 bool launch_decode_kv16_mfma(const DecodeParams& p, int G, int kv_dtype, dim3 grid, hipStream_t st);

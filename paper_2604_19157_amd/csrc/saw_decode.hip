@@ -425,8 +425,10 @@ static void launch_kv16(const DecodeParams& p, dim3 grid, hipStream_t st) {
 
 int launch_decode(const DecodeParams& p, int B, int D, int G, bool kv16, int kv_dtype, hipStream_t st) {
   dim3 grid(p.num_splits, p.n_kv_heads, B);
-  if (!kv16 && D == 128) {
-    if (launch_decode_int4_mfma(p, G, B, p.waves_per_item, grid, st) != SAW_OK) return SAW_EINVAL;
+  const bool head_pairs = !kv16 && decode_head_pairs(D, p.n_kv_heads, G);
+  if (!kv16 && (D == 128 || head_pairs)) {
+    const dim3 mgrid(grid.x, head_pairs ? grid.y / 2 : grid.y, grid.z);
+    if (launch_decode_int4_mfma(p, G, B, p.waves_per_item, head_pairs, mgrid, st) != SAW_OK) return SAW_EINVAL;
     if (hipGetLastError() != hipSuccess) return SAW_ELAUNCH;
     if (p.num_splits == 1) return SAW_OK;       // the kernel wrote the output itself
   } else if (kv16 && D == 128 && launch_decode_kv16_mfma(p, G, kv_dtype, grid, st)) {
@@ -509,12 +511,14 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   //     were never better.)
   p.pair = 0;
   p.sorted = 0;
-  if (!kv16 && c->head_dim == 128 && plan.num_splits == 1 && plan.waves_per_item == 1 &&
-      (int64_t)B * c->n_kv_heads > 256 && B <= 1024) {
-    if ((int64_t)((B + 1) / 2) * c->n_kv_heads <= 1024) p.pair = 1;
+  const int G = Hq / c->n_kv_heads;
+  const int items = decode_items_per_seq(c->head_dim, c->n_kv_heads);   // head_dim 64: pairs of kv heads
+  if (!kv16 && (c->head_dim == 128 || decode_head_pairs(c->head_dim, c->n_kv_heads, G)) &&
+      plan.num_splits == 1 && plan.waves_per_item == 1 && (int64_t)B * items > 256 && B <= 1024) {
+    if ((int64_t)((B + 1) / 2) * items <= 1024) p.pair = 1;
     else p.sorted = 1;
   }
-  return launch_decode(p, B, c->head_dim, Hq / c->n_kv_heads, kv16, kv_dtype, st);
+  return launch_decode(p, B, c->head_dim, G, kv16, kv_dtype, st);
 }
 
 }  // namespace saw

@@ -46,15 +46,27 @@ constexpr float kLazyTau = 8.0f;               // reference max may lag the true
 // `qs` is LDS scratch of G*128 floats.  It is a __restrict__ parameter on purpose: that keeps
 // these LDS accesses in an alias scope of their own, so the compiler does not make them wait for
 // the LDS-DMA transfers the caller already has in flight into other buffers.
-template <int G, int NH>
+// HP (two 64-channel heads per row, see the kernel): `qraw[j]`, j < G, is channel `lane` of the j-th
+// query head of the pair; its row gets the 64 values in the half of its own kv head and zeros in
+// the other half, so that the 128-channel products below are the 64-channel ones.
+template <int G, int NH, bool HP>
 __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&qraw)[2 * G], int lane,
                                           float* __restrict__ qs, float* __restrict__ qred, u32x4 (&a_q)[4],
                                           float (&qsum)[NH], float& qmul_out) {
   constexpr int D = 128;
   constexpr int LO = (G > 4) ? 8 : 4;
   const int row16 = lane & 15, grp = lane >> 4;
+  if (HP) {
 #pragma unroll
-  for (int j = 0; j < 2 * G; ++j) qs[lane + 64 * j] = qraw[j];
+    for (int j = 0; j < G; ++j) {
+      const int kv = j / (G / 2 > 0 ? G / 2 : 1);
+      qs[j * D + 64 * kv + lane] = qraw[j];
+      qs[j * D + 64 * (1 - kv) + lane] = 0.f;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 2 * G; ++j) qs[lane + 64 * j] = qraw[j];
+  }
   wave_sync();
   float qmul = p.q_scale;
   if (p.rot_k) {
@@ -280,12 +292,13 @@ __device__ __forceinline__ int seq_of_rank(int lane, const LenClasses& lc, int s
   return __builtin_amdgcn_readfirstlane(found);
 }
 
-constexpr int kMetaBytes = 1024;              // one batch's (scale, zero) pairs: K 4 pages x 128 B, then V
+// one batch's (scale, zero) pairs: K 4 pages x 128 B, then V (twice that for a pair of 64-channel heads)
+template <bool HP> constexpr int kMetaBytes = HP ? 2048 : 1024;
 // The P buffer is never a transfer target.  Up to G = 4 it also serves, at the start of a range, as the
 // query preparation's scratch (rotated query rows, 2 KB, next to 16 + 144 floats), so that this work
 // touches no memory a transfer may be writing.
 template <int G> constexpr int kPbufAlloc = (G <= 4 && (G * 128 + 16 + 144) * 4 > kPbufBytes) ? (G * 128 + 16 + 144) * 4 : kPbufBytes;
-template <int G> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc<G> + 2 * kMetaBytes;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
+template <int G, bool HP> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc<G> + 2 * kMetaBytes<HP>;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
 
 // Two ways of giving wavefronts their work.
 //
@@ -304,13 +317,24 @@ template <int G> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc<G> + 2 *
 // in global memory; with equal lengths it degenerates to one wavefront per sequence.
 enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 
-template <int G, int NW, bool PAIR>
+//
+// HP = true ("head pair") serves head_dim 64 with an even number of kv heads: the block's kv "head" is
+// a pair of neighbouring 64-channel heads, whose code tiles ([head][token][32 B]) and metadata are
+// contiguous in a page.  The transfers re-order a pair's tiles into rows of 128 channels (head 2j's
+// 64, then head 2j+1's), the G query rows (G/2 per kv head) carry zeros in the other head's half,
+// and everything between the transfers and the epilogue runs exactly as for head_dim 128; only the
+// (scale, zero) pairs are per (token, kv head), and a row's own 64 output channels are kept.
+template <int G, int NW, bool PAIR, bool HP = false>
 // (a launch of this kernel puts at most 8 wavefronts on a compute unit, 2 per SIMD: let the
 // register allocator use the 256 registers that leaves each of them)
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void decode_int4_mfma_kernel(DecodeParams p) {
   static_assert(!PAIR || NW == 2, "a pair block has two wavefronts");
-  constexpr int D = 128;
+  static_assert(!HP || G >= 2, "a head pair has at least one query head per kv head");
+  constexpr int D = 128;                       // channels of a row (a head, or a pair of 64-channel heads)
+  constexpr int DH = HP ? 64 : 128;            // channels of one head
+  constexpr int GK = HP ? G / 2 : G;           // query heads per kv head
+  constexpr int KV = (HP && G <= 4) ? 2 : 1;   // kv heads whose metadata one lane needs (G = 8: its own only)
   constexpr int NS = (G > 4) ? 2 : 1;          // tokens per lane in the softmax layout
   constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
   constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
@@ -321,7 +345,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int first_batch = PAIR ? 0 : wave;     // first batch of this wavefront inside its range
 
-  constexpr int kWaveLds = kWaveLdsG<G>;
+  constexpr int kWaveLds = kWaveLdsG<G, HP>;
   // One shared array for everything, the pair counter included: with a single LDS object the
   // compiler keeps the restrict scopes of the helpers' pointer arguments, which is what lets their LDS
   // accesses proceed while transfers are in flight (with two objects it replaces those scopes by
@@ -332,7 +356,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
   uint8_t* const mbuf_a = pbuf + kPbufAlloc<G>;   // metadata of the batch in vbuf_a / vbuf_b
-  uint8_t* const mbuf_b = mbuf_a + kMetaBytes;
+  uint8_t* const mbuf_b = mbuf_a + kMetaBytes<HP>;
   int* const shared_done_p = (int*)(lds_all + NW * kWaveLds);   // PAIR: wavefronts that have left their record of the long sequence
 
   // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
@@ -360,8 +384,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // empty range instead of a zero row)
     if (wave == 0) {
       if (nb_long == 0 && !p.append) {                  // empty sequence: zero output row
-        for (int i = lane; i < G * D; i += 64)
-          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * D + i, 0.f);
+        for (int i = lane; i < G * DH; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * DH + i, 0.f);
       } else {
         sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut); sg_len[0] = l_long;
         sg_mode[0] = shared ? kSegShare : kSegAlone;
@@ -372,8 +396,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
         sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_len[0] = l_short; sg_mode[0] = kSegAlone;
         nseg = 1;
       } else if (!self) {
-        for (int i = lane; i < G * D; i += 64)
-          store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * D + i, 0.f);
+        for (int i = lane; i < G * DH; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * DH + i, 0.f);
       }
       if (shared) {                                     // last, so that its record can stay in this wavefront's buffers
         if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_len[0] = l_long; sg_mode[0] = kSegShare; }
@@ -393,11 +417,14 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
   const int row16 = lane & 15, grp = lane >> 4;
   const int64_t head_tile = (int64_t)kvh * kTileBytes;
-  const int64_t page_stride = (int64_t)p.n_kv_heads * kTileBytes;
-  const int64_t head_meta = (int64_t)kvh * 32;                    // floats
+  const int64_t page_stride = (int64_t)p.n_kv_heads * (HP ? kTileBytes / 2 : kTileBytes);
+  const int64_t head_meta = (int64_t)kvh * (HP ? 64 : 32);        // floats
   const int64_t page_meta = (int64_t)p.n_kv_heads * 32;
-  // lane l fills LDS chunk l of a tile = token t = l/4, stored quarter (l & 3) = (Q + t/4) & 3
-  const int g_swz = 64 * (lane >> 2) + 16 * (((lane & 3) - (lane >> 4)) & 3);
+  // lane l fills LDS chunk l of a tile = token t = l/4, stored quarter (l & 3) = (Q + t/4) & 3;
+  // quarter Q of a row is 16 source bytes: of the token's 64 (head_dim 128), or half Q & 1 of the
+  // token's 32 in head Q >> 1 of the pair, whose tiles follow each other
+  const int q_src = ((lane & 3) - (lane >> 4)) & 3;
+  const int g_swz = HP ? 512 * (q_src >> 1) + 32 * (lane >> 2) + 16 * (q_src & 1) : 64 * (lane >> 2) + 16 * q_src;
   const uint32_t kbias = bf16_bias();
   // ---- per-lane constants ----
   const int kr_off = 16 * (4 * row16 + ((grp + (row16 >> 2)) & 3));                 // K read: t = row16, Q = grp
@@ -437,8 +464,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     t_end = min(seq_len_b, t_begin + p.chunk_tokens);
     if (t_begin >= t_end && !(p.append && t_begin == 0)) {            // block-uniform
       if (p.num_splits == 1)           // empty sequence and no merge pass: the output row is zero
-        for (int i = threadIdx.x; i < G * 128; i += 64 * NW)
-          store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * 128 + i, 0.f);
+        for (int i = threadIdx.x; i < G * DH; i += 64 * NW)
+          store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * DH + i, 0.f);
       return;
     }
   }
@@ -446,19 +473,21 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // this lane's share of the G query vectors (element lane + 64 j), issued ahead of the code transfers
   uint32_t qbits[2 * G];
   {
-    const int64_t qoff = ((int64_t)b * p.n_q_heads + kvh * G) * D + lane;
+    // (the block's G query heads are contiguous: G x 128 values, or G x 64 for a head pair)
+    constexpr int NQ = HP ? G : 2 * G;
+    const int64_t qoff = ((int64_t)b * p.n_q_heads + kvh * G) * DH + lane;
     if (p.q_dtype == SAW_F32) {
 #pragma unroll
-      for (int j = 0; j < 2 * G; ++j) qbits[j] = ((const uint32_t*)p.q)[qoff + 64 * j];
+      for (int j = 0; j < 2 * G; ++j) qbits[j] = (j < NQ) ? ((const uint32_t*)p.q)[qoff + 64 * j] : 0u;
     } else {
 #pragma unroll
-      for (int j = 0; j < 2 * G; ++j) qbits[j] = ((const uint16_t*)p.q)[qoff + 64 * j];
+      for (int j = 0; j < 2 * G; ++j) qbits[j] = (j < NQ) ? ((const uint16_t*)p.q)[qoff + 64 * j] : 0u;
     }
   }
 
   // fused append: the range that starts the sequence also takes the step's new token (wavefront
   // 0 of the block when several share the range); its inputs are requested here, with the query
-  const bool takes_new = p.append && t_begin == 0 && first_batch == 0;
+  const bool takes_new = !HP && p.append && t_begin == 0 && first_batch == 0;   // (head pairs: the caller stores first)
   uint32_t new_wk = 0, new_wv = 0;
   int new_pid = -1;
   if (takes_new) {
@@ -497,11 +526,17 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       const uint8_t* vp = p.v_codes + (int64_t)SAW_PID(batch, q) * page_stride + head_tile;     \
       SAW_DMA(vp + g_swz, VDST + q * kTileBytes);                                               \
     }                                                                                           \
-    const int mq = (lane >> 3) & 3;                                                             \
+    const int mq = HP ? (lane >> 4) : (lane >> 3) & 3;                                          \
     const int id = mq == 0 ? SAW_PID(batch, 0) : mq == 1 ? SAW_PID(batch, 1)                    \
                  : mq == 2 ? SAW_PID(batch, 2) : SAW_PID(batch, 3);                             \
-    const float* mp = (lane < 32 ? p.k_meta : p.v_meta) + (int64_t)id * page_meta + head_meta + 4 * (lane & 7); \
-    SAW_DMA(mp, MDST);                                                                          \
+    if (HP) { /* a page's pairs for both heads are 256 contiguous bytes: one transfer for K, one for V */ \
+      const int64_t mo = (int64_t)id * page_meta + head_meta + 4 * (lane & 15);                 \
+      SAW_DMA(p.k_meta + mo, MDST);                                                             \
+      SAW_DMA(p.v_meta + mo, MDST + 1024);                                                      \
+    } else {                                                                                    \
+      const float* mp = (lane < 32 ? p.k_meta : p.v_meta) + (int64_t)id * page_meta + head_meta + 4 * (lane & 7); \
+      SAW_DMA(mp, MDST);                                                                        \
+    }                                                                                           \
   }
   // K tiles of `batch` into KDST (the ids were rotated by the V fetch of the same batch)
 #define SAW_FETCH_K(batch, KDST)                                                                \
@@ -544,9 +579,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       const float as_f16 = f16_to_f32(qbits[j] & 0xffffu);
       qraw[j] = q_is_f32 ? as_f32 : (q_is_bf16 ? as_bf16 : as_f16);
       // randomised Hadamard: q diag(sigma) first (element lane + 64 j is channel lane + 64 (j & 1))
-      if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, lane + 64 * (j & 1), qraw[j]);
+      if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, HP ? lane : lane + 64 * (j & 1), qraw[j]);
     }
-    prepare_q<G, NH>(p, qraw, lane, qrows, qred, a_q, qsum, qmul);
+    prepare_q<G, NH, HP>(p, qraw, lane, qrows, qred, a_q, qsum, qmul);
   }
 
   f32x4 oacc[8];
@@ -555,9 +590,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   float m_ref[NH], lsum[NH], zs[NH];
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
-  if (takes_new)
-    append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
-                        qred + 16, oacc, m_ref, lsum);
+  if constexpr (!HP) {
+    if (takes_new)
+      append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
+                          qred + 16, oacc, m_ref, lsum);
+  }
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.
@@ -571,12 +608,17 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // (issued through the builtin, not inline asm, so that the compiler's wait-count pass sees it
     // and stops guarding earlier loads, e.g. the q~ operands, with waits of its own further down)
     __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): batch bi has landed (codes in LDS, metadata)
-    f32x2 km[NS], vm[NS];
+    f32x2 km[NS][KV], vm[NS][KV];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;        // page of this lane's token
-      km[s] = *(const f32x2*)(mcur + 128 * pg + 8 * row16);
-      vm[s] = *(const f32x2*)(mcur + 512 + 128 * pg + 8 * row16);
+#pragma unroll
+      for (int kv = 0; kv < KV; ++kv) {
+        // head pair: [page][kv head][token]; with G = 8 a lane's four heads belong to kv head grp & 1
+        const int mo = HP ? 256 * pg + 128 * (G > 4 ? (grp & 1) : kv) + 8 * row16 : 128 * pg + 8 * row16;
+        km[s][kv] = *(const f32x2*)(mcur + mo);
+        vm[s][kv] = *(const f32x2*)(mcur + kMetaBytes<HP> / 2 + mo);
+      }
     }
     // K operand reads first, before the next transfers are issued.
     u32x4 kw[4];
@@ -631,10 +673,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     for (int s = 0; s < NS; ++s) {
       const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;
       valid[s] = (tok0 + 16 * pg + row16) < t_end;
-      const float kz = km[s].y + 128.f;
 #pragma unroll
       for (int i = 0; i < NH; ++i) {
-        const float v = km[s].x * fmaf(-kz, qsum[i], sraw[s][i]);
+        const int kv = (KV == 2 && i >= G / 2) ? 1 : 0;
+        const float kz = km[s][kv].y + 128.f;
+        const float v = km[s][kv].x * fmaf(-kz, qsum[i], sraw[s][i]);
         lg[s][i] = valid[s] ? v : -INFINITY;
         need |= lg[s][i] > m_ref[i] + kLazyTau;
       }
@@ -664,10 +707,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     for (int s = 0; s < NS; ++s) {
       const int pg = (G > 4) ? (2 * s + (lane >> 5)) : grp;
       const int col = 16 * pg + pcol_t;
-      const float vs = valid[s] ? vm[s].x : 0.f;
-      const float vz = valid[s] ? vm[s].y + 128.f : 0.f;
 #pragma unroll
       for (int i = 0; i < NH; ++i) {
+        const int kv = (KV == 2 && i >= G / 2) ? 1 : 0;
+        const float vs = valid[s] ? vm[s][kv].x : 0.f;
+        const float vz = valid[s] ? vm[s][kv].y + 128.f : 0.f;
         const float pr = fast_exp2(lg[s][i] - m_ref[i]);     // exp2(-inf) = 0 for masked tokens
         lsum[i] += pr;
         uint32_t h16, l16;
@@ -764,11 +808,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
     for (int i = 0; i < NH; ++i) {
       const int head = head0 + i;
-      float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (D + 2);
+      float* dst = p.ws + (((int64_t)b * p.n_q_heads + kvh * G + head) * p.num_splits + split) * (DH + 2);
+      const int own = head / GK;                  // head pair: the half of the row that is this head's
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         const float o = (G > 4) ? add_xor32(oacc[c][i]) : add_xor16(oacc[c][i]);   // hi rows + lo rows
-        if (writer && i < G) dst[2 + 16 * c + row16] = o - zs[i];
+        if (writer && i < G && (!HP || (c >> 2) == own)) dst[2 + 16 * (HP ? (c & 3) : c) + row16] = o - zs[i];
       }
       if (writer && row16 == 0 && i < G) { dst[0] = m_ref[i]; dst[1] = lsum[i]; }
     }
@@ -830,11 +875,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     wave_lds_fwht128<G>(fb, p.had_block, lane);
     onorm = had_norm(p.had_block);
   }
-  const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
+  const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * DH;
   for (int i = lane; i < G * D; i += 64) {
     float o = fb[i] * onorm;
-    if (p.rot_v && p.has_signs) o = apply_sign(p.signs, i & (D - 1), o);       // (o~ H_blk) diag(sigma) = o~ R^T
-    store_elem(p.out, p.out_dtype, obase + i, o);
+    if (p.rot_v && p.has_signs) o = apply_sign(p.signs, i & (DH - 1), o);      // (o~ H_blk) diag(sigma) = o~ R^T
+    if (HP) {                                    // a row's own 64 channels; the other half is cross terms
+      const int h = i >> 7, c = i & 127;
+      if ((c >> 6) == h / GK) store_elem(p.out, p.out_dtype, obase + h * 64 + (c & 63), o);
+    } else {
+      store_elem(p.out, p.out_dtype, obase + i, o);
+    }
   }
   wave_sync();                                   // the next range's prologue reuses these buffers
   }  // ranges of this wavefront
@@ -848,24 +898,35 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #undef SAW_LOAD_PIDS
 #undef SAW_CLAMP_PID
 
-template <int G>
+template <int G, bool HP>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
   if (p.pair) {
-    decode_int4_mfma_kernel<G, 2, true><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
+    decode_int4_mfma_kernel<G, 2, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
     return;
   }
-  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false><<<grid, dim3(256), 0, st>>>(p);
-  else if (nw == 2) decode_int4_mfma_kernel<G, 2, false><<<grid, dim3(128), 0, st>>>(p);
-  else decode_int4_mfma_kernel<G, 1, false><<<grid, dim3(64), 0, st>>>(p);
+  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false, HP><<<grid, dim3(256), 0, st>>>(p);
+  else if (nw == 2) decode_int4_mfma_kernel<G, 2, false, HP><<<grid, dim3(128), 0, st>>>(p);
+  else decode_int4_mfma_kernel<G, 1, false, HP><<<grid, dim3(64), 0, st>>>(p);
 }
 
-// `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or 4 (ignored in pair mode).
-int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, dim3 grid, hipStream_t st) {
+// `G`: query heads per kv head.  `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or
+// 4 (ignored in pair mode).  `head_pairs`: head_dim 64, grid.y = n_kv_heads / 2 blocks of two kv
+// heads each (2 G rows), G <= 4; otherwise head_dim 128 and grid.y = n_kv_heads.
+int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, bool head_pairs, dim3 grid, hipStream_t st) {
+  if (head_pairs) {
+    switch (G) {
+      case 1: launch_g<2, true>(p, B, nw, grid, st); break;
+      case 2: launch_g<4, true>(p, B, nw, grid, st); break;
+      case 4: launch_g<8, true>(p, B, nw, grid, st); break;
+      default: return SAW_EINVAL;
+    }
+    return SAW_OK;
+  }
   switch (G) {
-    case 1: launch_g<1>(p, B, nw, grid, st); break;
-    case 2: launch_g<2>(p, B, nw, grid, st); break;
-    case 4: launch_g<4>(p, B, nw, grid, st); break;
-    case 8: launch_g<8>(p, B, nw, grid, st); break;
+    case 1: launch_g<1, false>(p, B, nw, grid, st); break;
+    case 2: launch_g<2, false>(p, B, nw, grid, st); break;
+    case 4: launch_g<4, false>(p, B, nw, grid, st); break;
+    case 8: launch_g<8, false>(p, B, nw, grid, st); break;
     default: return SAW_EINVAL;
   }
   return SAW_OK;
