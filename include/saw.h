@@ -111,7 +111,7 @@ int saw_rotate_quant_store(const saw_cache_t* cache, const void* K, const void* 
                            const int32_t* slots, saw_stream_t stream);
 
 /*
- * Bytes of scratch saw_paged_decode_attn needs for these arguments (split-KV partial
+ * Bytes of scratch the decode calls need for these arguments (split-KV partial
  * results [B][n_q_heads][splits][head_dim + 2] float32, rounded up to 16 bytes).  max_seq_len and num_splits
  * have the meaning below; returns 0 on invalid arguments.
  */
@@ -119,8 +119,10 @@ size_t saw_decode_workspace_bytes(const saw_cache_t* cache, int32_t B, int32_t n
                                   int32_t max_seq_len, int32_t num_splits);
 
 /*
- * The split-KV geometry the decode calls will use for these arguments (host-side helper for
- * reporting): partitions per sequence and tokens per partition.  Either output may be NULL.
+ * The split-KV geometry saw_paged_decode_attn will use for these arguments (host-side helper
+ * for reporting): partitions per sequence and tokens per partition.  Either output may be NULL.
+ * (The 16-bit comparison call may choose more partitions for the same arguments;
+ * saw_decode_workspace_bytes covers both.)
  */
 int saw_decode_plan(const saw_cache_t* cache, int32_t B, int32_t max_seq_len, int32_t num_splits,
                     int32_t* splits_out, int32_t* chunk_tokens_out);
@@ -154,11 +156,12 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
  * sequence to the cache, then attend over the cache including it (Sec. 4.1: "new KV entries
  * are rotated, quantised and written" followed by the rotated-space attention).  The result is
  * that of saw_rotate_quant_store(slots = (b, seq_lens[b])) followed by saw_paged_decode_attn
- * over seq_lens[b] + 1 tokens.  With head_dim 128 the decode kernel does the append itself: the
+ * over seq_lens[b] + 1 tokens.  With head_dim 128, and with head_dim 64 when n_kv_heads is even
+ * and a kv head serves at most 4 query heads, the decode kernel does the append itself: the
  * wavefront that starts a sequence quantises and stores the new token and seeds its softmax state
  * with it, which makes the step ONE kernel launch when there is one partition per sequence (large
- * batches), and the decode and merge kernels otherwise.  With head_dim 64 the call enqueues the
- * store and the decode kernels back to back.
+ * batches), and the decode and merge kernels otherwise.  For the remaining head_dim 64 shapes the
+ * call enqueues the store and the decode kernels back to back.
  *
  *   K_new, V_new device, dense [B][n_kv_heads][head_dim] of kv_dtype (SAW_F16 | SAW_BF16),
  *               16-byte aligned: token b belongs to sequence b.

@@ -44,8 +44,12 @@ static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 // starts on a page boundary.  The automatic choice aims at about 2048 wavefronts (8 per compute
 // unit): one partition per sequence once the batch alone provides them, otherwise partitions of
 // at least 256 tokens, and 2 or 4 wavefronts per partition when even those are too few.
+// The INT4 kernels (`kv16` false) stay with one partition from 512 (sequence, kv head) items on:
+// their pair mode evens out ragged lengths inside the launch at any occupancy, and the merge
+// pass costs more than the extra wavefronts bring (256 sequences x 4 kv heads, 2304 tokens each:
+// 61 us against 66 us with two partitions; ragged 80 against 84; at 320 items partitions win).
 static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_len, int num_splits,
-                      SplitPlan* plan) {
+                      bool kv16, SplitPlan* plan) {
   const int64_t cap = (int64_t)max_pages * c->page_size;
   if (cap <= 0 || cap > 0x7fffffffLL) return false;
   int bound = (max_seq_len <= 0) ? (int)cap : max_seq_len;
@@ -58,6 +62,7 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
     int64_t s = (2048 + items - 1) / items;                // one wavefront per item, ~8 per compute unit
     const int64_t max_by_min_chunk = (units + 3) / 4;      // partitions of >= 256 tokens
     if (s > max_by_min_chunk) s = max_by_min_chunk;
+    if (!kv16 && items >= 512 && B <= 1024) s = 1;
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
     S = (int)s;
@@ -120,8 +125,13 @@ size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_h
   if (!c || !shape_ok(c) || B < 1 || n_q_heads < 1 || max_seq_len < 1) return 0;
   SplitPlan plan;
   const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
-  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return 0;
-  return partial_bytes(B, n_q_heads, plan.num_splits, c->head_dim);
+  // (the INT4 and the 16-bit calls may choose different partition counts: enough for either)
+  SplitPlan plan16;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, false, &plan) ||
+      !make_plan(c, B, max_pages, max_seq_len, num_splits, true, &plan16))
+    return 0;
+  return partial_bytes(B, n_q_heads, plan.num_splits > plan16.num_splits ? plan.num_splits : plan16.num_splits,
+                       c->head_dim);
 }
 
 int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_t num_splits,
@@ -130,7 +140,7 @@ int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_
   if (!shape_ok(c) || B < 1 || max_seq_len < 1) return SAW_EINVAL;
   SplitPlan plan;
   const int max_pages = (max_seq_len + c->page_size - 1) / c->page_size;
-  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, false, &plan)) return SAW_EINVAL;
   if (splits_out) *splits_out = plan.num_splits;
   if (chunk_tokens_out) *chunk_tokens_out = plan.chunk_tokens;
   return SAW_OK;
@@ -157,7 +167,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   if (!aligned16(kp) || !aligned16(vp) || !aligned16(ws)) return SAW_EINVAL;
   if (!isfinite(sm_scale)) return SAW_EINVAL;
   SplitPlan plan;
-  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, &plan)) return SAW_EINVAL;
+  if (!make_plan(c, B, max_pages, max_seq_len, num_splits, kv16, &plan)) return SAW_EINVAL;
   const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
@@ -201,8 +211,8 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
   const int64_t after = (max_seq_len <= 0 ? cap - 1 : (int64_t)max_seq_len) + 1;
   if (after > cap) return SAW_EINVAL;
   SplitPlan plan;
-  const bool fused_kernel = c->head_dim == 128;
-  if (!make_plan(c, B, max_pages, (int)after, 0, &plan)) return SAW_EINVAL;
+  const bool fused_kernel = c->head_dim == 128 || decode_head_pairs(c->head_dim, c->n_kv_heads, G);
+  if (!make_plan(c, B, max_pages, (int)after, 0, false, &plan)) return SAW_EINVAL;
   const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   if (fused_kernel) {
@@ -213,7 +223,7 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
     return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
                       sm_scale, out, out_dtype, ws, plan, K_new, V_new, kv_dtype, 0, (hipStream_t)stream);
   }
-  // head_dim 64: two launches from the same call: append (token b -> sequence b at seq_lens[b]),
+  // head_dim 64 outside the head-pair kernel: two launches from the same call: append (token b -> sequence b at seq_lens[b]),
   // then decode over seq_lens[b] + 1 tokens
   const int rc = launch_store(c, K_new, V_new, kv_dtype, B, (int64_t)c->n_kv_heads * c->head_dim, page_table, B,
                               max_pages, nullptr, seq_lens, (hipStream_t)stream);

@@ -20,7 +20,7 @@ struct DecodeParams {
   int32_t n_q_heads, n_kv_heads, max_pages, num_pages;
   int32_t had_block, rot_k, rot_v;
   int32_t num_splits, chunk_tokens, bound;
-  const void* k_new;    // fused append (d = 128 INT4 path, one partition): the step's K, V [B][Hkv][d], else null
+  const void* k_new;    // fused append (matrix-core INT4 path): the step's K, V [B][Hkv][d], else null
   const void* v_new;
   int32_t kv_new_dtype, append;
   int32_t len_bias;     // added to every seq_lens entry (1 when a separate store launch appended a token)

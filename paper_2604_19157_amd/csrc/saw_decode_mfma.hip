@@ -117,19 +117,23 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
 //         loaded by the caller early enough that nothing here waits for memory
 //   qrot  LDS, [G][128]: the (rotated) query rows before scaling; qmul their scale
 //   scr   LDS scratch of 144 floats, distinct from qrot
-template <int G, int NH>
+// HP: the 128 values are the new vectors of two neighbouring 64-channel kv heads (lanes 0-31 hold
+// the first head's channels), quantised and stored per head; `kvh` counts pairs.
+template <int G, int NH, bool HP>
 __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int lane, int L, int pid,
                                              uint32_t wk, uint32_t wv,
                                              const float* __restrict__ qrot, float qmul,
                                              float* __restrict__ scr, f32x4 (&oacc)[8],
                                              float (&m_ref)[NH], float (&lsum)[NH]) {
   constexpr int D = 128;
+  constexpr int DH = HP ? 64 : 128;  // channels of one head
   const int row16 = lane & 15, grp = lane >> 4;
   float* const yb = scr;            // [128]: rotation scratch, then the dequantised V row
   float* const lg = scr + 128;      // [G]: logits of the new token
   const int slot = L & 15;
   const bool place = pid >= 0 && pid < p.num_pages;          // otherwise attended to but not stored
-  const int64_t vec = ((int64_t)pid * p.n_kv_heads + kvh) * 16 + slot;
+  const int head = HP ? 2 * kvh + (lane >> 5) : kvh;         // kv head of this lane's two channels
+  const int64_t vec = ((int64_t)pid * p.n_kv_heads + head) * 16 + slot;
 #pragma unroll 1
   for (int which = 0; which < 2; ++which) {                  // 0: K, 1: V
     const bool rot = which ? (p.rot_v != 0) : (p.rot_k != 0);
@@ -137,8 +141,8 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     float x0, x1;
     if (p.kv_new_dtype == SAW_BF16) widen2<SAW_BF16>(w, x0, x1); else widen2<SAW_F16>(w, x0, x1);
     if (rot && p.has_signs) {                                // x diag(sigma), as the store kernel does
-      x0 = apply_sign(p.signs, 2 * lane, x0);
-      x1 = apply_sign(p.signs, 2 * lane + 1, x1);
+      x0 = apply_sign(p.signs, (2 * lane) & (DH - 1), x0);
+      x1 = apply_sign(p.signs, (2 * lane + 1) & (DH - 1), x1);
     }
     yb[2 * lane] = x0;
     yb[2 * lane + 1] = x1;
@@ -149,12 +153,15 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
       norm = had_norm(p.had_block);
     }
     const float y0 = yb[2 * lane], y1 = yb[2 * lane + 1];
-    // min and max over the 128 values: one reduction of (max, -min) pairs, rows first (DPP)
+    // min and max over the head's values (128: all lanes, 64: half of them): one reduction of
+    // (max, -min) pairs, rows first (DPP)
     float mx = row_allmax(fmaxf(y0, y1)), nmn = row_allmax(-fminf(y0, y1));
     mx = max_xor16(mx);
     nmn = max_xor16(nmn);
-    mx = max_xor32(mx);
-    nmn = max_xor32(nmn);
+    if (!HP) {
+      mx = max_xor32(mx);
+      nmn = max_xor32(nmn);
+    }
     const float mn = -nmn;
     const float range = mx - mn;
     float inv, zq, s_store, z_store;
@@ -174,8 +181,8 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     if (place) {
       uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes);
       float* meta = const_cast<float*>(which ? p.v_meta : p.k_meta);
-      codes[vec * (D / 2) + lane] = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
-      if (lane == 0) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
+      codes[vec * (DH / 2) + (lane & (DH / 2 - 1))] = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
+      if ((lane & (DH / 2 - 1)) == 0) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
     }
     const float d0 = s_store * (c0 - z_store), d1 = s_store * (c1 - z_store);
     wave_sync();                                             // every read of yb above is done
@@ -487,11 +494,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
   // fused append: the range that starts the sequence also takes the step's new token (wavefront
   // 0 of the block when several share the range); its inputs are requested here, with the query
-  const bool takes_new = !HP && p.append && t_begin == 0 && first_batch == 0;   // (head pairs: the caller stores first)
+  const bool takes_new = p.append && t_begin == 0 && first_batch == 0;
   uint32_t new_wk = 0, new_wv = 0;
   int new_pid = -1;
   if (takes_new) {
-    const int64_t e = (((int64_t)b * p.n_kv_heads + kvh) * D) / 2 + lane;
+    // (the block's new K|V values are 128 contiguous elements: one head, or a pair of 64-channel heads)
+    const int64_t e = ((int64_t)b * p.n_kv_heads * DH + (int64_t)kvh * D) / 2 + lane;
     new_wk = ((const uint32_t*)p.k_new)[e];
     new_wv = ((const uint32_t*)p.v_new)[e];
     if ((seq_len_b >> 4) < p.max_pages) new_pid = p.page_table[pt_row + (seq_len_b >> 4)];
@@ -590,11 +598,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   float m_ref[NH], lsum[NH], zs[NH];
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
-  if constexpr (!HP) {
-    if (takes_new)
-      append_token<G, NH>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
-                          qred + 16, oacc, m_ref, lsum);
-  }
+  if (takes_new)
+    append_token<G, NH, HP>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
+                            qred + 16, oacc, m_ref, lsum);
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.

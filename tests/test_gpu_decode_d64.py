@@ -97,3 +97,17 @@ def test_head_pairs_fp16_cache_input(saw):
 def test_append_then_attend(saw, B, Hq, Hkv, ctx):
     """saw_append_decode_attn at head_dim 64: the store launch, then the decode over one more token."""
     TA._case(saw, _w(batch=B, ctx=ctx, n_q_heads=Hq, n_kv_heads=Hkv))
+
+
+@pytest.mark.parametrize("h,mask,sign_seed", [(64, 3, 5), (16, 3, None), (32, 1, 6), (64, 2, None), (1, 3, None)])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (16, 4)])
+def test_append_block_sizes_masks_signs(saw, h, mask, sign_seed, Hq, Hkv):
+    """The decode kernel's own append at head_dim 64: the new token's bytes per kv head of a pair."""
+    TA._case(saw, _w(batch=4, ctx=(1, 200), n_q_heads=Hq, n_kv_heads=Hkv, had_block=h, rotate_mask=mask,
+                     sign_seed=sign_seed))
+
+
+def test_append_unmapped_page_and_odd_kv_heads(saw):
+    # (the unmapped token must open a page of its own, or cached tokens would lose their page with it)
+    TA._case(saw, _w(batch=3, seq_lens=[40, 64, 95], n_q_heads=8, n_kv_heads=4), unmapped=(1,))
+    TA._case(saw, _w(batch=3, ctx=(20, 150), n_q_heads=6, n_kv_heads=3))        # store launch + decode
