@@ -498,12 +498,16 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.append = k_new != nullptr;
   p.len_bias = len_bias;
   p.batch = B;
-  // How the d = 128 INT4 kernel hands out work when one partition covers each sequence and the
+  // How the matrix-core INT4 kernel hands out work when one partition covers each sequence and the
   // batch provides more (sequence, kv head) items than compute units (and at most 16 lengths per
   // lane for the in-kernel ranking).  A compute unit holds 8 wavefronts of this kernel, 2048 on
   // the chip:
   //   * up to 2048 items everything is resident at once and nothing rebalances later, so the
-  //     work is evened out up front: pair mode (two-wavefront blocks over (long, short) pairs);
+  //     work is evened out up front: pair mode, blocks over (long, short) pairs of sequences, of
+  //     four wavefronts while that still fits the 2048 slots and of two beyond.  Four-wavefront
+  //     blocks pay off from 768 items on (ragged 256 sequences x 4 heads: 82 -> 70 us, 96 x 8: 69
+  //     -> 62 us against two wavefronts sharing each item; equal lengths lose 6 us to the ranking
+  //     and the records; at 512 items the two ways are level);
   //   * beyond that blocks queue for slots in index order, which is list scheduling: one
   //     wavefront per item, sequences taken longest first, so the launch ends on the shortest.
   //     (Measured at 288..512 sequences x 8 heads: 173-270 us against 224-332 us in pair mode,
@@ -514,9 +518,13 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   const int G = Hq / c->n_kv_heads;
   const int items = decode_items_per_seq(c->head_dim, c->n_kv_heads);   // head_dim 64: pairs of kv heads
   if (!kv16 && (c->head_dim == 128 || decode_head_pairs(c->head_dim, c->n_kv_heads, G)) &&
-      plan.num_splits == 1 && plan.waves_per_item == 1 && (int64_t)B * items > 256 && B <= 1024) {
-    if ((int64_t)((B + 1) / 2) * items <= 1024) p.pair = 1;
-    else p.sorted = 1;
+      plan.num_splits == 1 && B <= 1024) {
+    const int64_t blocks = (int64_t)((B + 1) / 2) * items;
+    if ((int64_t)B * items >= 768 && blocks <= 512) p.pair = 4;
+    else if (plan.waves_per_item == 1 && (int64_t)B * items > 256) {
+      if (blocks <= 1024) p.pair = 2;
+      else p.sorted = 1;
+    }
   }
   return launch_decode(p, B, c->head_dim, G, kv16, kv_dtype, st);
 }

@@ -314,14 +314,19 @@ template <int G, bool HP> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc
 // at the end; with several partitions the result goes to the workspace for the merge kernel.
 //
 // PAIR = true (one partition per sequence, batch too large for every wavefront to need help):
-// a block of two wavefronts owns the sequences at ranks r and B-1-r of the longest-first order
-// and splits their batches evenly: wavefront 0 takes the first half of the total from the long
-// sequence, wavefront 1 the whole short sequence and then the rest of the long one.  Each leaves
-// its share of the long sequence as a (max, sum, accumulator) record in its own LDS buffers and
-// counts itself in with an LDS atomic; whichever comes second combines the two records and writes
-// the output, so nobody waits for anybody.  Every wavefront of the launch then streams the same
-// number of tokens (give or take a batch) however ragged the batch is, with no partial results
-// in global memory; with equal lengths it degenerates to one wavefront per sequence.
+// a block of NW = 2 or 4 wavefronts owns the sequences at ranks r and B-1-r of the longest-first
+// order and splits their batches, laid end to end (long, then short), into NW equal shares: a
+// wavefront gets a stretch of the long sequence, of the short one, or - one wavefront per block
+// at most - the end of the long one and the start of the short one.  A sequence that one
+// wavefront covers alone is finished by it; otherwise each wavefront leaves its share as a
+// (max, sum, accumulator) record in LDS and counts itself in with an LDS atomic, and whichever
+// comes last combines the records (always in wavefront order) and writes the output, so nobody
+// waits for anybody.  The wavefront with two stretches takes the short sequence's first, so the
+// record it leaves in its own buffers is its last act; the short sequence's record, if that one
+// is shared too (NW = 4 only), goes to a spare slot of the block.  Every wavefront of the launch
+// then streams the same number of tokens (give or take a batch) however ragged the batch is,
+// with no partial results in global memory.  NW = 4 keeps the chip's 2048 wavefront slots busy
+// when there are only 512 to 1024 (sequence, kv head) items.
 enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 
 //
@@ -336,7 +341,7 @@ template <int G, int NW, bool PAIR, bool HP = false>
 // register allocator use the 256 registers that leaves each of them)
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void decode_int4_mfma_kernel(DecodeParams p) {
-  static_assert(!PAIR || NW == 2, "a pair block has two wavefronts");
+  static_assert(!PAIR || NW == 2 || NW == 4, "a pair block has two or four wavefronts");
   static_assert(!HP || G >= 2, "a head pair has at least one query head per kv head");
   constexpr int D = 128;                       // channels of a row (a head, or a pair of 64-channel heads)
   constexpr int DH = HP ? 64 : 128;            // channels of one head
@@ -357,23 +362,29 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // compiler keeps the restrict scopes of the helpers' pointer arguments, which is what lets their LDS
   // accesses proceed while transfers are in flight (with two objects it replaces those scopes by
   // per-object ones and then orders every LDS access behind every transfer).
-  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds + 16];
+  constexpr int kRecFloats = G * 128 + 2 * G;                   // a record: accumulator rows, then (max, sum) per row
+  constexpr int kSpareBytes = (PAIR && NW > 2) ? kRecFloats * 4 : 0;
+  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds + 16 + kSpareBytes];
   uint8_t* const kbuf = lds_all + wave * kWaveLds;
   uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
   uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
   uint8_t* const mbuf_a = pbuf + kPbufAlloc<G>;   // metadata of the batch in vbuf_a / vbuf_b
   uint8_t* const mbuf_b = mbuf_a + kMetaBytes<HP>;
-  int* const shared_done_p = (int*)(lds_all + NW * kWaveLds);   // PAIR: wavefronts that have left their record of the long sequence
+  int* const done_cnt = (int*)(lds_all + NW * kWaveLds);        // PAIR: records left so far of the long [0] and the short [1] sequence
+  float* const spare_rec = (float*)(lds_all + NW * kWaveLds + 16);   // PAIR, NW = 4: see above
 
   // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
   int nseg = 1;
   int sg_b[2] = {(int)blockIdx.z, 0}, sg_t0[2] = {split * p.chunk_tokens, 0}, sg_t1[2] = {0, 0};
   int sg_mode[2] = {kSegSplitKV, kSegAlone};
   int sg_len[2] = {0, 0};                      // PAIR: length of the range's sequence
+  int sg_seq[2] = {0, 0};                      // PAIR: 0 the block's long sequence, 1 the short one
+  uint32_t part_mask[2] = {0u, 0u};            // PAIR: wavefronts with a share of the long / short sequence
+  int spare_wave = -1;                         // PAIR: wavefront whose record of the short sequence is in the spare slot
   if (PAIR) {
     const int B = p.batch;
-    if (threadIdx.x == 0) *shared_done_p = 0;
+    if (threadIdx.x < 2) done_cnt[threadIdx.x] = 0;
     __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     const int r_long = blockIdx.z, r_short = B - 1 - r_long;
@@ -383,34 +394,61 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int l_long = lc.lens[b_long];
     const int l_short = self ? 0 : lc.lens[b_short];
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
-    // wavefront 1 pays a second prologue when the long sequence is shared: one batch in its favour
-    const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
-    const bool shared = cut < nb_long;
+    // Shares of the batches [0, nb_long) of the long sequence followed by the short one's: wavefront
+    // k takes [T k / NW, T (k+1) / NW).  A wavefront that gets the end of one and the start of the
+    // other pays a second prologue, about the time of two batches: that cost sits between the two
+    // sequences as kGap batches nobody streams (short_at is where the short sequence starts).
+    constexpr int kGap = 2;
+    const int short_at = nb_long + (nb_short > 0 ? kGap : 0);
+    const int T = short_at + nb_short;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+      const int lo_k = (int)(((int64_t)T * k) / NW), hi_k = (int)(((int64_t)T * (k + 1)) / NW);
+      if (lo_k < min(hi_k, nb_long)) part_mask[0] |= 1u << k;
+      if (max(lo_k, short_at) < hi_k) part_mask[1] |= 1u << k;
+    }
+    const bool long_shared = __popc(part_mask[0]) > 1, short_shared = __popc(part_mask[1]) > 1;
+    if (short_shared) {
+      const uint32_t both = part_mask[0] & part_mask[1];          // at most one wavefront
+      if (both) spare_wave = __ffs((int)both) - 1;
+    }
+    const int lo = (int)(((int64_t)T * wave) / NW), hi = (int)(((int64_t)T * (wave + 1)) / NW);
+    const bool has_long = lo < min(hi, nb_long), has_short = max(lo, short_at) < hi;
     nseg = 0;
-    // (with a fused append an empty sequence still has its new token to attend to: it gets an
-    // empty range instead of a zero row)
-    if (wave == 0) {
-      if (nb_long == 0 && !p.append) {                  // empty sequence: zero output row
-        for (int i = lane; i < G * DH; i += 64)
-          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * DH + i, 0.f);
+    // first the short sequence's share.  (With a fused append an empty sequence still has its new
+    // token to attend to: it gets an empty range instead of a zero row; the last wavefront takes it.)
+    if (has_short) {
+      sg_b[0] = b_short; sg_t0[0] = 64 * (max(lo, short_at) - short_at); sg_t1[0] = min(l_short, 64 * (hi - short_at));
+      sg_len[0] = l_short; sg_mode[0] = short_shared ? kSegShare : kSegAlone; sg_seq[0] = 1;
+      nseg = 1;
+    } else if (!self && nb_short == 0 && wave == NW - 1) {
+      if (p.append) {
+        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = 0; sg_len[0] = 0; sg_mode[0] = kSegAlone; sg_seq[0] = 1;
+        nseg = 1;
       } else {
-        sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 64 * cut); sg_len[0] = l_long;
-        sg_mode[0] = shared ? kSegShare : kSegAlone;
-        nseg = 1;
-      }
-    } else {
-      if (nb_short > 0 || (p.append && !self)) {
-        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_len[0] = l_short; sg_mode[0] = kSegAlone;
-        nseg = 1;
-      } else if (!self) {
         for (int i = lane; i < G * DH; i += 64)
           store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * DH + i, 0.f);
       }
-      if (shared) {                                     // last, so that its record can stay in this wavefront's buffers
-        if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 64 * cut; sg_t1[0] = l_long; sg_len[0] = l_long; sg_mode[0] = kSegShare; }
-        else           { sg_b[1] = b_long; sg_t0[1] = 64 * cut; sg_t1[1] = l_long; sg_len[1] = l_long; sg_mode[1] = kSegShare; }
-        ++nseg;
+    }
+    // last the long sequence's share, so that its record can stay in this wavefront's buffers
+    // (an empty long sequence, then the short one is empty too, goes to wavefront 0)
+    int sb = 0, st0 = 0, st1 = 0, smode = kSegAlone;
+    bool add_long = false;
+    if (has_long) {
+      sb = b_long; st0 = 64 * lo; st1 = min(l_long, 64 * min(hi, nb_long)); smode = long_shared ? kSegShare : kSegAlone;
+      add_long = true;
+    } else if (nb_long == 0 && wave == 0) {
+      if (p.append) {
+        sb = b_long; add_long = true;
+      } else {
+        for (int i = lane; i < G * DH; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * DH + i, 0.f);
       }
+    }
+    if (add_long) {
+      if (nseg == 0) { sg_b[0] = sb; sg_t0[0] = st0; sg_t1[0] = st1; sg_len[0] = l_long; sg_mode[0] = smode; sg_seq[0] = 0; }
+      else           { sg_b[1] = sb; sg_t0[1] = st0; sg_t1[1] = st1; sg_len[1] = l_long; sg_mode[1] = smode; sg_seq[1] = 0; }
+      ++nseg;
     }
     wave_sync();                                        // the ranking's scratch lived in kbuf (and on into vbuf_a)
   } else if (p.sorted) {
@@ -449,6 +487,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   const int b = seg == 0 ? sg_b[0] : sg_b[1];
   const int t_begin = seg == 0 ? sg_t0[0] : sg_t0[1];
   const int mode = seg == 0 ? sg_mode[0] : sg_mode[1];
+  const int sq = seg == 0 ? sg_seq[0] : sg_seq[1];
   const int64_t pt_row = (int64_t)b * p.max_pages;
   // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page
   // pg_first + 64*window + l, i.e. one vector load covers a window of 16 batches; `pidv_nx` is
@@ -825,52 +864,84 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
     return;
   }
-  // The range's result as a record in this wavefront's V buffers (every read of them is done):
-  // acc[G][128] (un-normalised, zero-point term removed), then (max, sum) per head; with G = 8
-  // the pairs land at the start of the second buffer.
+  // The range's result as a record (every read of this wavefront's V buffers is done):
+  // acc[G][128] (un-normalised, zero-point term removed), then (max, sum) per head.  It lives at the
+  // start of the V buffers (with G = 8 the pairs land at the start of the second one), or in the
+  // block's spare slot when this wavefront still has its share of the long sequence to stream.
   float* const fb = (float*)vbuf_a;
-  float* const ml = fb + G * D;
+  const bool to_spare = PAIR && NW > 2 && emode == kSegShare && sq == 1 && wave == spare_wave;
+  float* const rec = to_spare ? spare_rec : fb;
+  float* const ml = rec + G * D;
   wave_sync();
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const float o = (G > 4) ? add_xor32(oacc[c][i]) : add_xor16(oacc[c][i]);   // hi rows + lo rows
-      if (writer && i < G) fb[(head0 + i) * D + 16 * c + row16] = o - zs[i];
+      if (writer && i < G) rec[(head0 + i) * D + 16 * c + row16] = o - zs[i];
     }
     if (writer && row16 == 0 && i < G) {
       ml[2 * (head0 + i)] = m_ref[i];
       ml[2 * (head0 + i) + 1] = lsum[i];
     }
   }
-  const float* other = nullptr;                  // the other wavefront's record of the same sequence
+  // the records that make up the sequence's result: this one, or with a shared sequence those of
+  // every wavefront that has a share, in wavefront order (so the sum does not depend on who
+  // happens to come last)
+  const float* recs[NW];
+#pragma unroll
+  for (int k = 0; k < NW; ++k) recs[k] = rec;
+  int nrec = 1;
   if (PAIR && emode == kSegShare) {
     // LDS operations of a wavefront complete in order, so the record is in place before the
-    // count; the wavefront that finds the other already counted does the rest for both.
+    // count; the wavefront that finds all others counted does the rest for everybody.
+    const uint32_t mask = sq ? part_mask[1] : part_mask[0];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     int before = 0;
-    if (lane == 0) before = __hip_atomic_fetch_add(shared_done_p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (lane == 0) before = __hip_atomic_fetch_add(done_cnt + sq, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     before = __builtin_amdgcn_readfirstlane(before);
-    if (before == 0) return;                     // a shared range is always the wavefront's last
+    if (before != __popc(mask) - 1) {
+      // (a record in this wavefront's own buffers is its last act; after one in the spare slot
+      // the next range's prologue reuses the buffers)
+      wave_sync();
+      continue;
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    other = (const float*)(lds_all + (1 - wave) * kWaveLds + 4 * kTileBytes);
+    nrec = 0;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+      if ((mask >> k) & 1u) {
+        const float* rk = (sq == 1 && k == spare_wave) ? spare_rec
+                                                       : (const float*)(lds_all + k * kWaveLds + 4 * kTileBytes);
+#pragma unroll
+        for (int r = 0; r < NW; ++r)
+          if (r == nrec) recs[r] = rk;
+        ++nrec;
+      }
+    }
   }
   wave_sync();
-  // normalise (after adding the other wavefront's share of the same sequence, if there is one;
-  // wavefront 0's record is always the first operand, so the result does not depend on which
-  // of the two happens to come second)
-  const float* const rec0 = (PAIR && other && wave == 1) ? other : fb;
-  const float* const rec1 = (PAIR && other && wave == 1) ? fb : other;
+  // combine and normalise into this wavefront's buffer (element by element: a record that lives
+  // there is read before it is overwritten, and its (max, sum) pairs sit behind the rows)
   for (int idx = lane; idx < G * D; idx += 64) {
     const int h = idx >> 7;
-    float l0 = rec0[G * D + 2 * h + 1];
-    float v = rec0[idx];
-    if (PAIR && other) {
-      const float m0 = rec0[G * D + 2 * h], m1 = rec1[G * D + 2 * h], l1 = rec1[G * D + 2 * h + 1];
-      const float mm = fmaxf(m0, m1);
-      const float a0 = fast_exp2(m0 - mm), a1 = fast_exp2(m1 - mm);
-      v = fmaf(a1, rec1[idx], a0 * v);
-      l0 = fmaf(a1, l1, a0 * l0);
+    float v = recs[0][idx], l0 = recs[0][G * D + 2 * h + 1];
+    if (PAIR && nrec > 1) {
+      float mm = recs[0][G * D + 2 * h];
+#pragma unroll
+      for (int r = 1; r < NW; ++r)
+        if (r < nrec) mm = fmaxf(mm, recs[r][G * D + 2 * h]);
+      const float a0 = fast_exp2(recs[0][G * D + 2 * h] - mm);
+      v *= a0;
+      l0 *= a0;
+#pragma unroll
+      for (int r = 1; r < NW; ++r) {
+        if (r < nrec) {
+          const float ar = fast_exp2(recs[r][G * D + 2 * h] - mm);
+          v = fmaf(ar, recs[r][idx], v);
+          l0 = fmaf(ar, recs[r][G * D + 2 * h + 1], l0);
+        }
+      }
     }
     fb[idx] = v / l0;
   }
@@ -906,6 +977,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
 template <int G, bool HP>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
+  if (p.pair == 4) {
+    decode_int4_mfma_kernel<G, 4, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(256), 0, st>>>(p);
+    return;
+  }
   if (p.pair) {
     decode_int4_mfma_kernel<G, 2, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
     return;

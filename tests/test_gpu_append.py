@@ -100,7 +100,7 @@ def test_small_batch_one_launch(saw):
     _case(saw, synth.make_workload("tiny"))
 
 
-@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 8)])
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (200, 8), (300, 8)])
 def test_large_ragged_batch_pair_mode(saw, B, Hkv):
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)
@@ -146,3 +146,9 @@ def test_several_partitions_with_lengths_on_partition_boundaries(saw):
     w = synth.make_workload("tiny", batch=len(lens), seq_lens=lens)
     _case(saw, w)
     _case(saw, synth.make_workload("longctx1", batch=2, seq_lens=[700, 0], had_block=64))     # G = 8
+
+
+def test_pair_blocks_of_four_with_empty_sequences(saw):
+    """512 items: four-wavefront pair blocks; empty sequences still attend to (and store) their new token."""
+    lens = [0] * 20 + [1] * 10 + [64] * 10 + [200] * 23 + [129]
+    _case(saw, synth.make_workload("highconc", batch=len(lens), seq_lens=lens))

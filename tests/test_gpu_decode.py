@@ -84,10 +84,11 @@ def test_ragged_lengths_with_empty_and_single(saw):
     assert not o[0].any()                                           # empty sequence -> zero row
 
 
-@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (300, 8)])
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (65, 8), (200, 8), (255, 8), (300, 8)])
 def test_many_sequences_balanced_item_order(saw, B, Hkv):
     """More (sequence, kv head) items than compute units: the kernel pairs long with short sequences
-    (everything resident at once) or, beyond 2048 items, takes them longest first.  Every sequence is
+    (everything resident at once: blocks of four wavefronts per pair from 512 to 1024 items, the first
+    four cases, of two up to 2048 items) or, beyond that, takes them longest first.  Every sequence is
     compared, so an item served twice or never shows up; lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)
@@ -151,3 +152,15 @@ def test_kv16_comparison_path(saw, dtype, Hq, Hkv, d):
         err = parity.attn_error(o.cpu().numpy(), o_ref)
         print(f"[kv16 {dtype} Hq={Hq}/{Hkv} d={d} splits={splits}] err={err:.2e}", flush=True)
         assert err < TOL
+
+
+@pytest.mark.parametrize("lens", [[0] * 64, [1] * 64, [0] * 40 + [1] * 24, [64] * 63 + [0], [65] * 32 + [63] * 32,
+                                  [200] * 2 + [1] * 62, [129] * 33 + [0] * 32, [256] + [0] * 63,
+                                  list(range(64)), [128] * 64, [64 * (i % 5) for i in range(64)]])
+def test_pair_blocks_of_four_share_boundaries(saw, lens):
+    """64 sequences x 8 kv heads = 512 items: blocks of four wavefronts over (long, short) pairs.  The
+    lengths put the cuts between the wavefronts' shares everywhere: fewer batches than wavefronts,
+    empty sequences, the pair's boundary on a cut, inside a share, and a short sequence that is
+    itself shared between wavefronts."""
+    w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens)
+    _decode_case(saw, w, end_to_end=False)
