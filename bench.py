@@ -560,6 +560,10 @@ def main():
             "llama8b": other_decode(saw, dev, "llama8b", with_append=True),
             "longctx1": other_decode(saw, dev, "longctx1"),
             "longctx4": other_decode(saw, dev, "longctx4"),
+            # 1024 (sequence, kv head) items: pair blocks of four wavefronts
+            "highconc_4kv_heads": other_decode(saw, dev, "highconc", n_q_heads=16, n_kv_heads=4),
+            # head_dim 64 (two kv heads per block as one 128-channel row), Llama-3.2-1B-like heads
+            "highconc_head_dim64": other_decode(saw, dev, "highconc", head_dim=64, had_block=64, with_append=True),
         }
         result["extra"] = ex
 
