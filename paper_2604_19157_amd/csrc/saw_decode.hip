@@ -505,9 +505,10 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   //   * up to 2048 items everything is resident at once and nothing rebalances later, so the
   //     work is evened out up front: pair mode, blocks over (long, short) pairs of sequences, of
   //     four wavefronts while that still fits the 2048 slots and of two beyond.  Four-wavefront
-  //     blocks pay off from 768 items on (ragged 256 sequences x 4 heads: 82 -> 70 us, 96 x 8: 69
-  //     -> 62 us against two wavefronts sharing each item; equal lengths lose 6 us to the ranking
-  //     and the records; at 512 items the two ways are level);
+  //     blocks pay off on ragged batches from 576 items on (256 sequences x 4 heads: 82 -> 70 us,
+  //     90 x 8: 70 -> 61 us, 72 x 8: 63 -> 57 us against 2 or 4 wavefronts interleaving each
+  //     item's batches; equal lengths lose 2-8 us to the ranking and the records; at 528 items
+  //     four interleaving wavefronts per item are ahead: 51 against 64 us);
   //   * beyond that blocks queue for slots in index order, which is list scheduling: one
   //     wavefront per item, sequences taken longest first, so the launch ends on the shortest.
   //     (Measured at 288..512 sequences x 8 heads: 173-270 us against 224-332 us in pair mode,
@@ -520,7 +521,7 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   if (!kv16 && (c->head_dim == 128 || decode_head_pairs(c->head_dim, c->n_kv_heads, G)) &&
       plan.num_splits == 1 && B <= 1024) {
     const int64_t blocks = (int64_t)((B + 1) / 2) * items;
-    if ((int64_t)B * items >= 768 && blocks <= 512) p.pair = 4;
+    if ((int64_t)B * items >= 576 && blocks <= 512) p.pair = 4;
     else if (plan.waves_per_item == 1 && (int64_t)B * items > 256) {
       if (blocks <= 1024) p.pair = 2;
       else p.sorted = 1;

@@ -102,6 +102,28 @@ def test_workspace_and_plan(saw):
     assert L.saw_decode_workspace_bytes(ctypes.byref(st), 0, 32, 100, 0) == 0
 
 
+def test_plan_keeps_one_partition_from_512_items_on(saw):
+    """The INT4 decode calls stay with one partition per sequence once the batch provides 512 (sequence,
+    kv head) items (head_dim 64 with an even head count: pairs of kv heads are the items); the workspace
+    figure also covers the 16-bit call, which keeps splitting there."""
+    L = saw.lib()
+
+    def plan(st, B, msl):
+        s, c = ctypes.c_int32(), ctypes.c_int32()
+        assert L.saw_decode_plan(ctypes.byref(st), B, msl, 0, ctypes.byref(s), ctypes.byref(c)) == 0
+        return s.value, c.value
+
+    st = _struct(saw, n_kv_heads=8)
+    assert plan(st, 64, 4096)[0] == 1 and plan(st, 63, 4096)[0] > 1
+    assert plan(st, 1024, 4096)[0] == 1
+    need = L.saw_decode_workspace_bytes(ctypes.byref(st), 64, 32, 4096, 0)
+    assert need > 64 * 32 * 1 * 130 * 4                              # more than the one partition: the 16-bit call's
+    st64 = _struct(saw, n_kv_heads=8, head_dim=64, had_block=64)
+    assert plan(st64, 128, 4096)[0] == 1 and plan(st64, 64, 4096)[0] > 1
+    st64odd = _struct(saw, n_kv_heads=7, head_dim=64, had_block=64)
+    assert plan(st64odd, 74, 4096)[0] == 1 and plan(st64odd, 73, 4096)[0] > 1
+
+
 def test_dequant_rejects_bad_arguments(saw):
     L = saw.lib()
     P = ctypes.c_void_p
