@@ -56,15 +56,20 @@ def _sample(w, n):
     return sorted(picks)
 
 
-@pytest.mark.parametrize("name,n_sample,out_dtype", [
-    ("highconc", 6, torch.bfloat16),      # the headline configuration: 256 ragged sequences, bf16 in and out
-    ("highconc", 6, torch.float32),
-    ("llama8b", 3, torch.float32),
-    ("longctx4", 1, torch.float32),
-    ("longctx1", 1, torch.float32),
+@pytest.mark.parametrize("name,n_sample,out_dtype,over", [
+    ("highconc", 6, torch.bfloat16, {}),  # the headline configuration: 256 ragged sequences, bf16 in and out
+    ("highconc", 6, torch.float32, {}),
+    ("llama8b", 3, torch.float32, {}),
+    ("longctx4", 1, torch.float32, {}),
+    ("longctx1", 1, torch.float32, {}),
+    # the other figures bench.py reports: 1024 items (four-wavefront pair blocks), and head_dim 64 (pairs of
+    # kv heads per block) with 8 and with 32 kv heads
+    ("highconc", 4, torch.float32, dict(n_q_heads=16, n_kv_heads=4)),
+    ("highconc", 4, torch.float32, dict(head_dim=64, had_block=64)),
+    ("highconc", 3, torch.float32, dict(head_dim=64, had_block=64, n_kv_heads=32)),
 ])
-def test_decode_full_size_sampled(saw, name, n_sample, out_dtype):
-    w = synth.make_workload(name)
+def test_decode_full_size_sampled(saw, name, n_sample, out_dtype, over):
+    w = synth.make_workload(name, **over)
     seqs = _sample(w, n_sample)
     print(f"[{name}] B={w.batch} tokens={w.total_tokens} sampled sequences {seqs}", flush=True)
     ref = gc.oracle_fill(w, chunk=8192, seqs=seqs)
