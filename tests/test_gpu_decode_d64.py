@@ -63,10 +63,11 @@ def test_head_pairs_ragged_with_empty_and_single(saw):
     assert not o[0].any()
 
 
-@pytest.mark.parametrize("B,Hq,Hkv", [(70, 32, 8), (140, 16, 4), (300, 8, 8), (600, 8, 8)])
+@pytest.mark.parametrize("B,Hq,Hkv", [(70, 32, 8), (140, 16, 4), (150, 32, 8), (255, 8, 8), (300, 8, 8), (600, 8, 8)])
 def test_head_pairs_many_sequences(saw, B, Hq, Hkv):
-    """More (sequence, head pair) items than compute units: pair mode up to 2048 wavefronts, longest
-    first beyond (the last case).  Lengths include empty sequences and many ties."""
+    """More (sequence, head pair) items than compute units: pair mode (blocks of two wavefronts, of four
+    from 576 to 1024 items: the third and fourth case), longest first beyond 2048 items (the last case).
+    Lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 200, size=B)
     lens[rng.integers(0, B, size=B // 5)] = 64
@@ -93,7 +94,8 @@ def test_head_pairs_fp16_cache_input(saw):
     TD._decode_case(saw, _w("tiny", batch=2, ctx=(30, 300), n_q_heads=8, n_kv_heads=2, dtype=torch.float16))
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,ctx", [(3, 8, 4, (20, 150)), (70, 32, 8, (1, 120)), (2, 8, 2, (700, 900))])
+@pytest.mark.parametrize("B,Hq,Hkv,ctx", [(3, 8, 4, (20, 150)), (70, 32, 8, (1, 120)), (150, 16, 8, (0, 200)),
+                                          (2, 8, 2, (700, 900))])
 def test_append_then_attend(saw, B, Hq, Hkv, ctx):
     """saw_append_decode_attn at head_dim 64: the store launch, then the decode over one more token."""
     TA._case(saw, _w(batch=B, ctx=ctx, n_q_heads=Hq, n_kv_heads=Hkv))
