@@ -533,8 +533,8 @@ def main():
                              "int4_speedup": round(med / med_d, 3),
                              "bytes_ratio": round(b16 / dbytes, 3),
                              "note": "16-bit baseline = MFMA kernel of the same design (direct K operand loads, "
-                                     "HBM->LDS V tiles, LDS transpose reads), one wavefront per (sequence, kv head), "
-                                     "no pair balancing; at equal bandwidth the speed-up would equal bytes_ratio"}
+                                     "HBM->LDS V tiles, LDS transpose reads, the same pair balancing of the ragged "
+                                     "batch); at equal bandwidth the speed-up would equal bytes_ratio"}
         del kv16, ws16
         torch.cuda.empty_cache()
         ex["prefill_store_sweep"] = store_sweep(saw, dev)
@@ -565,6 +565,11 @@ def main():
             # head_dim 64 (two kv heads per block as one 128-channel row), Llama-3.2-1B-like heads
             "highconc_head_dim64": other_decode(saw, dev, "highconc", head_dim=64, had_block=64, with_append=True),
         }
+        u = ex["other_decode"]["highconc_uniform2304"]["kv16_decode"]
+        ex["int4_vs_16bit_decode"] = {
+            "ragged_speedup": ex["kv16_decode"]["int4_speedup"],     # both kernels balance the ragged batch the same way
+            "equal_lengths_speedup": u["int4_speedup"],
+            "bytes_ratio": u["bytes_ratio"]}
         result["extra"] = ex
 
     if not args.no_cpu:

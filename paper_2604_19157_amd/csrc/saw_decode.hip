@@ -527,6 +527,11 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
       else p.sorted = 1;
     }
   }
+  // the 16-bit matrix-core kernel has the two-wavefront pair mode as well (same conditions), so that
+  // the comparison on a ragged batch is between formats and not between schedules
+  if (kv16 && c->head_dim == 128 && G <= 4 && plan.num_splits == 1 && B <= 1024 &&
+      (int64_t)B * c->n_kv_heads > 256 && (int64_t)((B + 1) / 2) * c->n_kv_heads <= 1024)
+    p.pair = 2;
   return launch_decode(p, B, c->head_dim, G, kv16, kv_dtype, st);
 }
 

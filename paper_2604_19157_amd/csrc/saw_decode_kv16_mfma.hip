@@ -17,8 +17,17 @@
 //     O[head][channel] in eight 16x16 tiles.
 // Group sizes up to 4 (rows: hi limbs of the heads, then lo limbs); larger groups use the
 // vector-ALU kernel.
+//
+// PAIR = true gives this kernel the INT4 kernel's way of evening out a ragged batch when all of it
+// is resident at once (one partition per sequence, 257..2048 (sequence, kv head) items): a block
+// of two wavefronts owns the sequences at ranks r and B-1-r of the longest-first order and halves
+// their 32-token batches: wavefront 0 streams the first part of the long sequence, wavefront 1 the
+// short sequence and then the rest of the long one; the two leave their shares of the long
+// sequence as (max, sum, accumulator) records in LDS, and whichever comes second combines them
+// (wavefront 0's first) and writes the output.
 #include "saw_decode.h"
 #include "saw_wave_util.h"
+#include "saw_rank.h"
 
 namespace saw {
 
@@ -57,26 +66,84 @@ __device__ __forceinline__ void split16(float x, uint32_t& hi16, uint32_t& lo16)
 
 }  // namespace kv16
 
-template <int G, int DT>
-__global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
+template <int G, int DT, bool PAIR>
+__global__ __launch_bounds__(PAIR ? 128 : 64) void decode_kv16_mfma_kernel(DecodeParams p) {
   using namespace kv16;
   constexpr int D = 128;
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x;
+  constexpr int NWV = PAIR ? 2 : 1;
+  const int split = blockIdx.x, kvh = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int row16 = lane & 15, grp = lane >> 4;
-  const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
-  const int t_begin = split * p.chunk_tokens;
-  const int t_end = min(L, t_begin + p.chunk_tokens);
-  if (t_begin >= t_end) {
-    if (p.num_splits == 1)
-      for (int i = lane; i < G * D; i += 64)
-        store_elem(p.out, p.out_dtype, ((int64_t)b * p.n_q_heads + kvh * G) * D + i, 0.f);
-    return;
-  }
-  __shared__ __attribute__((aligned(16))) uint8_t lds[kWaveLds];
+  // (one shared array for everything: see the INT4 kernel on why)
+  __shared__ __attribute__((aligned(16))) uint8_t lds_all[NWV * kWaveLds + 16];
+  uint8_t* const lds = lds_all + wave * kWaveLds;
   uint8_t* const vbuf_a = lds;
   uint8_t* const vbuf_b = lds + kVbufBytes;
   uint8_t* const pbuf = lds + 2 * kVbufBytes;
+  int* const done_cnt = (int*)(lds_all + NWV * kWaveLds);      // PAIR: records left of the long sequence
+
+  // ---- the ranges this wavefront streams ----
+  int nseg = 1;
+  int sg_b[2] = {(int)blockIdx.z, 0}, sg_t0[2] = {0, 0}, sg_t1[2] = {0, 0};
+  bool sg_share[2] = {false, false};
+  if (PAIR) {
+    const int B = p.batch;
+    if (threadIdx.x == 0) done_cnt[0] = 0;
+    __syncthreads();
+    const LenClasses lc = build_len_classes(p, B, lane, (int*)vbuf_a);
+    const int r_long = blockIdx.z, r_short = B - 1 - r_long;
+    const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
+    const int b_long = seq_of_rank(lane, lc, r_long);
+    const int b_short = self ? b_long : seq_of_rank(lane, lc, r_short);
+    const int l_long = lc.lens[b_long];
+    const int l_short = self ? 0 : lc.lens[b_short];
+    const int nb_long = (l_long + 31) >> 5, nb_short = (l_short + 31) >> 5;
+    // wavefront 1 pays a second prologue when the long sequence is shared: two batches in its favour
+    const int cut = min(nb_long, (nb_long + nb_short + 2) >> 1);
+    const bool shared = cut < nb_long;
+    nseg = 0;
+    if (wave == 0) {
+      if (nb_long == 0) {                               // empty sequence: zero output row
+        for (int i = lane; i < G * D; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * D + i, 0.f);
+      } else {
+        sg_b[0] = b_long; sg_t0[0] = 0; sg_t1[0] = min(l_long, 32 * cut); sg_share[0] = shared;
+        nseg = 1;
+      }
+    } else {
+      if (nb_short > 0) {
+        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = l_short; sg_share[0] = false;
+        nseg = 1;
+      } else if (!self) {
+        for (int i = lane; i < G * D; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * D + i, 0.f);
+      }
+      if (shared) {                                     // last, so that its record can stay in this wavefront's buffers
+        if (nseg == 0) { sg_b[0] = b_long; sg_t0[0] = 32 * cut; sg_t1[0] = l_long; sg_share[0] = true; }
+        else           { sg_b[1] = b_long; sg_t0[1] = 32 * cut; sg_t1[1] = l_long; sg_share[1] = true; }
+        ++nseg;
+      }
+    }
+    wave_sync();                                        // the ranking's scratch lived in vbuf_a
+  } else {
+    const int L = min(p.seq_lens[sg_b[0]] + p.len_bias, p.bound);
+    sg_t0[0] = split * p.chunk_tokens;
+    sg_t1[0] = min(L, sg_t0[0] + p.chunk_tokens);
+    if (sg_t0[0] >= sg_t1[0]) {
+      if (p.num_splits == 1)
+        for (int i = lane; i < G * D; i += 64)
+          store_elem(p.out, p.out_dtype, ((int64_t)sg_b[0] * p.n_q_heads + kvh * G) * D + i, 0.f);
+      return;
+    }
+  }
+
+#pragma unroll 1
+  for (int seg = 0; seg < nseg; ++seg) {
+  const int b = seg == 0 ? sg_b[0] : sg_b[1];
+  const int t_begin = seg == 0 ? sg_t0[0] : sg_t0[1];
+  const int t_end = seg == 0 ? sg_t1[0] : sg_t1[1];
+  const bool share = seg == 0 ? sg_share[0] : sg_share[1];
 
   const uint8_t* const kpages = p.k_codes;
   const uint8_t* const vpages = p.v_codes;
@@ -259,6 +326,43 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
   }
   // oacc[c][i] of lane (grp, row16) = O[row 4 grp + i][channel 16c + row16]: rows 0..3 (grp 0) hi, 4..7 (grp 1) lo
   const bool writer = grp == 0;
+  if (PAIR && share) {
+    // this wavefront's share of the long sequence as a record in its own V buffer (every read of
+    // it is done and nothing is in flight): acc[G][128] un-normalised, then (max, sum) per head
+    float* const rec = (float*)vbuf_a;
+    wave_sync();
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float o = add_xor16(oacc[c][i]);     // hi rows + lo rows
+        if (writer) rec[i * D + 16 * c + row16] = o;
+      }
+      if (writer && row16 == 0) { rec[G * D + 2 * i] = m_ref[i]; rec[G * D + 2 * i + 1] = lsum[i]; }
+    }
+    // LDS operations of a wavefront complete in order, so the record is in place before the count;
+    // the wavefront that finds the other already counted does the rest for both (a shared range
+    // is always a wavefront's last).
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    int before = 0;
+    if (lane == 0) before = __hip_atomic_fetch_add(done_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const float* const rec0 = (const float*)lds_all;                  // wavefront 0's record is always the first operand
+    const float* const rec1 = (const float*)(lds_all + kWaveLds);
+    const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * D;
+    for (int idx = lane; idx < G * D; idx += 64) {
+      const int h = idx >> 7;
+      const float m0 = rec0[G * D + 2 * h], m1 = rec1[G * D + 2 * h];
+      const float mm = fmaxf(m0, m1);
+      const float a0 = fast_exp2(m0 - mm), a1 = fast_exp2(m1 - mm);
+      const float v = fmaf(a1, rec1[idx], a0 * rec0[idx]);
+      const float l = fmaf(a1, rec1[G * D + 2 * h + 1], a0 * rec0[G * D + 2 * h + 1]);
+      store_elem(p.out, p.out_dtype, obase + idx, v / l);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < G; ++i) {
     const int head = kvh * G + i;
@@ -276,6 +380,8 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
     }
     if (p.num_splits != 1 && writer && row16 == 0) { part[0] = m_ref[i]; part[1] = lsum[i]; }
   }
+  wave_sync();                                   // the next range's prologue reuses the buffers
+  }  // ranges of this wavefront
 }
 
 #undef KV16_LOAD_K
@@ -284,8 +390,12 @@ __global__ __launch_bounds__(64) void decode_kv16_mfma_kernel(DecodeParams p) {
 // head_dim 128, group size <= 4; returns false when this kernel does not cover the case.
 bool launch_decode_kv16_mfma(const DecodeParams& p, int G, int kv_dtype, dim3 grid, hipStream_t st) {
 #define KV16_GO(GG)                                                                              \
-  if (kv_dtype == SAW_BF16) decode_kv16_mfma_kernel<GG, SAW_BF16><<<grid, dim3(64), 0, st>>>(p); \
-  else decode_kv16_mfma_kernel<GG, SAW_F16><<<grid, dim3(64), 0, st>>>(p);
+  if (p.pair) {                                                                                  \
+    const dim3 pgrid(1, grid.y, (p.batch + 1) / 2);                                              \
+    if (kv_dtype == SAW_BF16) decode_kv16_mfma_kernel<GG, SAW_BF16, true><<<pgrid, dim3(128), 0, st>>>(p); \
+    else decode_kv16_mfma_kernel<GG, SAW_F16, true><<<pgrid, dim3(128), 0, st>>>(p);             \
+  } else if (kv_dtype == SAW_BF16) decode_kv16_mfma_kernel<GG, SAW_BF16, false><<<grid, dim3(64), 0, st>>>(p); \
+  else decode_kv16_mfma_kernel<GG, SAW_F16, false><<<grid, dim3(64), 0, st>>>(p);
   switch (G) {
     case 1: KV16_GO(1) return true;
     case 2: KV16_GO(2) return true;

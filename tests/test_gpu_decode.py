@@ -164,3 +164,32 @@ def test_pair_blocks_of_four_share_boundaries(saw, lens):
     itself shared between wavefronts."""
     w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens)
     _decode_case(saw, w, end_to_end=False)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("B,Hq,Hkv", [(70, 32, 8), (129, 4, 4), (255, 16, 8)])
+def test_kv16_comparison_path_pair_mode(saw, dtype, B, Hq, Hkv):
+    """The 16-bit kernel's two-wavefront blocks over (long, short) sequence pairs (one partition, 257..2048
+    items): every sequence compared, lengths with empty sequences and ties."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(0, 200, size=B)
+    lens[rng.integers(0, B, size=B // 5)] = 32
+    lens[:4] = [0, 199, 1, 33]
+    w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=Hq, n_kv_heads=Hkv, dtype=dtype)
+    kc = saw.Kv16Cache(w.num_pages, Hkv, w.head_dim, dtype)
+    pt = torch.from_numpy(w.page_table).cuda()
+    for b in range(w.batch):
+        L = int(w.seq_lens[b])
+        if L:
+            K, V = synth.gen_kv(w, b, 0, L)
+            saw.kv16_store(kc, K.cuda(), V.cuda(), pt, torch.from_numpy(synth.slots_for(b, 0, L)).cuda())
+    q = synth.gen_q(w)
+    o_ref = O.kv16_paged_decode_attn(kc.k_pages.float().cpu().numpy(), kc.v_pages.float().cpu().numpy(),
+                                     q.float().numpy(), w.page_table, w.seq_lens)
+    o = torch.full((w.batch, Hq, w.head_dim), float("nan"), device="cuda")
+    saw.kv16_paged_decode_attn(kc, q.cuda(), pt, torch.from_numpy(w.seq_lens).cuda(), num_splits=1, out=o)
+    torch.cuda.synchronize()
+    err = parity.attn_error(o.cpu().numpy(), o_ref)
+    print(f"[kv16 pair {dtype} B={B} Hq={Hq}/{Hkv}] err={err:.2e}", flush=True)
+    assert err < TOL
+    assert not o[0].any()
