@@ -312,9 +312,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
     // Shares of the batches [0, nb_long) of the long sequence followed by the short one's: wavefront
     // k takes [T k / NW, T (k+1) / NW).  A wavefront that gets the end of one and the start of the
-    // other pays a second prologue, about the time of two batches: that cost sits between the two
-    // sequences as kGap batches nobody streams (short_at is where the short sequence starts).
-    constexpr int kGap = 2;
+    // other pays a second prologue, about the time of two or three batches: that cost sits between
+    // the two sequences as kGap batches nobody streams (short_at is where the short sequence starts;
+    // 2 and 3 measured 1-2 % better than their neighbours for blocks of two and of four).
+    constexpr int kGap = (NW > 2) ? 3 : 2;
     const int short_at = nb_long + (nb_short > 0 ? kGap : 0);
     const int T = short_at + nb_short;
 #pragma unroll
