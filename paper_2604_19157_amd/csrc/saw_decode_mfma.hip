@@ -52,7 +52,7 @@ constexpr float kLazyTau = 8.0f;               // reference max may lag the true
 // the other half, so that the 128-channel products below are the 64-channel ones.
 template <int G, int NH, bool HP>
 __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&qraw)[2 * G], int lane,
-                                          float* __restrict__ qs, float* __restrict__ qred, u32x4 (&a_q)[4],
+                                          float* __restrict__ qs, u32x4 (&a_q)[4],
                                           float (&qsum)[NH], float& qmul_out) {
   constexpr int D = 128;
   constexpr int LO = (G > 4) ? 8 : 4;
@@ -65,43 +65,57 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
       qs[j * D + 64 * (1 - kv) + lane] = 0.f;
     }
   } else {
+    // a lane holds channels `lane` and `lane + 64` of every head: the butterflies of stride 64
+    // (h = 128) are done here, in registers, and the LDS transform only goes up to order 64
+    const bool top = p.rot_k && p.had_block > 64;
 #pragma unroll
-    for (int j = 0; j < 2 * G; ++j) qs[lane + 64 * j] = qraw[j];
+    for (int g = 0; g < G; ++g) {
+      const float a = qraw[2 * g], b = qraw[2 * g + 1];
+      qs[lane + 128 * g] = top ? a + b : a;
+      qs[lane + 128 * g + 64] = top ? a - b : b;
+    }
   }
   wave_sync();
   float qmul = p.q_scale;
   if (p.rot_k) {
-    wave_lds_fwht128<G>(qs, p.had_block, lane);
+    wave_lds_fwht128<G>(qs, min(p.had_block, 64), lane);
     qmul *= had_norm(p.had_block);
   }
   const bool is_lo = row16 >= LO;
   const int qhead = row16 - (is_lo ? LO : 0);
   const bool q_live = qhead < G;
   const float* qrow = qs + (q_live ? qhead : 0) * D + 32 * grp;
-  float qpart = 0.f;
+  const float qm = q_live ? qmul : 0.f;                      // idle rows of the tile carry zeros
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    uint32_t limb[8];
+    const f32x4 va = *(const f32x4*)(qrow + 8 * kk), vb = *(const f32x4*)(qrow + 8 * kk + 4);
+    uint32_t w[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float x = q_live ? qrow[8 * kk + j] * qmul : 0.f;
-      uint32_t h16, l16;
-      float sum;
-      split_bf16(x, h16, l16, sum);
-      limb[j] = is_lo ? l16 : h16;
-      qpart += __uint_as_float(limb[j] << 16);
+    for (int j = 0; j < 4; ++j) {                            // dword j packs channels j (low half) and j + 4
+      const float x0 = va[j] * qm, x1 = vb[j] * qm;
+      const uint32_t u0 = __float_as_uint(x0), u1 = __float_as_uint(x1);
+      // hi limbs: the top 16 bits of both values in one byte permute
+      const uint32_t hi = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+      // lo limbs: the remainders, rounded to nearest even (v_cvt_pk_bf16_f32)
+      const f32x2 rem = f32x2{x0 - __uint_as_float(u0 & 0xffff0000u), x1 - __uint_as_float(u1 & 0xffff0000u)};
+      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+      const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(rem, bf16x2_t));
+      w[j] = is_lo ? lo : hi;
     }
-    a_q[kk] = u32x4{limb[0] | (limb[4] << 16), limb[1] | (limb[5] << 16), limb[2] | (limb[6] << 16), limb[3] | (limb[7] << 16)};
+    a_q[kk] = u32x4{w[0], w[1], w[2], w[3]};
   }
-  qpart = add_xor16(qpart);
-  qpart = add_xor32(qpart);            // every lane of row m: sum of the limbs it feeds
-  wave_sync();
-  if (lane < 16) qred[lane] = qpart;
-  wave_sync();
+  // qsum = sum over channels of the limbs as the matrix cores will see them: one product per k-step
+  // with a matrix of ones leaves row m's sum in every column; lane (grp, .) holds rows 4 grp + i,
+  // and the hi and lo rows of a head sit one (G <= 4) or two (G = 8) lane groups apart
+  f32x4 rs = f32x4{0.f, 0.f, 0.f, 0.f};
+  const bf16x8 ones = as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) rs = mfma_bf16(as_bf16x8(a_q[kk]), ones, rs);
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
-    const int hd = (G > 4) ? (4 * (grp & 1) + i) : i;
-    qsum[i] = qred[hd] + qred[LO + hd];
+    float t = rs[i];
+    if (G <= 4) t = add_xor16(t);                            // rows 0-3 (hi) + rows 4-7 (lo); groups 2, 3 hold zeros
+    qsum[i] = add_xor32(t);                                  // G = 8: rows 4 (grp & 1) + i (hi) + 8 more (lo)
   }
   wave_sync();
   qmul_out = qmul;
@@ -545,7 +559,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       // randomised Hadamard: q diag(sigma) first (element lane + 64 j is channel lane + 64 (j & 1))
       if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, HP ? lane : lane + 64 * (j & 1), qraw[j]);
     }
-    prepare_q<G, NH, HP>(p, qraw, lane, qrows, qred, a_q, qsum, qmul);
+    prepare_q<G, NH, HP>(p, qraw, lane, qrows, a_q, qsum, qmul);
   }
 
   f32x4 oacc[8];
