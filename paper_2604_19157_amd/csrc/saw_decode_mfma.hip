@@ -333,8 +333,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int short_at = nb_long + (nb_short > 0 ? kGap : 0);
     const int T = short_at + nb_short;
 #pragma unroll
-    for (int k = 0; k < NW; ++k) {
-      const int lo_k = (int)(((int64_t)T * k) / NW), hi_k = (int)(((int64_t)T * (k + 1)) / NW);
+    for (int k = 0; k < NW; ++k) {       // (T < 2^27 batches: the products fit 32 bits)
+      const int lo_k = (int)(((uint32_t)T * (uint32_t)k) / NW), hi_k = (int)(((uint32_t)T * (uint32_t)(k + 1)) / NW);
       if (lo_k < min(hi_k, nb_long)) part_mask[0] |= 1u << k;
       if (max(lo_k, short_at) < hi_k) part_mask[1] |= 1u << k;
     }
@@ -343,7 +343,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       const uint32_t both = part_mask[0] & part_mask[1];          // at most one wavefront
       if (both) spare_wave = __ffs((int)both) - 1;
     }
-    const int lo = (int)(((int64_t)T * wave) / NW), hi = (int)(((int64_t)T * (wave + 1)) / NW);
+    const int lo = (int)(((uint32_t)T * (uint32_t)wave) / NW), hi = (int)(((uint32_t)T * (uint32_t)(wave + 1)) / NW);
     const bool has_long = lo < min(hi, nb_long), has_short = max(lo, short_at) < hi;
     nseg = 0;
     // first the short sequence's share.  (With a fused append an empty sequence still has its new

@@ -34,10 +34,12 @@ __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, i
   int* const lens = scratch + 64;
   lc.lens = lens;
   int mine[kMaxRanked / 64];
+  // (the `v < lc.V` tests are wavefront-uniform: the groups of 64 past the batch cost a branch each)
 #pragma unroll
   for (int v = 0; v < kMaxRanked / 64; ++v) {
     const int idx = 64 * v + lane;
-    mine[v] = (idx < B) ? p.seq_lens[idx] : 0;
+    mine[v] = 0;
+    if (v < lc.V) mine[v] = (idx < B) ? p.seq_lens[idx] : 0;
   }
   hist[lane] = 0;
   wave_sync();
@@ -45,7 +47,7 @@ __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, i
   for (int v = 0; v < kMaxRanked / 64; ++v) {
     const int idx = 64 * v + lane;
     lc.cls[v] = -1;
-    if (idx < B) {
+    if (v < lc.V && idx < B) {
       const int len = max(min(mine[v] + p.len_bias, p.bound), 0);
       lens[idx] = len;
       lc.cls[v] = len_class(len, kscale);
