@@ -81,6 +81,11 @@ def fill(w, saw, dev, cache, kv16=None, chunk=8192):
 SETTLE_S = 0.15              # untimed calls before every measurement: after an idle gap the clocks need ~0.1 s to come back up
 
 
+# the side workloads are timed right after their caches are filled and cloned (the GPU has been doing
+# other, lighter work): half a second of the call itself first, or the first figures come out 30-40 % slow
+OTHER_SETTLE_S = 0.5
+
+
 def _settle(fns, seconds):
     t0 = time.perf_counter()
     while time.perf_counter() - t0 < seconds:
@@ -307,13 +312,13 @@ def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, with_appen
     if with_kv16:
         def call16():
             saw.kv16_paged_decode_attn(kv16, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
-        med, med16 = time_interleaved([call, call16], iters, warmup)
+        med, med16 = time_interleaved([call, call16], iters, warmup, settle=OTHER_SETTLE_S)
         p10 = p90 = float("nan")
         b16 = kv16_decode_bytes(w, lens)
         res16 = {"us": round(med16, 2), "GB_s": round(b16 / med16 / 1e3, 1), "int4_speedup": round(med16 / med, 3),
                  "bytes_ratio": round(b16 / nbytes, 3)}
     else:
-        med, mean, p10, p90 = time_calls(call, iters, warmup)
+        med, mean, p10, p90 = time_calls(call, iters, warmup, settle=OTHER_SETTLE_S)
     step_us = None
     if with_append:
         # the whole decode step: this step's token of every sequence appended and attended to, one call
@@ -326,7 +331,7 @@ def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, with_appen
             turn[0] += 1
             saw.append_decode_attn(c, newK, newV, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws2)
 
-        step_us = time_calls(call_step, iters, warmup)[0]
+        step_us = time_calls(call_step, iters, warmup, settle=OTHER_SETTLE_S)[0]
     overhead = 2 * w.batch * w.n_q_heads * splits * (w.head_dim + 2) * 4 if splits > 1 else 0
     r = {"batch": w.batch, "tokens_cached": int(lens.sum()), "splits": splits, "cache_copies_rotated": len(copies),
          "split_partials_bytes_written_and_read": overhead,
