@@ -18,7 +18,10 @@ def saw():
     return binding
 
 
-@pytest.mark.parametrize("name,kw", [("highconc", dict(batch=70, ctx=(1, 200))),      # pair mode, one launch
+@pytest.mark.parametrize("name,kw", [("highconc", dict(batch=70, ctx=(1, 200))),      # 560 items: one launch, ...
+                                     ("highconc", dict(batch=80, ctx=(1, 200))),      # ... 640: pair blocks of four
+                                     ("highconc", dict(batch=200, ctx=(1, 120))),     # ... 1600: pair blocks of two
+                                     ("highconc", dict(batch=150, ctx=(1, 150), head_dim=64, had_block=64)),  # head pairs
                                      ("tiny", dict(batch=3, ctx=(130, 700)))])         # split-KV + merge kernel
 def test_decode_step_replays_from_a_graph(saw, name, kw):
     w = synth.make_workload(name, **kw)
