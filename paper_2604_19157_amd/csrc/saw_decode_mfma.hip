@@ -131,7 +131,7 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
 //   pid, wk, wv  page id of position L and this lane's two channels of the new K and V vectors,
 //         loaded by the caller early enough that nothing here waits for memory
 //   qrot  LDS, [G][128]: the (rotated) query rows before scaling; qmul their scale
-//   scr   LDS scratch of 144 floats, distinct from qrot
+//   scr   LDS scratch of 272 floats (16-byte aligned), distinct from qrot
 // HP: the 128 values are the new vectors of two neighbouring 64-channel kv heads (lanes 0-31 hold
 // the first head's channels), quantised and stored per head; `kvh` counts pairs.
 template <int G, int NH, bool HP>
@@ -143,42 +143,61 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
   constexpr int D = 128;
   constexpr int DH = HP ? 64 : 128;  // channels of one head
   const int row16 = lane & 15, grp = lane >> 4;
-  float* const yb = scr;            // [128]: rotation scratch, then the dequantised V row
-  float* const lg = scr + 128;      // [G]: logits of the new token
+  float* const yb = scr;            // [2][128]: K and V for the rotation, then [128] the dequantised V row
+  float* const lg = scr + 256;      // [G]: logits of the new token
   const int slot = L & 15;
   const bool place = pid >= 0 && pid < p.num_pages;          // otherwise attended to but not stored
   const int head = HP ? 2 * kvh + (lane >> 5) : kvh;         // kv head of this lane's two channels
   const int64_t vec = ((int64_t)pid * p.n_kv_heads + head) * 16 + slot;
-#pragma unroll 1
-  for (int which = 0; which < 2; ++which) {                  // 0: K, 1: V
-    const bool rot = which ? (p.rot_v != 0) : (p.rot_k != 0);
-    const uint32_t w = which ? wv : wk;
-    float x0, x1;
-    if (p.kv_new_dtype == SAW_BF16) widen2<SAW_BF16>(w, x0, x1); else widen2<SAW_F16>(w, x0, x1);
-    if (rot && p.has_signs) {                                // x diag(sigma), as the store kernel does
-      x0 = apply_sign(p.signs, (2 * lane) & (DH - 1), x0);
-      x1 = apply_sign(p.signs, (2 * lane + 1) & (DH - 1), x1);
+  // K and V go through every step together (index 0: K, 1: V): one two-vector transform instead of
+  // two single ones, and reductions that overlap each other
+  const bool rot[2] = {p.rot_k != 0, p.rot_v != 0};
+  float x[2][2];
+  if (p.kv_new_dtype == SAW_BF16) { widen2<SAW_BF16>(wk, x[0][0], x[0][1]); widen2<SAW_BF16>(wv, x[1][0], x[1][1]); }
+  else                            { widen2<SAW_F16>(wk, x[0][0], x[0][1]);  widen2<SAW_F16>(wv, x[1][0], x[1][1]); }
+  if (p.has_signs) {                                         // x diag(sigma), as the store kernel does
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      if (rot[w]) {
+        x[w][0] = apply_sign(p.signs, (2 * lane) & (DH - 1), x[w][0]);
+        x[w][1] = apply_sign(p.signs, (2 * lane + 1) & (DH - 1), x[w][1]);
+      }
     }
-    yb[2 * lane] = x0;
-    yb[2 * lane + 1] = x1;
+  }
+  if (rot[0] || rot[1]) {
+    *(f32x2*)(yb + 2 * lane) = f32x2{x[0][0], x[0][1]};
+    *(f32x2*)(yb + D + 2 * lane) = f32x2{x[1][0], x[1][1]};
     wave_sync();
-    float norm = 1.0f;
-    if (rot) {
-      wave_lds_fwht128<1>(yb, p.had_block, lane);
-      norm = had_norm(p.had_block);
-    }
-    const float y0 = yb[2 * lane], y1 = yb[2 * lane + 1];
-    // min and max over the head's values (128: all lanes, 64: half of them): one reduction of
-    // (max, -min) pairs, rows first (DPP)
-    float mx = row_allmax(fmaxf(y0, y1)), nmn = row_allmax(-fminf(y0, y1));
-    mx = max_xor16(mx);
-    nmn = max_xor16(nmn);
+    if (rot[0] && rot[1]) wave_lds_fwht128<2>(yb, p.had_block, lane);
+    else if (rot[0]) wave_lds_fwht128<1>(yb, p.had_block, lane);
+    else wave_lds_fwht128<1>(yb + D, p.had_block, lane);
+    const f32x2 yk = *(const f32x2*)(yb + 2 * lane), yv = *(const f32x2*)(yb + D + 2 * lane);
+    x[0][0] = yk.x; x[0][1] = yk.y; x[1][0] = yv.x; x[1][1] = yv.y;
+    wave_sync();                                             // yb is rewritten below
+  }
+  // min and max over each head's values (128: all lanes, 64: half of them): reductions of
+  // (max, -min) pairs, rows first (DPP)
+  float mx[2], nmn[2];
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    mx[w] = row_allmax(fmaxf(x[w][0], x[w][1]));
+    nmn[w] = row_allmax(-fminf(x[w][0], x[w][1]));
+  }
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    mx[w] = max_xor16(mx[w]);
+    nmn[w] = max_xor16(nmn[w]);
     if (!HP) {
-      mx = max_xor32(mx);
-      nmn = max_xor32(nmn);
+      mx[w] = max_xor32(mx[w]);
+      nmn[w] = max_xor32(nmn[w]);
     }
-    const float mn = -nmn;
-    const float range = mx - mn;
+  }
+  float d[2][2];
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const float norm = rot[w] ? had_norm(p.had_block) : 1.0f;
+    const float mn = -nmn[w];
+    const float range = mx[w] - mn;
     float inv, zq, s_store, z_store;
     if (range > 0.0f) {
       inv = 15.0f / range;
@@ -191,31 +210,29 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
       s_store = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
       z_store = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
     }
-    const float c0 = __builtin_amdgcn_fmed3f(rintf(y0 * inv) + zq, 0.0f, 15.0f);
-    const float c1 = __builtin_amdgcn_fmed3f(rintf(y1 * inv) + zq, 0.0f, 15.0f);
+    const float c0 = __builtin_amdgcn_fmed3f(rintf(x[w][0] * inv) + zq, 0.0f, 15.0f);
+    const float c1 = __builtin_amdgcn_fmed3f(rintf(x[w][1] * inv) + zq, 0.0f, 15.0f);
     if (place) {
-      uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes);
-      float* meta = const_cast<float*>(which ? p.v_meta : p.k_meta);
+      uint8_t* codes = const_cast<uint8_t*>(w ? p.v_codes : p.k_codes);
+      float* meta = const_cast<float*>(w ? p.v_meta : p.k_meta);
       codes[vec * (DH / 2) + (lane & (DH / 2 - 1))] = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
       if ((lane & (DH / 2 - 1)) == 0) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
     }
-    const float d0 = s_store * (c0 - z_store), d1 = s_store * (c1 - z_store);
-    wave_sync();                                             // every read of yb above is done
-    if (which == 0) {
-#pragma unroll
-      for (int j = 0; j < G; ++j) {
-        float part = fmaf(qrot[j * D + 2 * lane], d0, qrot[j * D + 2 * lane + 1] * d1);
-        part = row_allsum(part);
-        part = add_xor16(part);
-        part = add_xor32(part);
-        if (lane == 0) lg[j] = part * qmul;
-      }
-    } else {
-      yb[2 * lane] = d0;
-      yb[2 * lane + 1] = d1;
-    }
-    wave_sync();
+    d[w][0] = s_store * (c0 - z_store);
+    d[w][1] = s_store * (c1 - z_store);
   }
+  // the new token's logits against the rotated query rows, and its dequantised V row
+  *(f32x2*)(yb + 2 * lane) = f32x2{d[1][0], d[1][1]};
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const f32x2 qq = *(const f32x2*)(qrot + j * D + 2 * lane);
+    float part = fmaf(qq.x, d[0][0], qq.y * d[0][1]);
+    part = row_allsum(part);
+    part = add_xor16(part);
+    part = add_xor32(part);
+    if (lane == 0) lg[j] = part * qmul;
+  }
+  wave_sync();
   const int head0 = (G > 4) ? 4 * (grp & 1) : 0;
   const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
   const bool counts = (G > 4) ? (lane == 0 || lane == 16) : (lane == 0);   // one lane per head group holds the weight
@@ -232,10 +249,9 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
 // one batch's (scale, zero) pairs: K 4 pages x 128 B, then V (twice that for a pair of 64-channel heads)
 template <bool HP> constexpr int kMetaBytes = HP ? 2048 : 1024;
 // The P buffer is never a transfer target.  Up to G = 4 it also serves, at the start of a range, as the
-// query preparation's scratch (rotated query rows, 2 KB, next to 16 + 144 floats), so that this work
-// touches no memory a transfer may be writing.
-template <int G> constexpr int kPbufAlloc = (G <= 4 && (G * 128 + 16 + 144) * 4 > kPbufBytes) ? (G * 128 + 16 + 144) * 4 : kPbufBytes;
-template <int G, bool HP> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufAlloc<G> + 2 * kMetaBytes<HP>;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
+// query preparation's scratch (the rotated query rows, at most 2 KB), so that this work touches no
+// memory a transfer may be writing.
+template <int G, bool HP> constexpr int kWaveLdsG = 12 * kTileBytes + kPbufBytes + 2 * kMetaBytes<HP>;   // per wavefront: K buffer, two V buffers, P buffer, two metadata buffers
 
 // Two ways of giving wavefronts their work.
 //
@@ -299,7 +315,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
   uint8_t* const vbuf_b = kbuf + 8 * kTileBytes;
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
-  uint8_t* const mbuf_a = pbuf + kPbufAlloc<G>;   // metadata of the batch in vbuf_a / vbuf_b
+  uint8_t* const mbuf_a = pbuf + kPbufBytes;   // metadata of the batch in vbuf_a / vbuf_b
   uint8_t* const mbuf_b = mbuf_a + kMetaBytes<HP>;
   int* const done_cnt = (int*)(lds_all + NW * kWaveLds);        // PAIR: records left so far of the long [0] and the short [1] sequence
   float* const spare_rec = (float*)(lds_all + NW * kWaveLds + 16);   // PAIR, NW = 4: see above
@@ -543,7 +559,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // query scratch: up to G = 4 in the P buffer (no transfer ever targets it), else the second V
   // buffer for the rows (first written by the second batch's transfers, which leave after this)
   float* const qrows = (G <= 4) ? (float*)pbuf : (float*)vbuf_b;
-  float* const qred = (G <= 4) ? (float*)pbuf + G * 128 : (float*)pbuf;
+  // fused append scratch (272 floats): the second V buffer is idle until the first batch's body
+  // requests the second batch; with G = 8 it holds the query rows and the P buffer is free instead
+  float* const ascr = (G <= 4) ? (float*)vbuf_b : (float*)pbuf;
   u32x4 a_q[4];
   float qsum[NH];
   float qmul;
@@ -570,7 +588,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
   if (takes_new)
     append_token<G, NH, HP>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
-                            qred + 16, oacc, m_ref, lsum);
+                            ascr, oacc, m_ref, lsum);
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
   // only ones this wavefront has in flight.
