@@ -508,7 +508,10 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   //     blocks pay off on ragged batches from 576 items on (256 sequences x 4 heads: 82 -> 70 us,
   //     90 x 8: 70 -> 61 us, 72 x 8: 63 -> 57 us against 2 or 4 wavefronts interleaving each
   //     item's batches; equal lengths lose 2-8 us to the ranking and the records; at 528 items
-  //     four interleaving wavefronts per item are ahead: 51 against 64 us);
+  //     four interleaving wavefronts per item are ahead: 51 against 64 us).  Between 1025 and 1151
+  //     items two interleaving wavefronts per item still fit the slots well enough (136 x 8: 79
+  //     against 94 us in pair mode); from 1152 on they spill into a second round and pair mode
+  //     wins (160 x 8: 96 against 103 us);
   //   * beyond that blocks queue for slots in index order, which is list scheduling: one
   //     wavefront per item, sequences taken longest first, so the launch ends on the shortest.
   //     (Measured at 288..512 sequences x 8 heads: 173-270 us against 224-332 us in pair mode,
@@ -522,6 +525,7 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
       plan.num_splits == 1 && B <= 1024) {
     const int64_t blocks = (int64_t)((B + 1) / 2) * items;
     if ((int64_t)B * items >= 576 && blocks <= 512) p.pair = 4;
+    else if ((int64_t)B * items >= 1152 && blocks <= 1024) p.pair = 2;   // (whatever the plan's wavefronts per item)
     else if (plan.waves_per_item == 1 && (int64_t)B * items > 256) {
       if (blocks <= 1024) p.pair = 2;
       else p.sorted = 1;
