@@ -89,7 +89,10 @@ def _case(saw, w, out_dtype=torch.float32, unmapped=()):
     worst = 0.0
     for b in range(B):
         err = parity.attn_error(o[b:b + 1], o_ref[b:b + 1])
-        assert err < (5e-2 if exempt[b] else tol), f"[{w.name} seq {b} len {int(w.seq_lens[b])} exempt={exempt[b]}] err={err:.2e}"
+        # (a code the boundary rule exempts moves one value by a whole quantisation step: up to 2/15 of the
+        # largest magnitude when the new token is most of what the sequence holds)
+        lim = (0.15 if int(w.seq_lens[b]) < 8 else 5e-2) if exempt[b] else tol
+        assert err < lim, f"[{w.name} seq {b} len {int(w.seq_lens[b])} exempt={exempt[b]}] err={err:.2e}"
         worst = max(worst, err)
     print(f"[{w.name} B={B} Hq={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} h={w.had_block} mask={w.rotate_mask}] "
           f"worst err={worst:.2e} exempt sequences={int(exempt.sum())}", flush=True)
@@ -152,3 +155,11 @@ def test_pair_blocks_of_four_with_empty_sequences(saw):
     """512 items: four-wavefront pair blocks; empty sequences still attend to (and store) their new token."""
     lens = [0] * 20 + [1] * 10 + [64] * 10 + [200] * 23 + [129]
     _case(saw, synth.make_workload("highconc", batch=len(lens), seq_lens=lens))
+
+
+@pytest.mark.parametrize("seed", range(100, 112))
+def test_random_shapes(saw, seed):
+    """The decode test's seeded random shapes through the append entry point."""
+    import test_gpu_decode as TD
+    kw, _ = TD._random_case(seed)
+    _case(saw, synth.make_workload("highconc", **kw))

@@ -193,3 +193,37 @@ def test_kv16_comparison_path_pair_mode(saw, dtype, B, Hq, Hkv):
     print(f"[kv16 pair {dtype} B={B} Hq={Hq}/{Hkv}] err={err:.2e}", flush=True)
     assert err < TOL
     assert not o[0].any()
+
+
+def _random_case(seed):
+    """A seeded random decode shape: batch sizes that reach every way of handing out work (partitions with
+    a merge pass, several wavefronts per item, pair blocks of two and of four, longest-first order), group
+    sizes, both head dims, block orders, rotation masks, and lengths with empty sequences, ties and
+    multiples of the 64-token batch."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    items_target = int(rng.choice([3, 40, 300, 600, 900, 1300, 1900, 2500]))
+    per_seq = Hkv // 2 if (d == 64 and Hkv % 2 == 0) else Hkv
+    B = int(min(1024, max(1, round(items_target / per_seq))))
+    top = int(rng.choice([70, 200, 700])) if B <= 40 else int(rng.choice([40, 130]))
+    lens = rng.integers(0, top + 1, size=B)
+    lens[rng.random(B) < 0.15] = 0
+    lens[rng.random(B) < 0.15] = 64 * int(rng.integers(0, max(1, top // 64) + 1))
+    if lens.max() == 0:
+        lens[0] = 1
+    h = int(rng.choice([1, 16, 32, 64] + ([128] if d == 128 else [])))
+    mask = int(rng.choice([3, 3, 1, 2]))
+    kw = dict(batch=B, seq_lens=lens, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, had_block=h, rotate_mask=mask)
+    if rng.random() < 0.3:
+        kw["sign_seed"] = int(rng.integers(1, 100))
+    splits = int(rng.choice([0, 0, 1, 3]))
+    return kw, splits
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(saw, seed):
+    kw, splits = _random_case(seed)
+    w = synth.make_workload("highconc", **kw)
+    _decode_case(saw, w, num_splits=splits, end_to_end=False)
