@@ -26,6 +26,7 @@ struct DecodeParams {
   int32_t len_bias;     // added to every seq_lens entry (1 when a separate store launch appended a token)
   int32_t sorted;           // matrix-core path, one block per (sequence, kv head): block z takes the sequence of length rank z
   int32_t pair;             // matrix-core path: blocks of this many wavefronts (2 or 4) over (long, short) sequence pairs; 0: off
+  int32_t pair_seqs;        // matrix-core path, pair mode: sequences per block, 2 or (with pair == 4) 3
   int32_t batch;
   int32_t waves_per_item;   // matrix-core path: wavefronts sharing one partition (1, 2 or 4)
   int32_t has_signs;        // any bit of `signs` set

@@ -510,21 +510,31 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   //     item's batches; equal lengths lose 2-8 us to the ranking and the records; at 528 items
   //     four interleaving wavefronts per item are ahead: 51 against 64 us).  Between 1025 and 1151
   //     items two interleaving wavefronts per item still fit the slots well enough (136 x 8: 79
-  //     against 94 us in pair mode); from 1152 on they spill into a second round and pair mode
-  //     wins (160 x 8: 96 against 103 us);
+  //     against 94 us in pair mode); from 1152 on they spill into a second round.  Up to 1536
+  //     items blocks of four wavefronts over THREE sequences then fill the chip where blocks of two
+  //     over pairs leave a quarter to a half of the slots empty (144 x 8: 93 -> 83 us, 160 x 8:
+  //     93 -> 85 us, 176 x 8: 94 -> 89 us, level at 192 x 8), beyond that blocks of two;
   //   * beyond that blocks queue for slots in index order, which is list scheduling: one
   //     wavefront per item, sequences taken longest first, so the launch ends on the shortest.
   //     (Measured at 288..512 sequences x 8 heads: 173-270 us against 224-332 us in pair mode,
   //     whose equal blocks make the last round as long as the others; 2 or 4 wavefronts per item
   //     were never better.)
   p.pair = 0;
+  p.pair_seqs = 2;
   p.sorted = 0;
   const int G = Hq / c->n_kv_heads;
   const int items = decode_items_per_seq(c->head_dim, c->n_kv_heads);   // head_dim 64: pairs of kv heads
   if (!kv16 && (c->head_dim == 128 || decode_head_pairs(c->head_dim, c->n_kv_heads, G)) &&
       plan.num_splits == 1 && B <= 1024) {
     const int64_t blocks = (int64_t)((B + 1) / 2) * items;
+    const int64_t blocks3 = (int64_t)((B + 2) / 3) * items;
     if ((int64_t)B * items >= 576 && blocks <= 512) p.pair = 4;
+    else if ((int64_t)B * items >= 1152 && blocks3 <= 512 && !(c->head_dim == 64 && G == 4)) {
+      // four wavefronts over three sequences (not for head pairs with eight query rows: two such
+      // blocks with their two spare records do not fit a compute unit's LDS)
+      p.pair = 4;
+      p.pair_seqs = 3;
+    }
     else if ((int64_t)B * items >= 1152 && blocks <= 1024) p.pair = 2;   // (whatever the plan's wavefronts per item)
     else if (plan.waves_per_item == 1 && (int64_t)B * items > 256) {
       if (blocks <= 1024) p.pair = 2;

@@ -282,7 +282,12 @@ enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 // 64, then head 2j+1's), the G query rows (G/2 per kv head) carry zeros in the other head's half,
 // and everything between the transfers and the epilogue runs exactly as for head_dim 128; only the
 // (scale, zero) pairs are per (token, kv head), and a row's own 64 output channels are kept.
-template <int G, int NW, bool PAIR, bool HP = false>
+// PK (pair mode): sequences per block, 2 (ranks r and B-1-r) or 3 (ranks r, 2n-1-r and 2n+r with
+// n = ceil(B/3): the first two add up alike, the third makes the totals differ by up to a third of
+// the spread of the lengths).  Four wavefronts over three sequences put 4/3 wavefronts on a (sequence,
+// kv head) item, which fills the chip when there are 1025 to 1536 items - too many for four
+// wavefronts per pair, and with two per pair a quarter to a half of the slots would stay empty.
+template <int G, int NW, bool PAIR, bool HP = false, int PK = 2>
 // (a launch of this kernel puts at most 8 wavefronts on a compute unit, 2 per SIMD: let the
 // register allocator use the 256 registers that leaves each of them)
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -309,7 +314,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // accesses proceed while transfers are in flight (with two objects it replaces those scopes by
   // per-object ones and then orders every LDS access behind every transfer).
   constexpr int kRecFloats = G * 128 + 2 * G;                   // a record: accumulator rows, then (max, sum) per row
-  constexpr int kSpareBytes = (PAIR && NW > 2) ? kRecFloats * 4 : 0;
+  constexpr int K = PAIR ? PK : 1;                              // sequences of a pair-mode block
+  static_assert(PK == 2 || (PK == 3 && NW == 4), "three sequences per block go with four wavefronts");
+  constexpr int kSpareBytes = (PAIR && NW > 2) ? (K - 1) * kRecFloats * 4 : 0;
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds + 16 + kSpareBytes];
   uint8_t* const kbuf = lds_all + wave * kWaveLds;
   uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
@@ -317,85 +324,92 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   uint8_t* const pbuf = kbuf + 12 * kTileBytes;
   uint8_t* const mbuf_a = pbuf + kPbufBytes;   // metadata of the batch in vbuf_a / vbuf_b
   uint8_t* const mbuf_b = mbuf_a + kMetaBytes<HP>;
-  int* const done_cnt = (int*)(lds_all + NW * kWaveLds);        // PAIR: records left so far of the long [0] and the short [1] sequence
-  float* const spare_rec = (float*)(lds_all + NW * kWaveLds + 16);   // PAIR, NW = 4: see above
+  int* const done_cnt = (int*)(lds_all + NW * kWaveLds);        // PAIR: records left so far of the block's sequences [k]
+  float* const spare_rec = (float*)(lds_all + NW * kWaveLds + 16);   // PAIR, NW = 4: spare record of sequence k >= 1 at (k - 1) * kRecFloats
 
   // ---- the ranges this wavefront streams: (sequence, first token, end token, what to do with the result) ----
   int nseg = 1;
-  int sg_b[2] = {(int)blockIdx.z, 0}, sg_t0[2] = {split * p.chunk_tokens, 0}, sg_t1[2] = {0, 0};
-  int sg_mode[2] = {kSegSplitKV, kSegAlone};
-  int sg_len[2] = {0, 0};                      // PAIR: length of the range's sequence
-  int sg_seq[2] = {0, 0};                      // PAIR: 0 the block's long sequence, 1 the short one
-  uint32_t part_mask[2] = {0u, 0u};            // PAIR: wavefronts with a share of the long / short sequence
-  int spare_wave = -1;                         // PAIR: wavefront whose record of the short sequence is in the spare slot
+  // (a wavefront has at most one range per sequence of its block; the arrays are read with
+  // select chains, never indexed at run time)
+  constexpr int MS = (K > 2) ? K : 2;
+  int sg_t0[MS], sg_t1[MS], sg_mode[MS], sg_seq[MS];   // per range: tokens, mode, which of the block's sequences
+  int bk[MS], lk[MS];                                   // per sequence of the block: index in the batch, cached tokens
+#pragma unroll
+  for (int i = 0; i < MS; ++i) { sg_t0[i] = 0; sg_t1[i] = 0; sg_mode[i] = kSegAlone; sg_seq[i] = 0; bk[i] = 0; lk[i] = 0; }
+  bk[0] = (int)blockIdx.z; sg_t0[0] = split * p.chunk_tokens; sg_mode[0] = kSegSplitKV;
+  uint32_t part_mask[MS];                      // PAIR: wavefronts with a share of sequence k of the block
+#pragma unroll
+  for (int i = 0; i < MS; ++i) part_mask[i] = 0u;
   if (PAIR) {
     const int B = p.batch;
-    if (threadIdx.x < 2) done_cnt[threadIdx.x] = 0;
+    if (threadIdx.x < 4) done_cnt[threadIdx.x] = 0;
     __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
     const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
-    const int r_long = blockIdx.z, r_short = B - 1 - r_long;
-    const bool self = r_long == r_short;                // odd batch: the middle sequence pairs with itself
-    const int b_long = seq_of_rank(lane, lc, r_long);
-    const int b_short = self ? b_long : seq_of_rank(lane, lc, r_short);
-    const int l_long = lc.lens[b_long];
-    const int l_short = self ? 0 : lc.lens[b_short];
-    const int nb_long = (l_long + 63) >> 6, nb_short = (l_short + 63) >> 6;
-    // Shares of the batches [0, nb_long) of the long sequence followed by the short one's: wavefront
-    // k takes [T k / NW, T (k+1) / NW).  A wavefront that gets the end of one and the start of the
-    // other pays a second prologue, about the time of two or three batches: that cost sits between
-    // the two sequences as kGap batches nobody streams (short_at is where the short sequence starts;
-    // 2 and 3 measured 1-2 % better than their neighbours for blocks of two and of four).
-    constexpr int kGap = (NW > 2) ? 3 : 2;
-    const int short_at = nb_long + (nb_short > 0 ? kGap : 0);
-    const int T = short_at + nb_short;
-#pragma unroll
-    for (int k = 0; k < NW; ++k) {       // (T < 2^27 batches: the products fit 32 bits)
-      const int lo_k = (int)(((uint32_t)T * (uint32_t)k) / NW), hi_k = (int)(((uint32_t)T * (uint32_t)(k + 1)) / NW);
-      if (lo_k < min(hi_k, nb_long)) part_mask[0] |= 1u << k;
-      if (max(lo_k, short_at) < hi_k) part_mask[1] |= 1u << k;
+    // the block's sequences by length rank, longest first; rank >= B: no such sequence
+    int rk[K], nbk[K], stk[K];
+    bool present[K];
+    if (K == 2) {
+      rk[0] = blockIdx.z; rk[1] = B - 1 - rk[0];
+      present[0] = true; present[1] = rk[1] != rk[0];   // odd batch: the middle sequence is alone
+    } else {
+      const int n3 = (B + 2) / 3;
+      rk[0] = blockIdx.z; rk[1] = 2 * n3 - 1 - rk[0]; rk[K - 1] = 2 * n3 + rk[0];
+      present[0] = true; present[1] = rk[1] < B; present[K - 1] = rk[K - 1] < B;
     }
-    const bool long_shared = __popc(part_mask[0]) > 1, short_shared = __popc(part_mask[1]) > 1;
-    if (short_shared) {
-      const uint32_t both = part_mask[0] & part_mask[1];          // at most one wavefront
-      if (both) spare_wave = __ffs((int)both) - 1;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      bk[k] = present[k] ? seq_of_rank(lane, lc, rk[k]) : 0;
+      lk[k] = present[k] ? lc.lens[bk[k]] : 0;
+      nbk[k] = (lk[k] + 63) >> 6;
+    }
+    // Shares of the sequences' batches laid end to end: wavefront w takes [T w / NW, T (w+1) / NW).
+    // A wavefront that gets the end of one sequence and the start of the next pays another
+    // prologue, about the time of two or three batches: that cost sits in front of every sequence
+    // but the first as kGap batches nobody streams (stk[k] is where sequence k starts; 2 and 3
+    // measured 1-2 % better than their neighbours for blocks of two and of four).
+    constexpr int kGap = (NW > 2) ? 3 : 2;
+    int T = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      stk[k] = T + ((k > 0 && nbk[k] > 0) ? kGap : 0);
+      T = stk[k] + nbk[k];
+    }
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {       // (T < 2^27 batches: the products fit 32 bits)
+      const int lo_w = (int)(((uint32_t)T * (uint32_t)w) / NW), hi_w = (int)(((uint32_t)T * (uint32_t)(w + 1)) / NW);
+#pragma unroll
+      for (int k = 0; k < K; ++k)
+        if (max(lo_w, stk[k]) < min(hi_w, stk[k] + nbk[k])) part_mask[k] |= 1u << w;
     }
     const int lo = (int)(((uint32_t)T * (uint32_t)wave) / NW), hi = (int)(((uint32_t)T * (uint32_t)(wave + 1)) / NW);
-    const bool has_long = lo < min(hi, nb_long), has_short = max(lo, short_at) < hi;
     nseg = 0;
-    // first the short sequence's share.  (With a fused append an empty sequence still has its new
-    // token to attend to: it gets an empty range instead of a zero row; the last wavefront takes it.)
-    if (has_short) {
-      sg_b[0] = b_short; sg_t0[0] = 64 * (max(lo, short_at) - short_at); sg_t1[0] = min(l_short, 64 * (hi - short_at));
-      sg_len[0] = l_short; sg_mode[0] = short_shared ? kSegShare : kSegAlone; sg_seq[0] = 1;
-      nseg = 1;
-    } else if (!self && nb_short == 0 && wave == NW - 1) {
-      if (p.append) {
-        sg_b[0] = b_short; sg_t0[0] = 0; sg_t1[0] = 0; sg_len[0] = 0; sg_mode[0] = kSegAlone; sg_seq[0] = 1;
-        nseg = 1;
-      } else {
-        for (int i = lane; i < G * DH; i += 64)
-          store_elem(p.out, p.out_dtype, ((int64_t)b_short * p.n_q_heads + kvh * G) * DH + i, 0.f);
+    // Last sequence first: what a wavefront streams last is then the sequence it shares with the
+    // wavefronts before it, whose record can stay in its own buffers.  A sequence without cached
+    // tokens has no share: its zero row - or, with a fused append, an empty range that still
+    // attends to the new token - goes to the last wavefront (the first, for the block's longest).
+#pragma unroll
+    for (int k = K - 1; k >= 0; --k) {
+      const int p0 = max(lo, stk[k]), p1 = min(hi, stk[k] + nbk[k]);
+      bool add = false;
+      int t0 = 0, t1 = 0, mode_k = kSegAlone;
+      if (p0 < p1) {
+        add = true;
+        t0 = 64 * (p0 - stk[k]); t1 = min(lk[k], 64 * (p1 - stk[k]));
+        mode_k = __popc(part_mask[k]) > 1 ? kSegShare : kSegAlone;
+      } else if (present[k] && nbk[k] == 0 && wave == (k == 0 ? 0 : NW - 1)) {
+        if (p.append) {
+          add = true;
+        } else {
+          for (int i = lane; i < G * DH; i += 64)
+            store_elem(p.out, p.out_dtype, ((int64_t)bk[k] * p.n_q_heads + kvh * G) * DH + i, 0.f);
+        }
       }
-    }
-    // last the long sequence's share, so that its record can stay in this wavefront's buffers
-    // (an empty long sequence, then the short one is empty too, goes to wavefront 0)
-    int sb = 0, st0 = 0, st1 = 0, smode = kSegAlone;
-    bool add_long = false;
-    if (has_long) {
-      sb = b_long; st0 = 64 * lo; st1 = min(l_long, 64 * min(hi, nb_long)); smode = long_shared ? kSegShare : kSegAlone;
-      add_long = true;
-    } else if (nb_long == 0 && wave == 0) {
-      if (p.append) {
-        sb = b_long; add_long = true;
-      } else {
-        for (int i = lane; i < G * DH; i += 64)
-          store_elem(p.out, p.out_dtype, ((int64_t)b_long * p.n_q_heads + kvh * G) * DH + i, 0.f);
+      if (add) {
+#pragma unroll
+        for (int i = 0; i < MS; ++i)
+          if (i == nseg) { sg_t0[i] = t0; sg_t1[i] = t1; sg_mode[i] = mode_k; sg_seq[i] = k; }
+        ++nseg;
       }
-    }
-    if (add_long) {
-      if (nseg == 0) { sg_b[0] = sb; sg_t0[0] = st0; sg_t1[0] = st1; sg_len[0] = l_long; sg_mode[0] = smode; sg_seq[0] = 0; }
-      else           { sg_b[1] = sb; sg_t0[1] = st0; sg_t1[1] = st1; sg_len[1] = l_long; sg_mode[1] = smode; sg_seq[1] = 0; }
-      ++nseg;
     }
     wave_sync();                                        // the ranking's scratch lived in kbuf (and on into vbuf_a)
   } else if (p.sorted) {
@@ -403,7 +417,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // in index order as earlier ones finish, so taking the sequences longest first leaves the
     // shortest for the end of the launch
     const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
-    sg_b[0] = seq_of_rank(lane, lc, blockIdx.z);
+    bk[0] = seq_of_rank(lane, lc, blockIdx.z);
     wave_sync();
   }
 
@@ -431,10 +445,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
 #pragma unroll 1
   for (int seg = 0; seg < nseg; ++seg) {
-  const int b = seg == 0 ? sg_b[0] : sg_b[1];
-  const int t_begin = seg == 0 ? sg_t0[0] : sg_t0[1];
-  const int mode = seg == 0 ? sg_mode[0] : sg_mode[1];
-  const int sq = seg == 0 ? sg_seq[0] : sg_seq[1];
+#define SAW_SEG(a) (seg == 0 ? a[0] : (seg == 1 || MS == 2) ? a[1] : a[MS - 1])
+#define SAW_SEQ(a) (sq == 0 ? a[0] : (sq == 1 || MS == 2) ? a[1] : a[MS - 1])
+  const int sq = SAW_SEG(sg_seq);
+  const int b = SAW_SEQ(bk);
+  const int t_begin = SAW_SEG(sg_t0);
+  const int mode = SAW_SEG(sg_mode);
   const int64_t pt_row = (int64_t)b * p.max_pages;
   // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page
   // pg_first + 64*window + l, i.e. one vector load covers a window of 16 batches; `pidv_nx` is
@@ -450,8 +466,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   SAW_LOAD_PIDS(pidv, pg_first)
   int t_end, seq_len_b;                // seq_len_b: cached tokens of the sequence (= position of an appended token)
   if (PAIR) {
-    t_end = seg == 0 ? sg_t1[0] : sg_t1[1];
-    seq_len_b = seg == 0 ? sg_len[0] : sg_len[1];
+    t_end = SAW_SEG(sg_t1);
+    seq_len_b = SAW_SEQ(lk);
   } else {
     seq_len_b = max(min(p.seq_lens[b] + p.len_bias, p.bound), 0);
     t_end = min(seq_len_b, t_begin + p.chunk_tokens);
@@ -818,8 +834,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // start of the V buffers (with G = 8 the pairs land at the start of the second one), or in the
   // block's spare slot when this wavefront still has its share of the long sequence to stream.
   float* const fb = (float*)vbuf_a;
-  const bool to_spare = PAIR && NW > 2 && emode == kSegShare && sq == 1 && wave == spare_wave;
-  float* const rec = to_spare ? spare_rec : fb;
+  // (a shared range that is not this wavefront's last is the start of sequence sq >= 1)
+  const bool to_spare = PAIR && NW > 2 && emode == kSegShare && seg != nseg - 1;
+  float* const rec = to_spare ? spare_rec + (sq - 1) * kRecFloats : fb;
   float* const ml = rec + G * D;
   wave_sync();
 #pragma unroll
@@ -844,7 +861,13 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   if (PAIR && emode == kSegShare) {
     // LDS operations of a wavefront complete in order, so the record is in place before the
     // count; the wavefront that finds all others counted does the rest for everybody.
-    const uint32_t mask = sq ? part_mask[1] : part_mask[0];
+    // the sequence's wavefronts, and those of them that also hold a share of an earlier sequence of
+    // the block (at most one: its record is the one in the spare slot)
+    uint32_t mask = part_mask[0], lower = 0u;
+#pragma unroll
+    for (int k = 1; k < K; ++k)
+      if (k == sq) { mask = part_mask[k]; } else if (k < sq) { lower |= part_mask[k]; }
+    if (sq > 0) lower |= part_mask[0];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     int before = 0;
     if (lane == 0) before = __hip_atomic_fetch_add(done_cnt + sq, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -860,8 +883,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
       if ((mask >> k) & 1u) {
-        const float* rk = (sq == 1 && k == spare_wave) ? spare_rec
-                                                       : (const float*)(lds_all + k * kWaveLds + 4 * kTileBytes);
+        const float* rk = ((lower >> k) & 1u) ? spare_rec + (sq - 1) * kRecFloats
+                                              : (const float*)(lds_all + k * kWaveLds + 4 * kTileBytes);
 #pragma unroll
         for (int r = 0; r < NW; ++r)
           if (r == nrec) recs[r] = rk;
@@ -923,9 +946,15 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #undef SAW_ROTATE_PIDS
 #undef SAW_LOAD_PIDS
 #undef SAW_CLAMP_PID
+#undef SAW_SEG
+#undef SAW_SEQ
 
 template <int G, bool HP>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
+  if (p.pair == 4 && p.pair_seqs == 3) {
+    decode_int4_mfma_kernel<G, 4, true, HP, 3><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
+    return;
+  }
   if (p.pair == 4) {
     decode_int4_mfma_kernel<G, 4, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(256), 0, st>>>(p);
     return;

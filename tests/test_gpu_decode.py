@@ -84,11 +84,13 @@ def test_ragged_lengths_with_empty_and_single(saw):
     assert not o[0].any()                                           # empty sequence -> zero row
 
 
-@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (65, 8), (200, 8), (255, 8), (300, 8)])
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (65, 8), (130, 8), (162, 8), (191, 8), (383, 4),
+                                   (200, 8), (255, 8), (300, 8)])
 def test_many_sequences_balanced_item_order(saw, B, Hkv):
     """More (sequence, kv head) items than compute units: the kernel pairs long with short sequences
-    (everything resident at once: blocks of four wavefronts per pair from 512 to 1024 items, the first
-    four cases, of two up to 2048 items) or, beyond that, takes them longest first.  Every sequence is
+    (everything resident at once: blocks of four wavefronts per pair from 576 to 1024 items, the first
+    four cases, blocks of four over three sequences up to 1536 items, the next four, blocks of two up to
+    2048 items) or, beyond that, takes them longest first.  Every sequence is
     compared, so an item served twice or never shows up; lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)
@@ -227,3 +229,15 @@ def test_random_shapes(saw, seed):
     kw, splits = _random_case(seed)
     w = synth.make_workload("highconc", **kw)
     _decode_case(saw, w, num_splits=splits, end_to_end=False)
+
+
+@pytest.mark.parametrize("lens", [[0] * 150, [1] * 150, [64] * 100 + [0] * 50, [200] * 3 + [1] * 147,
+                                  [129] * 50 + [64] * 50 + [0] * 50, [300, 10, 5] * 50, list(range(150)),
+                                  [128] * 148, [64 * (i % 4) for i in range(191)], [257] * 75 + [3] * 75])
+def test_blocks_of_four_over_three_sequences(saw, lens):
+    """1152..1536 items: a block of four wavefronts takes three sequences laid end to end.  The lengths
+    put the cuts everywhere: sequences that fit inside one share (three ranges for one wavefront), empty
+    sequences, batches fewer than wavefronts, a batch size that leaves the last block with one or two
+    sequences only."""
+    w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens)
+    _decode_case(saw, w, end_to_end=False)

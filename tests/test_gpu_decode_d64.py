@@ -63,10 +63,13 @@ def test_head_pairs_ragged_with_empty_and_single(saw):
     assert not o[0].any()
 
 
-@pytest.mark.parametrize("B,Hq,Hkv", [(70, 32, 8), (140, 16, 4), (150, 32, 8), (255, 8, 8), (300, 8, 8), (600, 8, 8)])
+@pytest.mark.parametrize("B,Hq,Hkv", [(70, 32, 8), (140, 16, 4), (150, 32, 8), (255, 8, 8), (300, 8, 8), (340, 16, 8),
+                                      (340, 32, 8), (600, 8, 8)])
 def test_head_pairs_many_sequences(saw, B, Hq, Hkv):
     """More (sequence, head pair) items than compute units: pair mode (blocks of two wavefronts, of four
-    from 576 to 1024 items: the third and fourth case), longest first beyond 2048 items (the last case).
+    from 576 to 1024 items: the third and fourth case; of four over three sequences from 1152 to 1536 items:
+    the sixth, while the seventh, with eight query rows per head pair, stays with blocks of two), longest first
+    beyond 2048 items (the last case).
     Lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 200, size=B)
