@@ -421,6 +421,13 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     wave_sync();
   }
 
+  // The bookkeeping above is wavefront-uniform, but it is read once per range only: parked in vector
+  // registers on purpose (the set-up code is short of scalar ones) and brought back when needed.
+#pragma unroll
+  for (int i = 0; i < MS; ++i) {
+    asm volatile("" : "+v"(sg_t0[i]), "+v"(sg_t1[i]), "+v"(sg_mode[i]), "+v"(sg_seq[i]));
+    asm volatile("" : "+v"(bk[i]), "+v"(lk[i]), "+v"(part_mask[i]));
+  }
   const int row16 = lane & 15, grp = lane >> 4;
   const int64_t head_tile = (int64_t)kvh * kTileBytes;
   const int64_t page_stride = (int64_t)p.n_kv_heads * (HP ? kTileBytes / 2 : kTileBytes);
@@ -447,10 +454,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   for (int seg = 0; seg < nseg; ++seg) {
 #define SAW_SEG(a) (seg == 0 ? a[0] : (seg == 1 || MS == 2) ? a[1] : a[MS - 1])
 #define SAW_SEQ(a) (sq == 0 ? a[0] : (sq == 1 || MS == 2) ? a[1] : a[MS - 1])
-  const int sq = SAW_SEG(sg_seq);
-  const int b = SAW_SEQ(bk);
-  const int t_begin = SAW_SEG(sg_t0);
-  const int mode = SAW_SEG(sg_mode);
+  const int sq = __builtin_amdgcn_readfirstlane(SAW_SEG(sg_seq));
+  const int b = __builtin_amdgcn_readfirstlane(SAW_SEQ(bk));
+  const int t_begin = __builtin_amdgcn_readfirstlane(SAW_SEG(sg_t0));
+  const int mode = __builtin_amdgcn_readfirstlane(SAW_SEG(sg_mode));
   const int64_t pt_row = (int64_t)b * p.max_pages;
   // Page ids: lane l of `pidv` holds the (clamped) physical page of logical page
   // pg_first + 64*window + l, i.e. one vector load covers a window of 16 batches; `pidv_nx` is
@@ -466,8 +473,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   SAW_LOAD_PIDS(pidv, pg_first)
   int t_end, seq_len_b;                // seq_len_b: cached tokens of the sequence (= position of an appended token)
   if (PAIR) {
-    t_end = SAW_SEG(sg_t1);
-    seq_len_b = SAW_SEQ(lk);
+    t_end = __builtin_amdgcn_readfirstlane(SAW_SEG(sg_t1));
+    seq_len_b = __builtin_amdgcn_readfirstlane(SAW_SEQ(lk));
   } else {
     seq_len_b = max(min(p.seq_lens[b] + p.len_bias, p.bound), 0);
     t_end = min(seq_len_b, t_begin + p.chunk_tokens);
@@ -868,6 +875,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     for (int k = 1; k < K; ++k)
       if (k == sq) { mask = part_mask[k]; } else if (k < sq) { lower |= part_mask[k]; }
     if (sq > 0) lower |= part_mask[0];
+    mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)mask);
+    lower = (uint32_t)__builtin_amdgcn_readfirstlane((int)lower);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     int before = 0;
     if (lane == 0) before = __hip_atomic_fetch_add(done_cnt + sq, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
