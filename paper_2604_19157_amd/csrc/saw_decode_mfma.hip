@@ -960,9 +960,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 
 template <int G, bool HP>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
-  if (p.pair == 4 && p.pair_seqs == 3) {
-    decode_int4_mfma_kernel<G, 4, true, HP, 3><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
-    return;
+  if constexpr (!(HP && G == 8)) {       // (two such blocks of head pairs with eight query rows would not fit LDS)
+    if (p.pair == 4 && p.pair_seqs == 3) {
+      decode_int4_mfma_kernel<G, 4, true, HP, 3><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
+      return;
+    }
   }
   if (p.pair == 4) {
     decode_int4_mfma_kernel<G, 4, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(256), 0, st>>>(p);
