@@ -29,6 +29,9 @@
  *     is physical page page_table[b][i]; logical position p sits in logical page
  *     p / page_size at slot p % page_size.
  *   - Query head j reads kv head j / (n_q_heads / n_kv_heads).
+ *   - Alignment: code pools, K/V inputs, read-back outputs and workspaces 16 bytes; the metadata
+ *     pools 8 bytes for the store and 16 bytes for the decode calls (which fetch the pairs with
+ *     16-byte transfers); anything else is SAW_EINVAL.
  *   - Supported: page_size 16; head_dim 64 or 128; had_block 1 (no rotation), 16, 32,
  *     64 or 128 with had_block <= head_dim; n_q_heads / n_kv_heads in {1, 2, 4, 8}.
  *   - Randomised Hadamard (Sec. 3): with sign_bits set in the cache descriptor the rotation of
@@ -99,7 +102,7 @@ const char* saw_strerror(int code);
  *               distance between tokens is token_stride_elems (>= n_kv_heads*head_dim,
  *               multiple of 8); base pointers 16-byte aligned.
  *   page_table  device, [n_seqs][max_pages_per_seq].
- *   slots       device, [T][2] int32 = (sequence index, logical position).  Slots must be
+ *   slots       device, [T][2] int32 = (sequence index, logical position), 8-byte aligned.  Slots must be
  *               unique within a call.  A token whose sequence index, position or page id
  *               is out of range (seq outside [0, n_seqs), position outside
  *               [0, max_pages_per_seq*page_size), page outside [0, num_pages)) is skipped.
@@ -126,6 +129,17 @@ size_t saw_decode_workspace_bytes(const saw_cache_t* cache, int32_t B, int32_t n
  */
 int saw_decode_plan(const saw_cache_t* cache, int32_t B, int32_t max_seq_len, int32_t num_splits,
                     int32_t* splits_out, int32_t* chunk_tokens_out);
+
+/*
+ * Host-side mirror of the longest-first order in which the decode kernels take a large batch's
+ * sequences (they derive it themselves from seq_lens on the device; nothing has to be passed in).
+ * For inspection and tests: seq_lens_host and order_out are HOST arrays of B <= 1024 entries;
+ * order_out[r] = index of the sequence at rank r.  Sequences are ranked by 64 length classes scaled
+ * to the longest sequence of the batch (after clamping to max_seq_len; <= 0: no clamp), ties in
+ * index order; sequences without cached tokens form the last class alone, so none of them ranks
+ * ahead of a non-empty sequence whatever the bound.
+ */
+int saw_decode_rank_order(const int32_t* seq_lens_host, int32_t B, int32_t max_seq_len, int32_t* order_out);
 
 /*
  * One decode step over the INT4 cache (Sec. 2: o = softmax(q K^T/sqrt(d)) V; Sec. 4.1 and
@@ -167,8 +181,9 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
  *               16-byte aligned: token b belongs to sequence b.
  *   seq_lens    device, [B] int32: tokens cached BEFORE this call; the new token goes to
  *               position seq_lens[b] (its page must be mapped in page_table; if it is not, the
- *               token is still attended to but not stored).  Not modified: the caller advances
- *               its lengths afterwards.
+ *               token is still attended to but not stored).  A sequence whose length exceeds
+ *               max_seq_len breaks the bound: nothing is stored for it and its output row covers a
+ *               clamped range only.  Not modified: the caller advances its lengths afterwards.
  *   max_seq_len host-side upper bound on seq_lens (before the append); <= 0 means
  *               max_pages_per_seq * page_size - 1.  max_seq_len + 1 must fit the page table row.
  *   workspace   at least saw_decode_workspace_bytes(cache, B, n_q_heads, max_seq_len + 1, 0) bytes.
@@ -185,7 +200,8 @@ int saw_append_decode_attn(const saw_cache_t* cache, const void* K_new, const vo
  * Dequantise positions [pos_begin, pos_end) of sequence `seq` into dense fp32
  * [pos_end - pos_begin][n_kv_heads][head_dim] buffers: x^ = s (c - z) (App. A.1).  With
  * unrotate != 0 the rotated tensors are multiplied by H_blk once more, which returns them
- * to the original space (H is symmetric and orthonormal, App. A.4).  Either output may be
+ * to the original space (H is symmetric and orthonormal, App. A.4; with sign_bits set the factor
+ * is R^T = H_blk diag(sigma), the inverse of R).  Either output may be
  * NULL to skip it.  The caller guarantees the positions are backed by valid pages.
  */
 int saw_dequant_pages(const saw_cache_t* cache, const int32_t* page_table,
@@ -196,8 +212,9 @@ int saw_dequant_pages(const saw_cache_t* cache, const int32_t* page_table,
  * Flatten-dequantise (the flatten_dequant step of App. B's prefill breakdown; arithmetic of
  * App. A.1 and A.4): positions [pos_begin, pos_end) of sequence `seq` are gathered from the
  * INT4 pages into dense buffers for a prefill / chunked-prefill attention consumer,
- * x^ = s (c - z), multiplied by H_blk once more when unrotate != 0 (tensors the cache holds
- * rotated return to the original space; with unrotate == 0 they stay in the rotated space).
+ * x^ = s (c - z), multiplied by H_blk once more when unrotate != 0 (by R^T = H_blk diag(sigma) when
+ * sign_bits are set; tensors the cache holds rotated return to the original space; with
+ * unrotate == 0 they stay in the rotated space).
  *
  *   k_out, v_out  device, [pos_end - pos_begin][n_kv_heads][head_dim] of out_dtype
  *                 (SAW_BF16 | SAW_F16 | SAW_F32), 16-byte aligned, token_stride_elems elements

@@ -53,6 +53,7 @@ def lib() -> ctypes.CDLL:
         L.saw_decode_workspace_bytes.restype = sz
         L.saw_decode_workspace_bytes.argtypes = [cp, i32, i32, i32, i32]
         L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.saw_decode_rank_order.argtypes = [ctypes.POINTER(i32), i32, i32, ctypes.POINTER(i32)]
         L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
         L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.saw_append_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, vp]
@@ -132,6 +133,15 @@ def decode_plan(cache: Cache, B, max_seq_len, num_splits=0):
     _check(lib().saw_decode_plan(ctypes.byref(st), B, max_seq_len, num_splits, ctypes.byref(s), ctypes.byref(c)),
            "saw_decode_plan")
     return s.value, c.value
+
+
+def decode_rank_order(seq_lens, max_seq_len=0):
+    """saw_decode_rank_order: host-side mirror of the decode kernels' longest-first order (host ints in, list out)."""
+    B = len(seq_lens)
+    src = (ctypes.c_int32 * B)(*[int(x) for x in seq_lens])
+    dst = (ctypes.c_int32 * B)()
+    _check(lib().saw_decode_rank_order(src, B, int(max_seq_len), dst), "saw_decode_rank_order")
+    return list(dst)
 
 
 def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,

@@ -8,7 +8,7 @@ namespace saw {
 
 
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
-                 int32_t, int32_t, const int32_t*, const int32_t*, hipStream_t);
+                 int32_t, int32_t, const int32_t*, const int32_t*, int32_t, hipStream_t);
 int launch_flatten(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, void*, void*, int64_t,
                    hipStream_t);
 int launch_dequant(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t,
@@ -114,10 +114,10 @@ int saw_rotate_quant_store(const saw_cache_t* c, const void* K, const void* V, i
     return SAW_ENULL;
   if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems & 7)) return SAW_EINVAL;
   if (!aligned16(K) || !aligned16(V) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
-      (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
+      (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u) || (((uintptr_t)slots) & 7u))
     return SAW_EINVAL;
   return launch_store(c, K, V, in_dtype, T, token_stride_elems, page_table, n_seqs, max_pages_per_seq,
-                      slots, nullptr, (hipStream_t)stream);
+                      slots, nullptr, 0, (hipStream_t)stream);
 }
 
 size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_heads,
@@ -146,6 +146,27 @@ int saw_decode_plan(const saw_cache_t* c, int32_t B, int32_t max_seq_len, int32_
   return SAW_OK;
 }
 
+int saw_decode_rank_order(const int32_t* seq_lens_host, int32_t B, int32_t max_seq_len, int32_t* order_out) {
+  if (!seq_lens_host || !order_out) return SAW_ENULL;
+  if (B < 1 || B > 1024) return SAW_EINVAL;
+  const int bound = max_seq_len <= 0 ? 0x7fffffff : max_seq_len;
+  int nbmax = 0;
+  int cls[1024];
+  for (int b = 0; b < B; ++b) {
+    const int len = seq_lens_host[b] < 0 ? 0 : (seq_lens_host[b] > bound ? bound : seq_lens_host[b]);
+    cls[b] = len;
+    const int nb = (int)(((int64_t)len + 63) >> 6);
+    if (nb > nbmax) nbmax = nb;
+  }
+  const float kscale = rank_scale(nbmax);
+  for (int b = 0; b < B; ++b) cls[b] = rank_class(cls[b], kscale);
+  int n = 0;
+  for (int c = 0; c < 64; ++c)                       // class 0 first; inside a class by sequence index
+    for (int b = 0; b < B; ++b)
+      if (cls[b] == c) order_out[n++] = b;
+  return SAW_OK;
+}
+
 static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const void* vp, int kv_dtype,
                          const void* q, int32_t q_dtype, int32_t B, int32_t Hq, const int32_t* pt,
                          int32_t max_pages, const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
@@ -165,6 +186,8 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   if (!kp || !vp || !q || !pt || !seq_lens || !out || !ws) return SAW_ENULL;
   if (!kv16 && (!c->k_meta || !c->v_meta)) return SAW_ENULL;
   if (!aligned16(kp) || !aligned16(vp) || !aligned16(ws)) return SAW_EINVAL;
+  // (the INT4 kernels fetch the (scale, zero) pairs with 16-byte transfers)
+  if (!kv16 && (!aligned16(c->k_meta) || !aligned16(c->v_meta))) return SAW_EINVAL;
   if (!isfinite(sm_scale)) return SAW_EINVAL;
   SplitPlan plan;
   if (!make_plan(c, B, max_pages, max_seq_len, num_splits, kv16, &plan)) return SAW_EINVAL;
@@ -203,7 +226,7 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
       !seq_lens || !out || !ws)
     return SAW_ENULL;
   if (!aligned16(K_new) || !aligned16(V_new) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
-      !aligned16(ws) || (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
+      !aligned16(ws) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
     return SAW_EINVAL;
   if (!isfinite(sm_scale) || max_seq_len < 0) return SAW_EINVAL;
   // the plan covers the lengths after the append (max_seq_len + 1 tokens)
@@ -226,7 +249,7 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
   // head_dim 64 outside the head-pair kernel: two launches from the same call: append (token b -> sequence b at seq_lens[b]),
   // then decode over seq_lens[b] + 1 tokens
   const int rc = launch_store(c, K_new, V_new, kv_dtype, B, (int64_t)c->n_kv_heads * c->head_dim, page_table, B,
-                              max_pages, nullptr, seq_lens, (hipStream_t)stream);
+                              max_pages, nullptr, seq_lens, (int32_t)(after - 1), (hipStream_t)stream);
   if (rc != SAW_OK) return rc;
   return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
                     sm_scale, out, out_dtype, ws, plan, nullptr, nullptr, 0, 1, (hipStream_t)stream);

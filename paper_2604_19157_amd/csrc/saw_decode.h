@@ -33,6 +33,18 @@ struct DecodeParams {
   SignBits signs;           // R = diag(sigma) H_blk for every rotated tensor and the query; outputs take R^T
 };
 
+// Length classes of the in-kernel longest-first ranking (saw_rank.h), shared with the host-side
+// mirror saw_decode_rank_order.  `nbmax` is the batch's longest (clamped) sequence in 64-token
+// units.  Class 63 is for sequences without cached tokens only; the others spread over classes
+// 0 (longest) to 62 in proportion to their length.
+__host__ __device__ inline float rank_scale(int nbmax) { return 63.0f / (float)(nbmax > 1 ? nbmax : 1); }
+__host__ __device__ inline int rank_class(int len, float kscale) {
+  const int nb = (len + 63) >> 6;
+  if (nb == 0) return 63;
+  const int c = 62 - (int)((float)(nb - 1) * kscale);
+  return c < 0 ? 0 : c;
+}
+
 // MFMA INT4 decode (saw_decode_mfma.hip) for head_dim 128, grid = (splits, kv heads, batch), and
 // with `head_pairs` for head_dim 64, grid = (splits, kv heads / 2, batch): see decode_head_pairs().
 int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, bool head_pairs, dim3 grid, hipStream_t st);

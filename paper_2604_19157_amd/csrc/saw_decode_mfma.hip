@@ -511,7 +511,9 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int64_t e = ((int64_t)b * p.n_kv_heads * DH + (int64_t)kvh * D) / 2 + lane;
     new_wk = ((const uint32_t*)p.k_new)[e];
     new_wv = ((const uint32_t*)p.v_new)[e];
-    if ((seq_len_b >> 4) < p.max_pages) new_pid = p.page_table[pt_row + (seq_len_b >> 4)];
+    // (a length beyond the caller's bound was clamped for the attention; storing at the clamped
+    // position would overwrite a cached token, so such a token is attended to but not stored)
+    if ((seq_len_b >> 4) < p.max_pages && p.seq_lens[b] <= p.bound) new_pid = p.page_table[pt_row + (seq_len_b >> 4)];
   }
 
   // (first use of the page ids: only here, so that the query and new-token loads above are in

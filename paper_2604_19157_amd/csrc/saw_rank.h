@@ -11,6 +11,11 @@ namespace saw {
 // together: one memory latency), leaves them clamped in LDS and their classes in registers, makes
 // the class histogram (LDS atomics) and its prefix sums across lanes (lane c owns class c, class
 // 0 = longest); `seq_of_rank` finds the sequence at a rank with two ballots per 64 sequences.
+// The classes are scaled to the longest sequence the batch actually holds (a wavefront-wide
+// maximum of the clamped lengths), not to the caller's bound, so that a loose bound - the usual
+// serving call, which avoids a host read of the lengths - costs no balance; and class 63 holds the
+// sequences without cached tokens and nothing else, so an empty sequence never ranks ahead of a
+// non-empty one (the pair-mode share logic relies on that: see rank_class()).
 // LDS scratch: 64 + B ints, B <= kMaxRanked.
 constexpr int kMaxRanked = 1024;
 struct LenClasses {
@@ -19,16 +24,12 @@ struct LenClasses {
   const int* lens;           // LDS: the clamped lengths
   int cls[kMaxRanked / 64];  // class of sequence 64 v + lane (-1 past the batch)
 };
-__device__ __forceinline__ int len_class(int len, float kscale) {
-  return 63 - (int)((float)((len + 63) >> 6) * kscale);
-}
 template <int CTRL, int ROWMASK>
 __device__ __forceinline__ int dpp_i0(int v) {               // lanes without a source (or outside ROWMASK) read 0
   return __builtin_amdgcn_update_dpp(0, v, CTRL, ROWMASK, 0xf, false);
 }
 __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, int B, int lane, int* scratch) {
   LenClasses lc;
-  const float kscale = 63.0f / (float)((p.bound + 63) >> 6);
   lc.V = (B + 63) >> 6;
   int* const hist = scratch;
   int* const lens = scratch + 64;
@@ -42,15 +43,30 @@ __device__ __forceinline__ LenClasses build_len_classes(const DecodeParams& p, i
     if (v < lc.V) mine[v] = (idx < B) ? p.seq_lens[idx] : 0;
   }
   hist[lane] = 0;
+  // clamp, and the batch's longest sequence in 64-token units (a max over the lanes)
+  int nbmax = 0;
+#pragma unroll
+  for (int v = 0; v < kMaxRanked / 64; ++v) {
+    if (v < lc.V) {
+      mine[v] = (64 * v + lane < B) ? max(min(mine[v] + p.len_bias, p.bound), 0) : 0;
+      nbmax = max(nbmax, (mine[v] + 63) >> 6);
+    }
+  }
+  nbmax = max(nbmax, dpp_i0<0x121, 0xf>(nbmax));         // row_ror:1, 2, 4, 8: every lane of a row has the row's max
+  nbmax = max(nbmax, dpp_i0<0x122, 0xf>(nbmax));
+  nbmax = max(nbmax, dpp_i0<0x124, 0xf>(nbmax));
+  nbmax = max(nbmax, dpp_i0<0x128, 0xf>(nbmax));
+  nbmax = max(max(__builtin_amdgcn_readlane(nbmax, 0), __builtin_amdgcn_readlane(nbmax, 16)),
+              max(__builtin_amdgcn_readlane(nbmax, 32), __builtin_amdgcn_readlane(nbmax, 48)));
+  const float kscale = rank_scale(nbmax);
   wave_sync();
 #pragma unroll
   for (int v = 0; v < kMaxRanked / 64; ++v) {
     const int idx = 64 * v + lane;
     lc.cls[v] = -1;
     if (v < lc.V && idx < B) {
-      const int len = max(min(mine[v] + p.len_bias, p.bound), 0);
-      lens[idx] = len;
-      lc.cls[v] = len_class(len, kscale);
+      lens[idx] = mine[v];
+      lc.cls[v] = rank_class(mine[v], kscale);
       atomicAdd(&hist[lc.cls[v]], 1);
     }
   }

@@ -128,13 +128,14 @@ __global__ __launch_bounds__(256) void kv16_store_kernel(Kv16StoreParams p) {
 // the store kernel itself lives in saw_store_mfma.hip
 int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                       const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
-                      const int32_t* append_lens, hipStream_t st);
+                      const int32_t* append_lens, int32_t append_bound, hipStream_t st);
 
-// `slots` null: token t is appended to sequence t at position append_lens[t].
+// `slots` null: token t is appended to sequence t at position append_lens[t] (skipped when that
+// exceeds append_bound).
 int launch_store(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                  const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
-                 const int32_t* append_lens, hipStream_t st) {
-  return launch_store_mfma(c, K, V, dt, T, stride, pt, n_seqs, max_pages, slots, append_lens, st);
+                 const int32_t* append_lens, int32_t append_bound, hipStream_t st) {
+  return launch_store_mfma(c, K, V, dt, T, stride, pt, n_seqs, max_pages, slots, append_lens, append_bound, st);
 }
 
 int launch_dequant(const saw_cache_t* c, const int32_t* pt, int32_t max_pages, int32_t seq,

@@ -34,7 +34,8 @@ struct StoreMfmaParams {
   const void* in[2];
   const int32_t* page_table;
   const int32_t* slots;         // [T][2] (sequence, position), or null:
-  const int32_t* append_lens;   // then token t goes to sequence t at position append_lens[t]
+  const int32_t* append_lens;   // then token t goes to sequence t at position append_lens[t],
+  int32_t append_bound;         // unless that exceeds append_bound (the caller's bound on the lengths): skipped
   int64_t T;
   int64_t token_stride;
   int32_t n_seqs, max_pages, num_pages, n_kv_heads;
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   int2 slot = make_int2(-1, -1);
   if (wave_live && t_mine < p.T)
     slot = p.slots ? *(const int2*)(p.slots + 2 * t_mine) : make_int2((int)t_mine, p.append_lens[t_mine]);
+  if (!p.slots && slot.y > p.append_bound) slot = make_int2(-1, -1);
 
   // ---- the +/-1 matrix: A[m][k], m = output row, k = input channel (low five bits) ----
   // MFMA #1 row m -> output channel (low five bits) 8*(m/4) + m%4, MFMA #2 row m -> that + 4,
@@ -264,13 +266,13 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
 
 int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                       const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
-                      const int32_t* append_lens,
+                      const int32_t* append_lens, int32_t append_bound,
                       hipStream_t st) {
   StoreMfmaParams p;
   p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
   p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
   p.in[0] = K; p.in[1] = V;
-  p.page_table = pt; p.slots = slots; p.append_lens = append_lens; p.T = T; p.token_stride = stride;
+  p.page_table = pt; p.slots = slots; p.append_lens = append_lens; p.append_bound = append_bound; p.T = T; p.token_stride = stride;
   p.n_seqs = n_seqs; p.max_pages = max_pages; p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads;
   p.had_block = c->had_block;
   p.rot[0] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);

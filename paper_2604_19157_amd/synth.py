@@ -128,6 +128,10 @@ def make_workload(name: str, rep: int = 0, **over) -> Workload:
         seq_lens = np.asarray(over["seq_lens"], np.int32)
     pt, num_pages = _page_table(rng, seq_lens, P, over.get("extra_tokens", 16),
                                 over.get("slack_pages", 3), over.get("shuffle", True))
+    if over.get("table_width", 0) > pt.shape[1]:
+        # a page table wider than any sequence needs (a serving engine sizes it for the longest context it
+        # admits); the extra entries are never used and stay 0
+        pt = np.concatenate([pt, np.zeros((pt.shape[0], over["table_width"] - pt.shape[1]), np.int32)], axis=1)
     ks = _chan_scale(rng, kind, Hkv, d)
     vs = _chan_scale(rng, kind, Hkv, d)
     return Workload(name=name, seed=seed, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_size=P,

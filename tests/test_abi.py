@@ -139,3 +139,43 @@ def test_binding_fails_loudly_without_library(saw, monkeypatch):
     monkeypatch.setattr(saw, "LIB_PATH", "/nonexistent/libsaw.so")
     with pytest.raises(RuntimeError):
         saw.lib()
+
+
+def test_rank_order_never_puts_an_empty_sequence_ahead_of_a_non_empty_one(saw):
+    """Host mirror of the decode kernels' longest-first order.  The pair-mode blocks take the sequences at
+    ranks (r, B-1-r) or (r, 2n-1-r, 2n+r) and rely on: if a block's k-th sequence has no cached tokens,
+    neither have the later ones.  With classes scaled to the caller's bound a loose bound put empty and
+    short sequences into one class (ordered by index); the classes now follow the batch's own longest
+    sequence and keep the empty ones apart, whatever the bound."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    cases = [([0] + [256] * 255, 16384), ([0] + [2048] * 127, 131072), ([0] * 50 + [300] * 100, 0),
+             ([0, 65] * 90, 1 << 30), ([5, 0, 4096, 0, 64, 63, 65, 1], 0)]
+    for _ in range(20):
+        B = int(rng.integers(2, 700))
+        lens = rng.integers(0, int(rng.choice([3, 70, 5000])), size=B)
+        lens[rng.random(B) < 0.2] = 0
+        cases.append((lens.tolist(), int(rng.choice([0, int(lens.max()) + 1, 1 << 20]))))
+    for lens, bound in cases:
+        order = saw.decode_rank_order(lens, bound)
+        B = len(lens)
+        assert sorted(order) == list(range(B))
+        eff = [min(l, bound) if bound > 0 else l for l in lens]
+        ranked = [eff[b] for b in order]
+        nz = [i for i, l in enumerate(ranked) if l == 0]
+        assert nz == list(range(B - len(nz), B)), (lens[:8], bound)           # the empty ones are exactly the tail
+        # longest first at the granularity of the classes: a later sequence is never more than a class longer
+        nbmax = max(1, max((l + 63) // 64 for l in eff))
+        width = 64 * (nbmax / 63.0) + 64
+        assert all(ranked[i + 1] <= ranked[i] + width for i in range(B - 1))
+        # the blocks' precondition, for pairs and for triples
+        for r in range((B + 1) // 2):
+            a, b = ranked[r], ranked[B - 1 - r]
+            assert not (a == 0 and b > 0)
+        n3 = (B + 2) // 3
+        for r in range(n3):
+            ks = [ranked[k] for k in (r, 2 * n3 - 1 - r, 2 * n3 + r) if k < B]
+            assert all(not (ks[i] == 0 and ks[j] > 0) for i in range(len(ks)) for j in range(i + 1, len(ks)))
+        # the bound does not change the order as long as it clamps nothing
+        if bound == 0 or bound > max(lens):
+            assert order == saw.decode_rank_order(lens, max(lens) + 1 if max(lens) else 1)

@@ -36,8 +36,9 @@ def _new_tokens(w):
     return torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
 
 
-def _case(saw, w, out_dtype=torch.float32, unmapped=()):
-    """`unmapped`: sequences whose new token's page is taken out of the page table (attended, not stored)."""
+def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None):
+    """`unmapped`: sequences whose new token's page is taken out of the page table (attended, not stored).
+    `max_seq_len`: the host-side bound handed to the call (None: the longest sequence; 0: the default)."""
     B = w.batch
     ref = gc.oracle_fill(w)
     cache = gc.upload_cache(ref, w, saw)
@@ -50,7 +51,8 @@ def _case(saw, w, out_dtype=torch.float32, unmapped=()):
     q = synth.gen_q(w)
     out = torch.full((B, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
     before = gc.cache_to_numpy(cache, w)
-    saw.append_decode_attn(cache, Kn.cuda(), Vn.cuda(), q.cuda(), pt, lens, max_seq_len=int(w.seq_lens.max()), out=out)
+    saw.append_decode_attn(cache, Kn.cuda(), Vn.cuda(), q.cuda(), pt, lens,
+                           max_seq_len=int(w.seq_lens.max()) if max_seq_len is None else max_seq_len, out=out)
     torch.cuda.synchronize()
     assert torch.equal(lens.cpu(), torch.from_numpy(w.seq_lens))              # lengths are the caller's to advance
     got = gc.cache_to_numpy(cache, w)
@@ -163,3 +165,54 @@ def test_random_shapes(saw, seed):
     import test_gpu_decode as TD
     kw, _ = TD._random_case(seed)
     _case(saw, synth.make_workload("highconc", **kw))
+
+
+@pytest.mark.parametrize("bound", [0, 32000])
+@pytest.mark.parametrize("seed", range(100, 112))
+def test_random_shapes_loose_bound(saw, seed, bound):
+    """The same with a page table sized for 32768-token contexts and the bound at its default or loose."""
+    import test_gpu_decode as TD
+    kw, _ = TD._random_case(seed)
+    _case(saw, synth.make_workload("highconc", table_width=TD.LOOSE_WIDTH, **kw), max_seq_len=bound)
+
+
+@pytest.mark.parametrize("lens,width", [([0] + [256] * 255, 1024), ([0] + [2048] * 127, 8192),
+                                        ([0] * 50 + [300] * 100, 8192), ([0, 65] * 90, 2048),
+                                        ([0] * 3 + [40] * 200 + [0] * 2 + [7] * 51, 4096)])
+def test_empty_sequence_first_under_a_loose_bound(saw, lens, width):
+    """An empty sequence at a low index and a bound so loose that, ranked by the caller's bound, it would
+    share a length class with the non-empty ones and rank ahead of them: blocks of two wavefronts (2048
+    items), of four over pairs (1024 items) and of four over three sequences.  The ranking keeps empty
+    sequences in a class of their own, so the block's first sequence is never the empty one."""
+    _case(saw, synth.make_workload("highconc", batch=len(lens), seq_lens=lens, table_width=width), max_seq_len=0)
+
+
+def test_length_beyond_the_bound_is_not_stored(saw):
+    """seq_lens[b] > max_seq_len breaks the caller's promise: nothing is stored for that sequence (a store
+    at the clamped position would overwrite a cached token), the other sequences are unaffected, and its
+    own output row stays finite (the fused kernel attends over max_seq_len cached tokens plus the new one)."""
+    for kw in (dict(), dict(n_q_heads=6, n_kv_heads=3, head_dim=64, had_block=64)):      # fused kernel; store + decode launches
+        w = synth.make_workload("tiny", batch=3, seq_lens=[40, 100, 70], **kw)
+        ref = gc.oracle_fill(w)
+        cache = gc.upload_cache(ref, w, saw)
+        before = gc.cache_to_numpy(cache, w)
+        Kn, Vn = _new_tokens(w)
+        q = synth.gen_q(w)
+        bound = 70
+        out = saw.append_decode_attn(cache, Kn.cuda(), Vn.cuda(), q.cuda(), torch.from_numpy(w.page_table).cuda(),
+                                     torch.from_numpy(w.seq_lens).cuda(), max_seq_len=bound)
+        torch.cuda.synchronize()
+        got = gc.cache_to_numpy(cache, w)
+        # sequence 1 is over the bound: its pages are untouched; the oracle sees it as `bound` cached tokens + the new one
+        pages1 = w.page_table[1, :(100 + 16) // 16 + 1]
+        for k in ("k_codes", "v_codes", "k_meta", "v_meta"):
+            assert np.array_equal(got[k][pages1], before[k][pages1]), k
+        lens_ref = np.minimum(w.seq_lens, bound)
+        pt_ref = w.page_table.copy()
+        slots = np.stack([np.arange(3, dtype=np.int32), lens_ref.astype(np.int32)], 1)
+        O.rotate_quant_store(ref, Kn.float().numpy(), Vn.float().numpy(), pt_ref, slots, w.had_block, w.rotate_mask)
+        o_ref = O.paged_decode_attn(ref, q.float().numpy(), pt_ref, lens_ref + 1, w.had_block, w.rotate_mask)
+        assert torch.isfinite(out).all()
+        for b in (0, 2) if kw else (0, 1, 2):          # (the two-launch path attends over the clamped cached range only)
+            err = parity.attn_error(out[b:b + 1].cpu().numpy(), o_ref[b:b + 1])
+            assert err < 5e-2, (b, err)

@@ -19,9 +19,12 @@ def saw():
     return binding
 
 
-def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_dtype=None, end_to_end=True):
+def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_dtype=None, end_to_end=True,
+                 max_seq_len=None):
     """Criterion: both sides attend over the SAME bytes, the ones the oracle's store wrote (uploaded to
-    the device cache), so the decode kernel is compared with the oracle independently of the store."""
+    the device cache), so the decode kernel is compared with the oracle independently of the store.
+    `max_seq_len`: the host-side bound handed to the call (None: the longest sequence; 0: the call's
+    default, the page table's capacity)."""
     ref = gc.oracle_fill(w)
     cache = gc.upload_cache(ref, w, saw)
     pt = torch.from_numpy(w.page_table).cuda()
@@ -29,7 +32,8 @@ def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_
     if q_dtype is not None:
         q = q.to(q_dtype)
     sl = torch.from_numpy(w.seq_lens).cuda()
-    kw = dict(max_seq_len=int(w.seq_lens.max()), sm_scale=sm_scale, out_dtype=out_dtype, num_splits=num_splits)
+    kw = dict(max_seq_len=int(w.seq_lens.max()) if max_seq_len is None else max_seq_len, sm_scale=sm_scale,
+              out_dtype=out_dtype, num_splits=num_splits)
     # the output starts as NaN: a row the path never writes fails the comparison
     o = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
     saw.paged_decode_attn(cache, q.cuda(), pt, sl, out=o, **kw)
@@ -229,6 +233,33 @@ def test_random_shapes(saw, seed):
     kw, splits = _random_case(seed)
     w = synth.make_workload("highconc", **kw)
     _decode_case(saw, w, num_splits=splits, end_to_end=False)
+
+
+LOOSE_WIDTH = 2048          # page-table columns of a table sized for 32768-token contexts
+
+
+@pytest.mark.parametrize("bound", [0, 16 * LOOSE_WIDTH - 40])
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_loose_bound(saw, seed, bound):
+    """The same shapes as a serving engine calls them: a page table sized for long contexts and the host
+    bound left at its default (the table's capacity) or set loosely - no host read of the lengths.  The
+    length classes of the in-kernel ranking then have to come from the lengths themselves."""
+    kw, splits = _random_case(seed)
+    w = synth.make_workload("highconc", table_width=LOOSE_WIDTH, **kw)
+    _decode_case(saw, w, num_splits=splits, end_to_end=False, max_seq_len=bound)
+
+
+@pytest.mark.parametrize("lens,Hkv", [([0] + [256] * 255, 8), ([0] * 3 + [40] * 200 + [0] * 2 + [7] * 51, 8),
+                                      ([0] + [300] * 127, 8), ([0] * 5 + [70] * 120 + [0] * 3, 8),
+                                      ([0] * 50 + [300] * 100, 8), ([0, 65] * 90, 8), ([0] * 10 + [33] * 350, 8)])
+def test_empty_sequences_under_a_loose_bound(saw, lens, Hkv):
+    """Empty sequences that come first in index order, with a bound so loose that the caller's bound alone
+    would put them in one length class with everything else: pair blocks of two and of four, blocks over
+    three sequences, and the longest-first order."""
+    w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv,
+                            table_width=8192)
+    o, _ = _decode_case(saw, w, end_to_end=False, max_seq_len=0)
+    assert not o[np.asarray(lens) == 0].any()
 
 
 @pytest.mark.parametrize("lens", [[0] * 150, [1] * 150, [64] * 100 + [0] * 50, [200] * 3 + [1] * 147,
