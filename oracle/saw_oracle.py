@@ -24,6 +24,13 @@ What it follows (paper sections / equations, restated in code):
   randomised; the standard construction (a fixed +/-1 diagonal in front of the
   Hadamard matrix) is taken: ``R = diag(sigma) H_blk``, still orthonormal,
   ``R^-1 = R^T = H_blk diag(sigma)``.  ``signs=None`` is the plain matrix.
+* Learned per-layer rotation -- Sec. 3 ("Hessian-Aware Quantization") and
+  App. A.3, runtime application: a dense orthogonal ``d x d`` matrix ``R_l`` is
+  composed AFTER the block Hadamard, ``q^ = (q H_b) R_l``, ``k^ = (k H_b) R_l``,
+  and the same transform is applied to V; the output returns through the
+  transpose, ``o = o~ R_l^T H_b``.  ``dense=None`` leaves it out.  How ``R_l``
+  is calibrated (the damped eigendecomposition of App. A.3) is outside this
+  path: the matrix is an input.
 * Paged cache -- Sec. 2 ("Paged Memory Layouts"): fixed-size pages of one
   uniform type reached through a page table, token-wise metadata only.
 
@@ -46,7 +53,7 @@ import numpy as np
 
 __all__ = [
     "hadamard", "block_hadamard", "rotate", "quantize", "dequantize",
-    "pack_nibbles", "unpack_nibbles", "new_cache", "rotate_quant_store",
+    "pack_nibbles", "unpack_nibbles", "new_cache", "rotation_matrix", "unrotate", "rotates", "rotate_quant_store",
     "dequant_pages", "paged_decode_attn", "kv16_paged_decode_attn",
     "attention_plain",
 ]
@@ -96,22 +103,41 @@ def rotation_matrix(d: int, h: int, signs=None) -> np.ndarray:
     return R
 
 
-def rotate(x: np.ndarray, h: int, signs=None) -> np.ndarray:
-    """``x R`` along the last axis, dense mat-vec in fp64.  ``h == 1`` is the identity (signs ignored:
-    they are part of the rotation)."""
+def _dense(dense, d: int):
+    Rl = np.asarray(dense, np.float64)
+    if Rl.shape != (d, d):
+        raise ValueError("the learned rotation must be a d x d matrix")
+    return Rl
+
+
+def rotates(h: int, dense=None) -> bool:
+    """Whether a tensor whose rotate_mask bit is set is transformed at all: a Hadamard order above 1, or
+    a learned rotation (which may also be used alone, with ``h == 1``)."""
+    return h > 1 or dense is not None
+
+
+def rotate(x: np.ndarray, h: int, signs=None, dense=None) -> np.ndarray:
+    """``(x R) R_l`` along the last axis, dense mat-vecs in fp64, in the order App. A.3 prints: the
+    (signed) block Hadamard first, the learned rotation ``dense`` = ``R_l`` after it.  ``h == 1``
+    skips the Hadamard (signs ignored: they are part of it); ``dense=None`` skips ``R_l``."""
     x = np.asarray(x, dtype=np.float64)
-    if h == 1:
-        return x.copy()
-    return x @ rotation_matrix(x.shape[-1], h, signs)
+    y = x.copy() if h == 1 else x @ rotation_matrix(x.shape[-1], h, signs)
+    if dense is not None:
+        y = y @ _dense(dense, x.shape[-1])
+    return y
 
 
-def unrotate(y: np.ndarray, h: int, signs=None) -> np.ndarray:
-    """``y R^T`` along the last axis: the inverse of ``rotate`` (App. A.4: the transpose undoes an
-    orthonormal rotation; for the plain symmetric Hadamard this is the same matrix again)."""
+def unrotate(y: np.ndarray, h: int, signs=None, dense=None) -> np.ndarray:
+    """The inverse of ``rotate``: ``(y R_l^T) R^T`` (App. A.4: the transpose undoes an orthonormal
+    rotation; for the plain symmetric Hadamard alone this is the same matrix again)."""
     y = np.asarray(y, dtype=np.float64)
-    if h == 1:
-        return y.copy()
-    return y @ rotation_matrix(y.shape[-1], h, signs).T
+    x = y.copy() if dense is None else y @ _dense(dense, y.shape[-1]).T
+    if h > 1:
+        x = x @ rotation_matrix(y.shape[-1], h, signs).T
+    return x
+
+
+_inverse_rotation = unrotate      # (dequant_pages has a flag of the same name)
 
 
 # --------------------------------------------------------------------------
@@ -171,16 +197,17 @@ def new_cache(num_pages: int, n_kv_heads: int, page_size: int, head_dim: int) ->
     }
 
 
-def _encode(x: np.ndarray, h: int, rot: bool, signs=None):
-    y = rotate(x, h, signs) if rot else np.asarray(x, np.float64)
+def _encode(x: np.ndarray, h: int, rot: bool, signs=None, dense=None):
+    y = rotate(x, h, signs, dense) if rot else np.asarray(x, np.float64)
     codes, s, z = quantize(y)
     return pack_nibbles(codes), s, z, y
 
 
 def rotate_quant_store(cache: dict, K: np.ndarray, V: np.ndarray, page_table: np.ndarray,
                        slots: np.ndarray, had_block: int, rotate_mask: int = ROT_K | ROT_V,
-                       return_prerounding: bool = False, signs=None):
-    """Rotate, quantise and place ``T`` new tokens (Sec. 3 eq. 1-3 then App. A.1).
+                       return_prerounding: bool = False, signs=None, dense=None):
+    """Rotate, quantise and place ``T`` new tokens (Sec. 3 eq. 1-3 then App. A.1; with ``dense`` the
+    learned rotation of App. A.3 follows the Hadamard for every tensor whose mask bit is set).
 
     ``K, V``: ``[T][Hkv][d]`` (any float dtype, widened exactly to fp64).
     ``slots[t] = (sequence, logical position)``; the token lands in physical
@@ -193,8 +220,8 @@ def rotate_quant_store(cache: dict, K: np.ndarray, V: np.ndarray, page_table: np
     K = np.asarray(K, np.float64)
     V = np.asarray(V, np.float64)
     h = int(had_block)
-    kp, ks, kz, ky = _encode(K, h, bool(rotate_mask & ROT_K) and h > 1, signs)
-    vp, vs, vz, vy = _encode(V, h, bool(rotate_mask & ROT_V) and h > 1, signs)
+    kp, ks, kz, ky = _encode(K, h, bool(rotate_mask & ROT_K) and rotates(h, dense), signs, dense)
+    vp, vs, vz, vy = _encode(V, h, bool(rotate_mask & ROT_V) and rotates(h, dense), signs, dense)
     seq = slots[:, 0].astype(np.int64)
     pos = slots[:, 1].astype(np.int64)
     page = np.asarray(page_table)[seq, pos // P].astype(np.int64)
@@ -223,20 +250,21 @@ def _gather(cache: dict, which: str, page_table_row: np.ndarray, pos_begin: int,
 
 
 def dequant_pages(cache: dict, page_table: np.ndarray, seq: int, pos_begin: int, pos_end: int,
-                  had_block: int, rotate_mask: int = ROT_K | ROT_V, unrotate: bool = False, signs=None):
+                  had_block: int, rotate_mask: int = ROT_K | ROT_V, unrotate: bool = False, signs=None,
+                  dense=None):
     """Read back positions ``[pos_begin, pos_end)`` of one sequence as fp64 ``(K^, V^)``.
 
-    ``unrotate`` applies the inverse rotation ``R^T`` (App. A.4; for the plain
-    Hadamard, symmetric and orthonormal, that is the same matrix once more).
+    ``unrotate`` applies the inverse rotation (App. A.4; for the plain
+    Hadamard, symmetric and orthonormal, that is the same matrix once more;
+    with a learned rotation ``R_l^T`` first, then the Hadamard's transpose).
     """
     k = _gather(cache, "k", page_table[seq], pos_begin, pos_end)
     v = _gather(cache, "v", page_table[seq], pos_begin, pos_end)
-    if unrotate and had_block > 1:
-        Rt = rotation_matrix(cache["head_dim"], had_block, signs).T
+    if unrotate and rotates(had_block, dense):
         if rotate_mask & ROT_K:
-            k = k @ Rt
+            k = _inverse_rotation(k, had_block, signs, dense)
         if rotate_mask & ROT_V:
-            v = v @ Rt
+            v = _inverse_rotation(v, had_block, signs, dense)
     return k, v
 
 
@@ -251,12 +279,14 @@ def _softmax_rows(logits: np.ndarray) -> np.ndarray:
 
 def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_lens: np.ndarray,
                       had_block: int, rotate_mask: int = ROT_K | ROT_V,
-                      sm_scale: float | None = None, signs=None) -> np.ndarray:
+                      sm_scale: float | None = None, signs=None, dense=None) -> np.ndarray:
     """One decode step over the INT4 cache as stored: ``o = softmax(q~ K^^T / sqrt(d)) V^ [R^T]``.
 
     ``q``: ``[B][Hq][d]``.  ``q~ = q R`` when K is rotated, else ``q``; the
     result is multiplied by ``R^T`` when V is rotated (``R = diag(signs) H_blk``;
-    without signs ``R^T = R = H_blk``).  A sequence of length 0 gives a zero row.
+    without signs ``R^T = R = H_blk``; with a learned rotation ``dense`` = ``R_l``,
+    App. A.3: ``q~ = (q R) R_l`` and the result is multiplied by ``R_l^T`` and then
+    ``R^T``).  A sequence of length 0 gives a zero row.
     """
     q = np.asarray(q, np.float64)
     B, Hq, d = q.shape
@@ -264,9 +294,8 @@ def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_le
     G = Hq // Hkv
     h = int(had_block)
     scale = (1.0 / np.sqrt(np.float64(d))) if (sm_scale is None or sm_scale <= 0) else float(sm_scale)
-    rot_k = bool(rotate_mask & ROT_K) and h > 1
-    rot_v = bool(rotate_mask & ROT_V) and h > 1
-    Hb = rotation_matrix(d, h, signs) if (rot_k or rot_v) else None
+    rot_k = bool(rotate_mask & ROT_K) and rotates(h, dense)
+    rot_v = bool(rotate_mask & ROT_V) and rotates(h, dense)
     out = np.zeros((B, Hq, d), np.float64)
     for b in range(B):
         L = int(seq_lens[b])
@@ -276,11 +305,11 @@ def paged_decode_attn(cache: dict, q: np.ndarray, page_table: np.ndarray, seq_le
         vhat = _gather(cache, "v", page_table[b], 0, L)
         for g in range(Hkv):
             qg = q[b, g * G:(g + 1) * G, :]                # [G][d]
-            qt = qg @ Hb if rot_k else qg
+            qt = rotate(qg, h, signs, dense) if rot_k else qg
             logits = (qt @ khat[:, g, :].T) * scale        # [G][L]
             p = _softmax_rows(logits)
             o = p @ vhat[:, g, :]                          # [G][d]
-            out[b, g * G:(g + 1) * G, :] = o @ Hb.T if rot_v else o
+            out[b, g * G:(g + 1) * G, :] = unrotate(o, h, signs, dense) if rot_v else o
     return out
 
 

@@ -453,3 +453,124 @@ def test_signed_decode_attention_vs_dense_matrix_route(mask):
         sl = np.stack([np.full(L[b], b, np.int32), np.arange(L[b], dtype=np.int32)], 1)
         O.rotate_quant_store(ref_un, Ks[b], Vs[b], pt, sl, h, mask)
     assert np.array_equal(un["k_codes"], ref_un["k_codes"]) and np.array_equal(un["v_meta"], ref_un["v_meta"])
+
+
+# ---------------------------------------------------------------- learned per-layer rotation (App. A.3)
+def _orthogonal(d, seed):
+    """A seeded random orthogonal matrix (QR of a Gaussian matrix) standing in for a calibrated R_l."""
+    Q, Rr = np.linalg.qr(np.random.default_rng(seed).standard_normal((d, d)))
+    return Q * np.sign(np.diag(Rr))
+
+
+@pytest.mark.parametrize("d,h", [(16, 4), (64, 16), (128, 64), (128, 1)])
+def test_learned_rotation_composes_after_the_hadamard(d, h):
+    Rl = _orthogonal(d, 11 + h)
+    assert np.allclose(Rl @ Rl.T, np.eye(d), atol=1e-12)
+    Hb = scipy.linalg.block_diag(*[scipy.linalg.hadamard(h) / math.sqrt(h)] * (d // h)) if h > 1 else np.eye(d)
+    W = Hb @ Rl                                                   # q^ = (q H_b) R_l  =  q (H_b R_l)
+    assert np.allclose(W @ W.T, np.eye(d), atol=1e-12)
+    x = RNG.standard_normal((6, d))
+    y = RNG.standard_normal((6, d))
+    xr = O.rotate(x, h, None, Rl)
+    assert np.allclose(xr, x @ W, atol=1e-12)
+    if h > 1:
+        assert not np.allclose(xr, x @ (Rl @ Hb), atol=1e-3)      # the other order is a different transform
+        assert not np.allclose(xr, x @ (Hb @ Rl.T), atol=1e-3)    # and so is the transposed matrix
+    assert np.allclose(xr @ O.rotate(y, h, None, Rl).T, x @ y.T, atol=1e-11)          # q^ . k^ = q . k (App. A.3)
+    assert np.allclose(np.linalg.norm(xr, axis=-1), np.linalg.norm(x, axis=-1))
+    assert np.allclose(O.unrotate(xr, h, None, Rl), x, atol=1e-12)
+    # the identity as R_l is the Hadamard-only transform, bit for bit
+    assert np.array_equal(O.rotate(x, h, None, np.eye(d)), O.rotate(x, h))
+    # with signs: diag(sigma) H_b R_l
+    sg = _signs(d, 3)
+    if h > 1:
+        assert np.allclose(O.rotate(x, h, sg, Rl), ((x * sg) @ Hb) @ Rl, atol=1e-12)
+    else:                                                         # the signs belong to the Hadamard: none without it
+        assert np.array_equal(O.rotate(x, h, sg, Rl), O.rotate(x, h, None, Rl))
+
+
+def test_learned_rotation_permutation_moves_codes():
+    """With a permutation matrix as R_l the stored codes are the Hadamard-only codes with their channels
+    moved: y_j = (x H_b)_{pi(j)}.  The permutation is a cyclic shift (not its own inverse), so a
+    transposed operand or a wrong multiplication order shows."""
+    d, h, Hkv, T, P = 32, 16, 2, 20, 16
+    shift = 5
+    Pm = np.zeros((d, d))
+    for j in range(d):
+        Pm[(j + shift) % d, j] = 1.0                               # column j picks input channel j + shift
+    K = RNG.integers(-64, 64, size=(T, Hkv, d)).astype(np.float64) / 8.0
+    V = RNG.integers(-64, 64, size=(T, Hkv, d)).astype(np.float64) / 8.0
+    pt = np.array([[2, 0]], np.int32)
+    sl = np.stack([np.zeros(T, np.int32), np.arange(T, dtype=np.int32)], 1)
+    a = O.new_cache(3, Hkv, P, d)
+    b = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(a, K, V, pt, sl, h, O.ROT_K | O.ROT_V, dense=Pm)
+    O.rotate_quant_store(b, K, V, pt, sl, h, O.ROT_K | O.ROT_V)
+    for which in ("k", "v"):
+        ca = O.unpack_nibbles(a[which + "_codes"])
+        cb = O.unpack_nibbles(b[which + "_codes"])
+        assert np.array_equal(ca, np.roll(cb, -shift, axis=-1)), which
+        assert np.array_equal(a[which + "_meta"], b[which + "_meta"])          # same min, max: same (s, z)
+    # K-only: V is stored without any rotation
+    c = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(c, K, V, pt, sl, h, O.ROT_K, dense=Pm)
+    e = O.new_cache(3, Hkv, P, d)
+    O.rotate_quant_store(e, K, V, pt, sl, 1)
+    assert np.array_equal(c["v_codes"], e["v_codes"]) and np.array_equal(c["k_codes"], a["k_codes"])
+
+
+def test_learned_rotation_store_equals_plain_store_of_prerotated_input():
+    d, h, Hkv, T, P = 32, 8, 2, 20, 16
+    Rl = _orthogonal(d, 21)
+    Hb = scipy.linalg.block_diag(*[scipy.linalg.hadamard(h) / math.sqrt(h)] * (d // h))
+    K = RNG.standard_normal((T, Hkv, d))
+    V = RNG.standard_normal((T, Hkv, d))
+    pt = np.array([[1, 0]], np.int32)
+    sl = np.stack([np.zeros(T, np.int32), np.arange(T, dtype=np.int32)], 1)
+    a = O.new_cache(2, Hkv, P, d)
+    b = O.new_cache(2, Hkv, P, d)
+    O.rotate_quant_store(a, K, V, pt, sl, h, O.ROT_K | O.ROT_V, dense=Rl)
+    O.rotate_quant_store(b, (K @ Hb) @ Rl, (V @ Hb) @ Rl, pt, sl, 1)
+    for key in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        assert np.array_equal(a[key], b[key]), key
+    # read-back through the inverse returns to the input within the quantiser's bound
+    kq, _ = O.dequant_pages(a, pt, 0, 0, T, h, unrotate=True, dense=Rl)
+    s_k = a["k_meta"][[1] * 16 + [0] * 4, :, list(range(16)) + list(range(4)), 0].astype(np.float64)
+    assert np.all(np.linalg.norm(kq - K, axis=-1) <= 0.5 * s_k * math.sqrt(d) * (1 + 1e-6))
+
+
+@pytest.mark.parametrize("mask,h", [(3, 8), (1, 8), (2, 8), (3, 1)])
+def test_learned_rotation_decode_attention_three_routes(mask, h):
+    """Attention with (h, R_l) over a cache stored with (h, R_l) against (2) the brute-force loop over a
+    no-rotation cache of pre-rotated tokens with the query pre-rotated and the output multiplied by
+    (H_b R_l)^T here, and (3) the library SDPA on the cache read back in the original space."""
+    d, Hq, Hkv, P = 16, 4, 2, 16
+    Rl = _orthogonal(d, 31)
+    Hb = scipy.linalg.block_diag(*[scipy.linalg.hadamard(h) / math.sqrt(h)] * (d // h)) if h > 1 else np.eye(d)
+    W = Hb @ Rl
+    L = np.array([7, 21], np.int32)
+    pt = np.array([[3, 1], [0, 2]], np.int32)
+    cache = O.new_cache(4, Hkv, P, d)
+    plain = O.new_cache(4, Hkv, P, d)
+    for b in range(2):
+        K = RNG.standard_normal((L[b], Hkv, d))
+        V = RNG.standard_normal((L[b], Hkv, d))
+        sl = np.stack([np.full(L[b], b, np.int32), np.arange(L[b], dtype=np.int32)], 1)
+        O.rotate_quant_store(cache, K, V, pt, sl, h, mask, dense=Rl)
+        O.rotate_quant_store(plain, (K @ Hb) @ Rl if mask & 1 else K, (V @ Hb) @ Rl if mask & 2 else V, pt, sl, 1)
+    for key in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        assert np.array_equal(cache[key], plain[key]), key
+    q = RNG.standard_normal((2, Hq, d))
+    o = O.paged_decode_attn(cache, q, pt, L, h, mask, dense=Rl)
+    o2 = _brute_force(plain, q @ W if mask & 1 else q, pt, L, 1, 0)
+    if mask & 2:
+        o2 = o2 @ W.T
+    assert np.allclose(o, o2, rtol=0, atol=1e-12)
+    for b in range(2):
+        kq, vq = O.dequant_pages(cache, pt, b, 0, int(L[b]), h, mask, unrotate=True, dense=Rl)
+        for j in range(Hq):
+            g = j // (Hq // Hkv)
+            ref = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(q[b, j][None, None]), torch.from_numpy(kq[:, g][None]),
+                torch.from_numpy(vq[:, g][None])).numpy()[0, 0]
+            assert np.allclose(o[b, j], ref, atol=1e-10)
