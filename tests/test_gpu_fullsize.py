@@ -1,11 +1,10 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times (automatic split
-choice, bf16 inputs, fp32 or bf16 output): the whole workload runs through the HIP path, and the oracle
-computes the sequences of a seeded sample one by one.
-
-The sampled sequences' cache pages hold the bytes the oracle's store wrote (uploaded), so the decode
-comparison is over identical bytes; every other sequence is stored by the HIP store from device-generated
-synthetic K/V and is checked through properties that hold at any size (finite output, a convex combination
-of cached vectors cannot be longer than the longest of them).
+choice, bf16 inputs, fp32 or bf16 output): the whole workload runs through the HIP path and EVERY sequence
+is compared with the oracle, over cache bytes the oracle's store wrote (uploaded), so that both sides
+attend over identical bytes.  The call bench.py times as its step, saw_append_decode_attn on the ragged
+256-sequence batch, is compared the same way: every sequence's output and every appended token's codes.
+Properties that hold at any size (finite output, a convex combination of cached vectors cannot be longer
+than the longest of them, bit-identical repeats) are checked as well.
 """
 import numpy as np
 import pytest
@@ -57,21 +56,22 @@ def _sample(w, n):
 
 
 @pytest.mark.parametrize("name,n_sample,out_dtype,over", [
-    ("highconc", 6, torch.bfloat16, {}),  # the headline configuration: 256 ragged sequences, bf16 in and out
-    ("highconc", 6, torch.float32, {}),
-    ("llama8b", 3, torch.float32, {}),
-    ("longctx4", 1, torch.float32, {}),
-    ("longctx1", 1, torch.float32, {}),
+    ("highconc", None, torch.bfloat16, {}),  # the headline configuration: 256 ragged sequences, bf16 in and out
+    ("highconc", None, torch.float32, {}),
+    ("llama8b", None, torch.float32, {}),
+    ("longctx4", None, torch.float32, {}),
+    ("longctx1", None, torch.float32, {}),
     # the other figures bench.py reports: 1024 items (four-wavefront pair blocks), and head_dim 64 (pairs of
-    # kv heads per block) with 8 and with 32 kv heads
-    ("highconc", 4, torch.float32, dict(n_q_heads=16, n_kv_heads=4)),
-    ("highconc", 4, torch.float32, dict(head_dim=64, had_block=64)),
-    ("highconc", 3, torch.float32, dict(head_dim=64, had_block=64, n_kv_heads=32)),
+    # kv heads per block) with 8 and with 32 kv heads (the last one sampled: 4096 items, longest first)
+    ("highconc", None, torch.float32, dict(n_q_heads=16, n_kv_heads=4)),
+    ("highconc", None, torch.float32, dict(head_dim=64, had_block=64)),
+    ("highconc", 6, torch.float32, dict(head_dim=64, had_block=64, n_kv_heads=32)),
 ])
-def test_decode_full_size_sampled(saw, name, n_sample, out_dtype, over):
+def test_decode_full_size(saw, name, n_sample, out_dtype, over):
+    """`n_sample` None: every sequence of the workload is compared with the oracle."""
     w = synth.make_workload(name, **over)
-    seqs = _sample(w, n_sample)
-    print(f"[{name}] B={w.batch} tokens={w.total_tokens} sampled sequences {seqs}", flush=True)
+    seqs = list(range(w.batch)) if n_sample is None else _sample(w, n_sample)
+    print(f"[{name}] B={w.batch} tokens={w.total_tokens} compared sequences: {len(seqs)} of {w.batch}", flush=True)
     ref = gc.oracle_fill(w, chunk=8192, seqs=seqs)
     cache, pt = _fill_device(w, saw, skip=set(seqs))
     gc.upload_cache(ref, w, saw, into=cache, pages=_pages_of(w, seqs))
@@ -87,16 +87,17 @@ def test_decode_full_size_sampled(saw, name, n_sample, out_dtype, over):
     o = o.float().cpu().numpy()
     assert np.isfinite(o).all()
     plan = saw.decode_plan(cache, w.batch, int(w.seq_lens.max()))
-    # sampled sequences against the oracle, one by one
-    worst = 0.0
+    # the compared sequences against the oracle, one by one (error relative to the sequence's own largest value)
+    worst, worst_b = 0.0, -1
     for b in seqs:
         o_ref = O.paged_decode_attn(ref, q[b:b + 1].float().numpy(), w.page_table[b:b + 1], w.seq_lens[b:b + 1],
                                     w.had_block, w.rotate_mask)
         err = parity.attn_error(o[b:b + 1], o_ref)
-        worst = max(worst, err)
-        print(f"  seq {b} len {int(w.seq_lens[b])}: err={err:.2e}", flush=True)
+        if err > worst:
+            worst, worst_b = err, b
+    print(f"  worst: seq {worst_b} len {int(w.seq_lens[worst_b])}: err={worst:.2e}", flush=True)
     tol = TOL if out_dtype == torch.float32 else TOL + 2.0 ** -8
-    assert worst < tol, f"{name}: plan={plan} worst sampled error {worst:.2e}"
+    assert worst < tol, f"{name}: plan={plan} worst error {worst:.2e} (sequence {worst_b})"
     # every sequence: the output is a convex combination of dequantised V rows (un-rotated by an
     # orthonormal matrix), so its norm cannot exceed the largest row norm; sqrt(d) * max|s (c - z)| <=
     # sqrt(d) * 15 * max scale bounds that without dequantising the cache.
@@ -104,6 +105,19 @@ def test_decode_full_size_sampled(saw, name, n_sample, out_dtype, over):
     assert np.linalg.norm(o, axis=-1).max() <= vmax * 1.01
     nonempty = w.seq_lens > 0
     assert (np.abs(o[nonempty]).max(axis=(1, 2)) > 0).all()
+
+
+@pytest.mark.parametrize("name,over", [("highconc", {}), ("llama8b", {}),
+                                       ("highconc", dict(head_dim=64, had_block=64))])
+def test_append_decode_full_size(saw, name, over):
+    """The step bench.py times: saw_append_decode_attn on the whole workload in the bench's launch shape
+    (bf16 K/V/q, fp32 output, the bound at the longest sequence).  Every sequence's output against the oracle
+    (2e-3; a sequence whose new token took a code the boundary rule exempts: the loose composed bound), every
+    appended token's codes and metadata under the store criterion, nothing else in the cache changed."""
+    import test_gpu_append as TA
+    w = synth.make_workload(name, **over)
+    print(f"[{name} {over}] B={w.batch} tokens={w.total_tokens}", flush=True)
+    TA._case(saw, w)
 
 
 @pytest.mark.parametrize("name", ["prefill", "prefill_mha"])
