@@ -65,6 +65,10 @@ extern "C" {
 #define SAW_ENULL      -2   /* a required pointer is NULL                               */
 #define SAW_EWORKSPACE -3   /* workspace smaller than saw_decode_workspace_bytes(...)   */
 #define SAW_ELAUNCH    -4   /* the HIP runtime refused the launch                       */
+#define SAW_ESCRATCH   -5   /* saw_paged_decode_attn_static: the call needs more than SAW_STATIC_SCRATCH_BYTES */
+
+/* size of the per-GPU scratch array behind saw_paged_decode_attn_static */
+#define SAW_STATIC_SCRATCH_BYTES (16u << 20)
 
 typedef void* saw_stream_t;
 
@@ -164,6 +168,28 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
                           void* out, int32_t out_dtype,
                           void* workspace, size_t workspace_bytes, int32_t num_splits,
                           saw_stream_t stream);
+
+/*
+ * saw_paged_decode_attn without a workspace argument, for callers that cannot allocate device
+ * memory or carry a workspace around: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same kernels, same arguments and same results as saw_paged_decode_attn;
+ * the split-KV partial results live in a static device array of SAW_STATIC_SCRATCH_BYTES (16 MiB)
+ * that every GPU the library runs on holds until the process ends.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine); its first use on a device resolves the
+ * array's address there (hipGetSymbolAddress), so make that first call outside a graph capture.
+ *   - A call whose partial results ([B][n_q_heads][splits][head_dim + 2] float32, see
+ *     saw_decode_workspace_bytes / saw_decode_plan) exceed the array returns SAW_ESCRATCH and
+ *     launches nothing; a smaller num_splits (1 needs 520 B per query row) makes it fit.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it.  Nothing in it has to start at zero and nothing is kept
+ *     from one call to the next.
+ */
+int saw_paged_decode_attn_static(const saw_cache_t* cache, const void* q, int32_t q_dtype,
+                                 int32_t B, int32_t n_q_heads,
+                                 const int32_t* page_table, int32_t max_pages_per_seq,
+                                 const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                                 void* out, int32_t out_dtype, int32_t num_splits,
+                                 saw_stream_t stream);
 
 /*
  * One whole decode step for a layer in a single call: append this step's K/V token of every

@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
         L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.saw_decode_rank_order.argtypes = [ctypes.POINTER(i32), i32, i32, ctypes.POINTER(i32)]
         L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
+        L.saw_paged_decode_attn_static.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, i32, vp]
         L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.saw_append_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, vp]
         L.saw_flatten_dequant.argtypes = [cp, vp, i32, i32, i32, i32, i32, i32, vp, vp, ctypes.c_int64, vp]
@@ -160,6 +161,19 @@ def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_s
                                        page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
                                        _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
                                        num_splits, _stream()), "saw_paged_decode_attn")
+    return out
+
+
+def paged_decode_attn_static(cache: Cache, q, page_table, seq_lens, out, max_seq_len=0, sm_scale=0.0, num_splits=0):
+    """saw_paged_decode_attn_static: the no-allocation variant (library-held scratch); `out` is the caller's."""
+    B, Hq, d = q.shape
+    assert q.is_contiguous() and page_table.is_contiguous() and seq_lens.dtype == torch.int32
+    assert out.shape == (B, Hq, d) and out.is_contiguous()
+    st = cache.struct()
+    _check(lib().saw_paged_decode_attn_static(ctypes.byref(st), _ptr(q), _DT[q.dtype], B, Hq, _ptr(page_table),
+                                              page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
+                                              _ptr(out), _DT[out.dtype], num_splits, _stream()),
+           "saw_paged_decode_attn_static")
     return out
 
 

@@ -2,7 +2,14 @@
 // caller's stream.  No allocation, no synchronisation, no global state.
 #include <math.h>
 
+#include <mutex>
+
 #include "saw_decode.h"
+
+// Split-KV scratch of saw_paged_decode_attn_static, the entry point for callers that cannot
+// allocate: one array per GPU the library runs on, held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[SAW_STATIC_SCRATCH_BYTES];
 
 namespace saw {
 
@@ -97,6 +104,7 @@ const char* saw_strerror(int code) {
     case SAW_ENULL: return "null pointer";
     case SAW_EWORKSPACE: return "workspace too small";
     case SAW_ELAUNCH: return "kernel launch failed";
+    case SAW_ESCRATCH: return "the split-KV partial results of this call exceed the static scratch of the no-allocation entry point";
     default: return "unknown error";
   }
 }
@@ -206,6 +214,44 @@ int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, 
   return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
                        max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
                        workspace_bytes, num_splits, stream);
+}
+
+// The device address of `scratch` on the current device, resolved once per device with that device
+// current (every GPU holds its own copy of the array at its own address).
+static int static_scratch_ptr(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptrs[kMaxDevices] = {nullptr};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SAW_ELAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SAW_ELAUNCH;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return SAW_OK;
+}
+
+int saw_paged_decode_attn_static(const saw_cache_t* c, const void* q, int32_t q_dtype, int32_t B,
+                                 int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                                 const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                                 int32_t out_dtype, int32_t num_splits, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || B < 1 || n_q_heads < 1 || max_pages_per_seq < 1) return SAW_EINVAL;
+  // the scratch the plan needs, before anything else: too large is an error of its own
+  SplitPlan plan;
+  if (!make_plan(c, B, max_pages_per_seq, max_seq_len, num_splits, false, &plan)) return SAW_EINVAL;
+  if (partial_bytes(B, n_q_heads, plan.num_splits, c->head_dim) > (size_t)SAW_STATIC_SCRATCH_BYTES) return SAW_ESCRATCH;
+  void* ws = nullptr;
+  const int rc = static_scratch_ptr(&ws);
+  if (rc != SAW_OK) return rc;
+  // (nothing in the scratch has to start at zero: every partial record the merge pass reads was
+  // written by the decode pass of the same call)
+  return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
+                       max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, ws,
+                       (size_t)SAW_STATIC_SCRATCH_BYTES, num_splits, stream);
 }
 
 int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
