@@ -162,6 +162,8 @@ def cpu_baseline(w, budget_s=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": nbytes / spent / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "implementation": f"numpy fp64 (explicit matrices, two-pass softmax); its matrix products run on the BLAS "
+                              f"pool, {int(cores)} threads; everything else is single-threaded",
             "sample": f"oracle store + decode of the first {n_seq} sequences ({tokens} tokens) of the workload, "
                       f"{spent:.1f} s of oracle time; bytes = same algorithmic bytes as the GPU figure"}
 
@@ -187,27 +189,46 @@ def store_sweep(saw, dev, iters=30, warmup=5, same_buffers=True):
         # variants: every block size, plus the largest one with a random +/-1 diagonal in front of the
         # Hadamard matrix (randomised Hadamard, Sec. 3); all timed in turn (plain, 16, 32, ..., plain, 16, ...),
         # each call on the next buffer set
+        # also: K-only rotation (the serving default of App. D: V stored as plain INT4), a learned per-layer
+        # rotation after the Hadamard (App. A.3, a seeded random orthogonal matrix standing in for it), and - as
+        # the leanest possible plain INT4 store - a vector-ALU kernel without matrix cores or LDS staging
         hmax = min(128, base.head_dim)
-        variants = [(f"h{h}", h, None) for h in (1, 16, 32, 64, 128) if h <= base.head_dim]
-        variants.append((f"h{hmax}_signs", hmax, synth.random_signs(base.head_dim, 1)))
+        variants = [(f"h{h}", h, None, 3, None) for h in (1, 16, 32, 64, 128) if h <= base.head_dim]
+        variants.append((f"h{hmax}_signs", hmax, synth.random_signs(base.head_dim, 1), 3, None))
+        variants.append((f"h{hmax}_k_only", hmax, None, 1, None))
+        if base.head_dim == 128:
+            variants.append(("h128_learned", 128, None, 3, synth.random_orthogonal(128, 2)))
+            variants.append(("h1_valu", 1, None, 3, None))
         for h in (1, 16, 32, 64, 128):
             if h > base.head_dim:
                 res[f"h{h}"] = None
-        caches = {key: [saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, 3, device=dev, signs=sg)
-                        for _ in range(SWEEP_SETS)] for key, h, sg in variants}
+        dense_bufs = {key: saw.prepare_dense_rotation(dn, base.head_dim, dev) for key, _, _, _, dn in variants if dn is not None}
+
+        def new_cache(key, h, sg, mask):
+            c = saw.Cache(base.num_pages, base.n_kv_heads, base.head_dim, h, mask, device=dev, signs=sg)
+            c.dense_rot = dense_bufs.get(key)
+            return c
+
+        caches = {key: [new_cache(key, h, sg, mask) for _ in range(SWEEP_SETS)] for key, h, sg, mask, _ in variants}
+        store_fn = lambda key: saw.plain_quant_store_valu if key == "h1_valu" else saw.rotate_quant_store
+
         def make_call(key):
             turn = [0]                                          # every variant walks all its buffer sets
 
             def call():
                 i = turn[0] % SWEEP_SETS
                 turn[0] += 1
-                saw.rotate_quant_store(caches[key][i], Ks[i], Vs[i], pt, sl)
+                store_fn(key)(caches[key][i], Ks[i], Vs[i], pt, sl)
             return call
 
-        meds = time_interleaved([make_call(key) for key, _, _ in variants], iters, warmup)
-        sames = (time_interleaved([(lambda key=key: saw.rotate_quant_store(caches[key][0], K, V, pt, sl)) for key, _, _ in variants],
+        meds = time_interleaved([make_call(v[0]) for v in variants], iters, warmup)
+        sames = (time_interleaved([(lambda key=v[0]: store_fn(key)(caches[key][0], K, V, pt, sl)) for v in variants],
                                   iters, warmup) if same_buffers else [None] * len(variants))
-        for (key, h, sg), med, same in zip(variants, meds, sames):
+        for (key, h, sg, mask, dn), med, same in zip(variants, meds, sames):
+            if dn is not None:                                  # (the flatten call does not rotate a learned rotation back)
+                res[key] = {"us": round(med, 2), "us_same_buffers": None if same is None else round(same, 2),
+                            "Gtok_s": round(T / med / 1e3, 4), "GB_s": round(store_bytes(base, T) / med / 1e3, 1), "k_mse": None}
+                continue
             # sanity column: quantisation error of K against the unquantised input (read back, rotated back)
             kq, _ = saw.flatten_dequant(caches[key][0], pt, 0, 0, T, unrotate=True, out_dtype=torch.float32, want_v=False)
             mse = float(((kq - K.float()) ** 2).mean())
@@ -218,7 +239,9 @@ def store_sweep(saw, dev, iters=30, warmup=5, same_buffers=True):
         plain = res["h1"]["us"]
         for k, v in res.items():
             if v is not None:
-                v["vs_plain"] = round(v["us"] / plain, 4)
+                v["vs_plain"] = round(v["us"] / plain, 4)                   # plain = this kernel with an identity matrix
+                if "h1_valu" in res:
+                    v["vs_plain_valu"] = round(v["us"] / res["h1_valu"]["us"], 4)   # plain = the lean vector-ALU store
         out[name] = res
         del Ks, Vs
     return out
@@ -344,6 +367,48 @@ def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, with_appen
     else:
         r["kv16_decode"] = res16
     return r
+
+
+def read_ceiling(saw, dev, w, cache, iters=30):
+    """Read-only streaming ceiling of this machine for the decode kernel's access pattern: saw_read_probe walks the
+    workload's pages (every sequence's pages in order, i.e. shuffled over the pool) and, for comparison, the
+    same number of pages in address order.  GB/s of bytes read."""
+    P = w.page_size
+    ids = np.concatenate([w.page_table[b, :(int(w.seq_lens[b]) + P - 1) // P] for b in range(w.batch)]).astype(np.int32)
+    shuffled = torch.from_numpy(ids).to(dev)
+    ordered = torch.arange(len(ids), dtype=torch.int32, device=dev)
+    sink = torch.empty(2048, dtype=torch.int32, device=dev)
+    out = {}
+    for key, pages in (("decode_pattern", shuffled), ("contiguous", ordered)):
+        nbytes = saw.read_probe(cache, pages, sink)
+        med = time_calls(lambda: saw.read_probe(cache, pages, sink), iters, 5)[0]
+        out[key] = {"us": round(med, 2), "GB_s": round(nbytes / med / 1e3, 1), "pct_of_hbm_peak": round(nbytes / med / 1e3 / HBM_PEAK_GBS * 100, 2)}
+    out["what"] = ("saw_read_probe: 2048 single-wavefront blocks reading the cache's K/V code tiles (1 KiB pieces) and "
+                   "(scale, zero) pairs of the workload's pages, one 9 KiB batch ahead, nothing else")
+    return out
+
+
+def layers_store(saw, dev, n_layers=32, iters=50):
+    """The decode step's KV write for a whole model: 16 new tokens (llama8b shape) for n_layers layers as one
+    saw_rotate_quant_store_layers launch against n_layers saw_rotate_quant_store launches."""
+    w = synth.make_workload("llama8b")
+    caches = [saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, device=dev) for _ in range(n_layers)]
+    Ks = [torch.cat([synth.gen_kv(w, b + 100 * l, 4096, 4097, device=dev)[0] for b in range(w.batch)]) for l in range(n_layers)]
+    Vs = [torch.cat([synth.gen_kv(w, b + 100 * l, 4096, 4097, device=dev)[1] for b in range(w.batch)]) for l in range(n_layers)]
+    pt = torch.from_numpy(w.page_table).to(dev)
+    sl = torch.from_numpy(np.stack([np.arange(w.batch, dtype=np.int32), np.full(w.batch, 4096, np.int32)], 1)).to(dev)
+
+    def one_launch():
+        saw.rotate_quant_store_layers(caches, Ks, Vs, pt, sl)
+
+    def per_layer():
+        for c, K, V in zip(caches, Ks, Vs):
+            saw.rotate_quant_store(c, K, V, pt, sl)
+
+    a = time_calls(one_launch, iters, 5)[0]
+    b = time_calls(per_layer, iters, 5)[0]
+    return {"layers": n_layers, "tokens_per_layer": w.batch, "one_launch_us": round(a, 2), "one_launch_us_per_layer": round(a / n_layers, 3),
+            "per_layer_launches_us": round(b, 2), "per_layer_launches_us_per_layer": round(b / n_layers, 3)}
 
 
 def copy_ceiling(dev, nbytes=1 << 30, iters=10):
@@ -542,6 +607,21 @@ def main():
                                      "batch); at equal bandwidth the speed-up would equal bytes_ratio"}
         del kv16, ws16
         torch.cuda.empty_cache()
+        # what this machine's memory system delivers to a kernel that only reads, in the decode kernel's pattern
+        rc = read_ceiling(saw, dev, w, cache)
+        rc["decode_pct_of_read_ceiling"] = round(achieved / rc["decode_pattern"]["GB_s"] * 100, 2)
+        rc["decode_only_pct_of_read_ceiling"] = round(dbytes / med_d / 1e3 / rc["decode_pattern"]["GB_s"] * 100, 2)
+        ex["box_read_ceiling"] = rc
+        # K-only rotation (the serving default of App. D): V is stored as plain INT4 and the output is not rotated back
+        ck = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, 1, device=dev)
+        fill(w, saw, dev, ck)
+        kd, kf = time_interleaved([lambda: saw.paged_decode_attn(ck, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws),
+                                   lambda: saw.append_decode_attn(ck, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0, out=out, workspace=ws)],
+                                  50, 5)
+        ex["k_only_rotation"] = {"decode_only_us": round(kd, 2), "fused_step_us": round(kf, 2),
+                                 "decode_only_vs_k_and_v": round(kd / med_d, 4)}
+        del ck
+        torch.cuda.empty_cache()
         ex["prefill_store_sweep"] = store_sweep(saw, dev)
         ex["prefill_flatten_sweep"] = flatten_sweep(saw, dev)
         del cache
@@ -559,6 +639,7 @@ def main():
         med, mean, p10, p90 = time_calls(lambda: saw.rotate_quant_store(c2, K2, V2, pt2, sl2), 50, 5)
         ex["llama8b_store_16_new_tokens_us"] = round(med, 2)          # launch-latency dominated
         del c2
+        ex["llama8b_store_32_layers"] = layers_store(saw, dev)
         ex["other_decode"] = {
             # equal lengths: neither kernel needs balancing, so the 16-bit comparison isolates the format
             "highconc_uniform2304": other_decode(saw, dev, "highconc", ctx=2304, with_kv16=True),
@@ -569,6 +650,9 @@ def main():
             "highconc_4kv_heads": other_decode(saw, dev, "highconc", n_q_heads=16, n_kv_heads=4),
             # head_dim 64 (two kv heads per block as one 128-channel row), Llama-3.2-1B-like heads
             "highconc_head_dim64": other_decode(saw, dev, "highconc", head_dim=64, had_block=64, with_append=True),
+            # mid-size ragged batch (384 items: partitions + merge) and equal lengths just above 2048 items
+            "highconc_48_sequences": other_decode(saw, dev, "highconc", batch=48),
+            "highconc_260_equal2304": other_decode(saw, dev, "highconc", batch=260, ctx=2304),
         }
         u = ex["other_decode"]["highconc_uniform2304"]["kv16_decode"]
         ex["int4_vs_16bit_decode"] = {

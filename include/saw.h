@@ -87,10 +87,31 @@ typedef struct saw_cache {
                             negated before the block Hadamard, i.e. R = diag(sigma) H_blk; every rotated
                             tensor uses R, the query R as well, outputs and read-backs R^T.  All zero = the
                             plain Hadamard.  Bits at or above head_dim must be zero (SAW_EINVAL). */
+  const void* dense_rot; /* learned per-layer rotation R_l (Sec. 3 "Hessian-Aware Quantization", App. A.3): a
+                            device buffer filled by saw_prepare_dense_rotation, or NULL for none.  Every tensor
+                            whose rotate_mask bit is set is then stored as ((x diag(sigma)) H_blk) R_l (with
+                            had_block 1: x R_l), the query takes the same transform and outputs / read-backs its
+                            transpose R_l^T first, then the Hadamard's.  head_dim 128 only (SAW_EINVAL otherwise). */
 } saw_cache_t;
 
 int saw_version(void);
 const char* saw_strerror(int code);
+
+/*
+ * Learned per-layer rotation (App. A.3, runtime application: q^ = (q H_b) R_l, k^ = (k H_b) R_l, the same
+ * for V).  The calibration that produces R_l is not part of this library: the caller supplies the
+ * orthogonal matrix.  saw_prepare_dense_rotation turns it, once per layer, into the operand layouts the
+ * kernels read (R_l and its transpose in fp32 for the query / output / read-back products, and three
+ * bf16 limbs of R_l in matrix-core operand order for the store kernel, whose product is accurate to
+ * fp32 so that the stored codes still follow the rounding-boundary rule):
+ *   R         device, [head_dim][head_dim] float32 row-major, y = x R (x a row vector); 16-byte aligned.
+ *   prepared  device, at least saw_dense_rotation_bytes(head_dim) bytes, 16-byte aligned; this pointer goes
+ *             into saw_cache_t.dense_rot and must stay valid while the cache is used.
+ * saw_dense_rotation_bytes returns 0 for an unsupported head_dim (only 128 is supported).
+ */
+size_t saw_dense_rotation_bytes(int32_t head_dim);
+int saw_prepare_dense_rotation(const float* R, int32_t head_dim, void* prepared, size_t prepared_bytes,
+                               saw_stream_t stream);
 
 /*
  * Fused rotate -> quantise -> pack -> paged store (Sec. 3 eqs. 1-3, App. A.1, App. A.4).
@@ -116,6 +137,25 @@ int saw_rotate_quant_store(const saw_cache_t* cache, const void* K, const void* 
                            int32_t in_dtype, int64_t T, int64_t token_stride_elems,
                            const int32_t* page_table, int32_t n_seqs, int32_t max_pages_per_seq,
                            const int32_t* slots, saw_stream_t stream);
+
+/*
+ * The same store for several layers in ONE kernel launch (App. B: at decode the per-layer KV write is a few
+ * microseconds of launch latency, not bandwidth; a caller that has several layers' new K/V at hand - a
+ * prefill chunk, a draft model's burst, a cache import - pays that latency once per SAW_MAX_STORE_LAYERS
+ * layers instead of once per layer).  Results are those of n_layers calls of saw_rotate_quant_store.
+ *
+ *   caches      HOST array of n_layers descriptors.  The layers share page_table and slots and must agree in
+ *               num_pages, n_kv_heads, page_size, head_dim, had_block, rotate_mask and sign_bits (SAW_EINVAL
+ *               otherwise); the pools and the learned rotation (all layers with one, or none) are per layer.
+ *   K, V        HOST arrays of n_layers device pointers, each as in saw_rotate_quant_store, with one
+ *               token_stride_elems for all.
+ * Any n_layers >= 1; more than SAW_MAX_STORE_LAYERS layers go out as several launches.
+ */
+#define SAW_MAX_STORE_LAYERS 32
+int saw_rotate_quant_store_layers(const saw_cache_t* caches, const void* const* K, const void* const* V,
+                                  int32_t n_layers, int32_t in_dtype, int64_t T, int64_t token_stride_elems,
+                                  const int32_t* page_table, int32_t n_seqs, int32_t max_pages_per_seq,
+                                  const int32_t* slots, saw_stream_t stream);
 
 /*
  * Bytes of scratch the decode calls need for these arguments (split-KV partial
@@ -245,7 +285,9 @@ int saw_dequant_pages(const saw_cache_t* cache, const int32_t* page_table,
  *   k_out, v_out  device, [pos_end - pos_begin][n_kv_heads][head_dim] of out_dtype
  *                 (SAW_BF16 | SAW_F16 | SAW_F32), 16-byte aligned, token_stride_elems elements
  *                 between tokens (>= n_kv_heads*head_dim, multiple of 8).  Either may be NULL.
- *   Positions whose page-table entry is outside [0, num_pages) are left unwritten.
+ *   Positions whose page-table entry is outside [0, num_pages) are left unwritten.  A cache with a learned
+ *   rotation (dense_rot) can be flattened as stored (unrotate == 0) only: rotating back is SAW_EINVAL here
+ *   (saw_dequant_pages does it).
  * pos_end == pos_begin is a no-op.  Errors: SAW_EINVAL for a bad range (negative, reversed,
  * beyond max_pages_per_seq * page_size), dtype, stride or alignment; SAW_ENULL for a null
  * cache / page table.
@@ -273,6 +315,29 @@ int saw_kv16_paged_decode_attn(const saw_cache_t* shape, const void* k_pages, co
                                const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
                                void* out, int32_t out_dtype,
                                void* workspace, size_t workspace_bytes, int32_t num_splits,
+                               saw_stream_t stream);
+
+/*
+ * Measurement aids (they compute nothing of the method; bench.py reports them next to the kernels' figures).
+ *
+ * saw_read_probe: a kernel that only READS the cache, in the decode kernel's access pattern - as many
+ * single-wavefront blocks as the chip holds of the decode kernel (2048), each walking an equal share of
+ * `page_ids` for one kv head in batches of four pages: the K and V code tiles (1 KiB pieces) and the
+ * (scale, zero) pairs, one batch ahead, streaming cache policy - and folds what it read into one word per
+ * wavefront.  Bytes read: n_pages * n_kv_heads * 2304 (head_dim 128 only).  Timing it gives the read-only
+ * streaming ceiling of the memory system for this pattern; with page_ids = 0, 1, 2, ... the plain
+ * contiguous read.  `sink`: device, at least 8192 bytes.
+ *
+ * saw_plain_quant_store_valu: saw_rotate_quant_store restricted to "no rotation" (had_block and
+ * rotate_mask are ignored; head_dim 128) on a plain vector-ALU kernel without matrix cores or LDS staging:
+ * the leanest plain INT4 store (App. A.1's quantiser, same bytes as the fused kernel with had_block 1), as
+ * the comparator for what the fused rotation costs.
+ */
+int saw_read_probe(const saw_cache_t* cache, const int32_t* page_ids, int64_t n_pages, void* sink,
+                   size_t sink_bytes, saw_stream_t stream);
+int saw_plain_quant_store_valu(const saw_cache_t* cache, const void* K, const void* V, int32_t in_dtype,
+                               int64_t T, int64_t token_stride_elems, const int32_t* page_table,
+                               int32_t n_seqs, int32_t max_pages_per_seq, const int32_t* slots,
                                saw_stream_t stream);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ class SawCacheStruct(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("page_size", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("had_block", ctypes.c_int32), ("rotate_mask", ctypes.c_int32),
-                ("sign_bits", ctypes.c_uint32 * 4)]
+                ("sign_bits", ctypes.c_uint32 * 4), ("dense_rot", ctypes.c_void_p)]
 
 
 class SawError(RuntimeError):
@@ -49,7 +49,14 @@ def lib() -> ctypes.CDLL:
         L.saw_version.restype = ctypes.c_int
         L.saw_strerror.restype = ctypes.c_char_p
         L.saw_strerror.argtypes = [ctypes.c_int]
+        L.saw_dense_rotation_bytes.restype = sz
+        L.saw_dense_rotation_bytes.argtypes = [i32]
+        L.saw_prepare_dense_rotation.argtypes = [vp, i32, vp, sz, vp]
         L.saw_rotate_quant_store.argtypes = [cp, vp, vp, i32, i64, i64, vp, i32, i32, vp, vp]
+        L.saw_rotate_quant_store_layers.argtypes = [cp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i64, i64, vp, i32,
+                                                    i32, vp, vp]
+        L.saw_read_probe.argtypes = [cp, vp, i64, vp, sz, vp]
+        L.saw_plain_quant_store_valu.argtypes = [cp, vp, vp, i32, i64, i64, vp, i32, i32, vp, vp]
         L.saw_decode_workspace_bytes.restype = sz
         L.saw_decode_workspace_bytes.argtypes = [cp, i32, i32, i32, i32]
         L.saw_decode_plan.argtypes = [cp, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -83,7 +90,7 @@ class Cache:
     """One layer's INT4 paged cache: device tensors plus the shape/rotation descriptor."""
 
     def __init__(self, num_pages, n_kv_heads, head_dim, had_block, rotate_mask=ROT_K | ROT_V,
-                 page_size=16, device="cuda", zero=True, signs=None):
+                 page_size=16, device="cuda", zero=True, signs=None, dense=None):
         alloc = torch.zeros if zero else torch.empty
         self.k_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
         self.v_codes = alloc((num_pages, n_kv_heads, page_size, head_dim // 2), dtype=torch.uint8, device=device)
@@ -99,14 +106,30 @@ class Cache:
                 if v < 0:
                     self.sign_bits[c // 32] |= 1 << (c % 32)
 
+        # dense: the learned rotation R_l, a [head_dim][head_dim] array-like (y = x R_l), or None
+        self.dense_rot = prepare_dense_rotation(dense, head_dim, device) if dense is not None else None
+
     def struct(self) -> SawCacheStruct:
         return SawCacheStruct(self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_meta.data_ptr(),
                               self.v_meta.data_ptr(), self.num_pages, self.n_kv_heads, self.page_size,
                               self.head_dim, self.had_block, self.rotate_mask,
-                              (ctypes.c_uint32 * 4)(*self.sign_bits))
+                              (ctypes.c_uint32 * 4)(*self.sign_bits),
+                              self.dense_rot.data_ptr() if self.dense_rot is not None else None)
 
     def nbytes(self) -> int:
         return sum(t.numel() * t.element_size() for t in (self.k_codes, self.v_codes, self.k_meta, self.v_meta))
+
+
+def prepare_dense_rotation(R, head_dim, device="cuda"):
+    """saw_prepare_dense_rotation: R ``[d][d]`` (array-like or tensor, y = x R) -> the prepared device buffer."""
+    Rt = torch.as_tensor(R, dtype=torch.float32).to(device).contiguous()
+    assert Rt.shape == (head_dim, head_dim)
+    n = lib().saw_dense_rotation_bytes(head_dim)
+    if n == 0:
+        raise SawError(-1, "saw_dense_rotation_bytes")
+    buf = torch.empty(n, dtype=torch.uint8, device=device)
+    _check(lib().saw_prepare_dense_rotation(_ptr(Rt), head_dim, _ptr(buf), n, _stream()), "saw_prepare_dense_rotation")
+    return buf
 
 
 def rotate_quant_store(cache: Cache, K, V, page_table, slots):
@@ -121,6 +144,48 @@ def rotate_quant_store(cache: Cache, K, V, page_table, slots):
                                         K.stride(0) if T > 1 else cache.n_kv_heads * cache.head_dim,
                                         _ptr(page_table), page_table.shape[0], page_table.shape[1],
                                         _ptr(slots), _stream()), "saw_rotate_quant_store")
+
+
+def rotate_quant_store_layers(caches, Ks, Vs, page_table, slots):
+    """saw_rotate_quant_store_layers: lists of n_layers caches and ``[T][Hkv][d]`` K / V tensors, one launch
+    per 32 layers."""
+    n = len(caches)
+    c0 = caches[0]
+    T = Ks[0].shape[0]
+    stride = Ks[0].stride(0) if T > 1 else c0.n_kv_heads * c0.head_dim
+    for K, V in zip(Ks, Vs):
+        assert K.dtype == Ks[0].dtype and K.shape == Ks[0].shape == V.shape and K.stride(2) == 1 and K.stride(1) == c0.head_dim
+        assert V.stride() == K.stride() and (T <= 1 or K.stride(0) == stride)
+    assert len(Ks) == n == len(Vs) and page_table.is_contiguous() and slots.is_contiguous() and slots.shape == (T, 2)
+    sts = (SawCacheStruct * n)(*[c.struct() for c in caches])
+    kp = (ctypes.c_void_p * n)(*[K.data_ptr() for K in Ks])
+    vp_ = (ctypes.c_void_p * n)(*[V.data_ptr() for V in Vs])
+    _check(lib().saw_rotate_quant_store_layers(sts, kp, vp_, n, _DT[Ks[0].dtype], T, stride, _ptr(page_table),
+                                               page_table.shape[0], page_table.shape[1], _ptr(slots), _stream()),
+           "saw_rotate_quant_store_layers")
+
+
+def read_probe(cache: Cache, page_ids, sink=None):
+    """saw_read_probe: read-only walk over `page_ids` (int32 device tensor) in the decode kernel's pattern;
+    returns the bytes it reads."""
+    assert page_ids.dtype == torch.int32 and page_ids.is_contiguous()
+    if sink is None:
+        sink = torch.empty(2048, dtype=torch.int32, device=page_ids.device)
+    st = cache.struct()
+    _check(lib().saw_read_probe(ctypes.byref(st), _ptr(page_ids), page_ids.numel(), _ptr(sink), sink.numel() * 4,
+                                _stream()), "saw_read_probe")
+    return page_ids.numel() * cache.n_kv_heads * 2304
+
+
+def plain_quant_store_valu(cache: Cache, K, V, page_table, slots):
+    """saw_plain_quant_store_valu: the plain INT4 store on the vector ALU (comparator; head_dim 128)."""
+    T = K.shape[0]
+    assert K.dtype == V.dtype and K.shape == V.shape and K.stride(2) == 1 and K.stride(1) == cache.head_dim
+    st = cache.struct()
+    _check(lib().saw_plain_quant_store_valu(ctypes.byref(st), _ptr(K), _ptr(V), _DT[K.dtype], T,
+                                            K.stride(0) if T > 1 else cache.n_kv_heads * cache.head_dim,
+                                            _ptr(page_table), page_table.shape[0], page_table.shape[1], _ptr(slots),
+                                            _stream()), "saw_plain_quant_store_valu")
 
 
 def decode_workspace_bytes(cache: Cache, B, n_q_heads, max_seq_len, num_splits=0) -> int:

@@ -16,6 +16,12 @@ namespace saw {
 
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
                  int32_t, int32_t, const int32_t*, const int32_t*, int32_t, hipStream_t);
+int launch_prepare_dense(const float*, void*, hipStream_t);
+int launch_read_probe(const saw_cache_t*, const int32_t*, int64_t, void*, int32_t, hipStream_t);
+int launch_plain_store_valu(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*, int32_t,
+                            int32_t, const int32_t*, hipStream_t);
+int launch_store_layers(const saw_cache_t*, const void* const*, const void* const*, int, int, int64_t, int64_t,
+                        const int32_t*, int32_t, int32_t, const int32_t*, hipStream_t);
 int launch_flatten(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, void*, void*, int64_t,
                    hipStream_t);
 int launch_dequant(const saw_cache_t*, const int32_t*, int32_t, int32_t, int32_t, int32_t, int32_t,
@@ -27,6 +33,8 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
                const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
                const SplitPlan& plan, const void* k_new, const void* v_new, int kv_new_dtype, int len_bias,
                hipStream_t st);
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
 static bool shape_ok(const saw_cache_t* c) {
   if (c->page_size != 16) return false;
@@ -42,10 +50,11 @@ static bool block_ok(const saw_cache_t* c) {
   if (c->rotate_mask & ~(SAW_ROT_K | SAW_ROT_V)) return false;
   // sign bits exist for the head's channels only
   if (c->head_dim == 64 && (c->sign_bits[2] | c->sign_bits[3])) return false;
+  // the learned rotation is built for head_dim 128, its prepared buffer read with 16-byte loads
+  if (c->dense_rot && (c->head_dim != kDenseD || !aligned16(c->dense_rot))) return false;
   return true;
 }
 
-static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
 // Split-KV plan.  Partitions are whole multiples of 64 tokens so every wavefront pass
 // starts on a page boundary.  The automatic choice aims at about 2048 wavefronts (8 per compute
@@ -109,6 +118,15 @@ const char* saw_strerror(int code) {
   }
 }
 
+size_t saw_dense_rotation_bytes(int32_t head_dim) { return head_dim == kDenseD ? kDenseBytes : 0; }
+
+int saw_prepare_dense_rotation(const float* R, int32_t head_dim, void* prepared, size_t prepared_bytes,
+                               saw_stream_t stream) {
+  if (!R || !prepared) return SAW_ENULL;
+  if (head_dim != kDenseD || prepared_bytes < kDenseBytes || !aligned16(R) || !aligned16(prepared)) return SAW_EINVAL;
+  return launch_prepare_dense(R, prepared, (hipStream_t)stream);
+}
+
 int saw_rotate_quant_store(const saw_cache_t* c, const void* K, const void* V, int32_t in_dtype,
                            int64_t T, int64_t token_stride_elems, const int32_t* page_table,
                            int32_t n_seqs, int32_t max_pages_per_seq, const int32_t* slots,
@@ -126,6 +144,73 @@ int saw_rotate_quant_store(const saw_cache_t* c, const void* K, const void* V, i
     return SAW_EINVAL;
   return launch_store(c, K, V, in_dtype, T, token_stride_elems, page_table, n_seqs, max_pages_per_seq,
                       slots, nullptr, 0, (hipStream_t)stream);
+}
+
+int saw_rotate_quant_store_layers(const saw_cache_t* caches, const void* const* K, const void* const* V,
+                                  int32_t n_layers, int32_t in_dtype, int64_t T, int64_t token_stride_elems,
+                                  const int32_t* page_table, int32_t n_seqs, int32_t max_pages_per_seq,
+                                  const int32_t* slots, saw_stream_t stream) {
+  if (!caches || !K || !V) return SAW_ENULL;
+  if (n_layers < 1) return SAW_EINVAL;
+  if (in_dtype != SAW_F16 && in_dtype != SAW_BF16) return SAW_EINVAL;
+  if (T < 0 || n_seqs < 1 || max_pages_per_seq < 1) return SAW_EINVAL;
+  const saw_cache_t* c0 = caches;
+  if (!shape_ok(c0) || !block_ok(c0)) return SAW_EINVAL;
+  if (token_stride_elems < (int64_t)c0->n_kv_heads * c0->head_dim || (token_stride_elems & 7)) return SAW_EINVAL;
+  if (!page_table || !slots) return T == 0 ? SAW_OK : SAW_ENULL;
+  if (((uintptr_t)slots) & 7u) return SAW_EINVAL;
+  for (int l = 0; l < n_layers; ++l) {
+    const saw_cache_t* c = caches + l;
+    // one launch, one shape: the layers of a model agree in everything but their pools, inputs and learned rotation
+    if (c->num_pages != c0->num_pages || c->n_kv_heads != c0->n_kv_heads || c->page_size != c0->page_size ||
+        c->head_dim != c0->head_dim || c->had_block != c0->had_block || c->rotate_mask != c0->rotate_mask ||
+        c->sign_bits[0] != c0->sign_bits[0] || c->sign_bits[1] != c0->sign_bits[1] ||
+        c->sign_bits[2] != c0->sign_bits[2] || c->sign_bits[3] != c0->sign_bits[3] ||
+        (c->dense_rot != nullptr) != (c0->dense_rot != nullptr))
+      return SAW_EINVAL;
+    if (!block_ok(c)) return SAW_EINVAL;
+    if (T == 0) continue;
+    if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !K[l] || !V[l]) return SAW_ENULL;
+    if (!aligned16(K[l]) || !aligned16(V[l]) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
+        (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u))
+      return SAW_EINVAL;
+  }
+  if (T == 0) return SAW_OK;
+  for (int l0 = 0; l0 < n_layers; l0 += SAW_MAX_STORE_LAYERS) {       // 32 layers per launch
+    const int n = n_layers - l0 < SAW_MAX_STORE_LAYERS ? n_layers - l0 : SAW_MAX_STORE_LAYERS;
+    const int rc = launch_store_layers(caches + l0, K + l0, V + l0, n, in_dtype, T, token_stride_elems, page_table,
+                                       n_seqs, max_pages_per_seq, slots, (hipStream_t)stream);
+    if (rc != SAW_OK) return rc;
+  }
+  return SAW_OK;
+}
+
+int saw_read_probe(const saw_cache_t* c, const int32_t* page_ids, int64_t n_pages, void* sink, size_t sink_bytes,
+                   saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || c->head_dim != 128 || n_pages < 1) return SAW_EINVAL;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !page_ids || !sink) return SAW_ENULL;
+  if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta)) return SAW_EINVAL;
+  const int32_t n_waves = (2048 / c->n_kv_heads) * c->n_kv_heads;       // as many as the chip holds of the decode kernel
+  if (n_waves < c->n_kv_heads || sink_bytes < (size_t)n_waves * 4) return SAW_EINVAL;
+  return launch_read_probe(c, page_ids, n_pages, sink, n_waves, (hipStream_t)stream);
+}
+
+int saw_plain_quant_store_valu(const saw_cache_t* c, const void* K, const void* V, int32_t in_dtype, int64_t T,
+                               int64_t token_stride_elems, const int32_t* page_table, int32_t n_seqs,
+                               int32_t max_pages_per_seq, const int32_t* slots, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  if (!shape_ok(c) || c->head_dim != 128) return SAW_EINVAL;
+  if (in_dtype != SAW_F16 && in_dtype != SAW_BF16) return SAW_EINVAL;
+  if (T < 0 || n_seqs < 1 || max_pages_per_seq < 1) return SAW_EINVAL;
+  if (T == 0) return SAW_OK;
+  if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !K || !V || !page_table || !slots) return SAW_ENULL;
+  if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems & 7)) return SAW_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
+      (((uintptr_t)c->k_meta) & 7u) || (((uintptr_t)c->v_meta) & 7u) || (((uintptr_t)slots) & 7u))
+    return SAW_EINVAL;
+  return launch_plain_store_valu(c, K, V, in_dtype, T, token_stride_elems, page_table, n_seqs, max_pages_per_seq, slots,
+                                 (hipStream_t)stream);
 }
 
 size_t saw_decode_workspace_bytes(const saw_cache_t* c, int32_t B, int32_t n_q_heads,
@@ -326,6 +411,7 @@ int saw_flatten_dequant(const saw_cache_t* c, const int32_t* page_table, int32_t
   if (seq < 0 || pos_begin < 0 || pos_end < pos_begin || max_pages_per_seq < 1) return SAW_EINVAL;
   if ((int64_t)pos_end > (int64_t)max_pages_per_seq * c->page_size) return SAW_EINVAL;
   if (token_stride_elems < (int64_t)c->n_kv_heads * c->head_dim || (token_stride_elems % 8)) return SAW_EINVAL;
+  if (unrotate && c->dense_rot && (c->rotate_mask & (SAW_ROT_K | SAW_ROT_V))) return SAW_EINVAL;   // not built here
   if (pos_end == pos_begin) return SAW_OK;
   if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !page_table) return SAW_ENULL;
   if (!k_out && !v_out) return SAW_OK;

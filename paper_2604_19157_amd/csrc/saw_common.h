@@ -70,6 +70,22 @@ __device__ __forceinline__ float apply_sign(const SignBits& sb, int c, float v) 
   return __uint_as_float(__float_as_uint(v) ^ sign_flip32(sb, c));
 }
 
+// The prepared form of a learned per-layer rotation R_l (App. A.3) for head_dim 128, as
+// saw_prepare_dense_rotation lays it out:
+//   [0, 64 KiB)        R_l, fp32 row-major [i][j]                (y = x R_l: query, appended token)
+//   [64 KiB, 128 KiB)  R_l^T, fp32 row-major                     (outputs, read-backs)
+//   [128 KiB, 224 KiB) three bf16 limbs (hi, mid, lo; hi + mid + lo = R_l to 24 bits) as A operands of
+//                      v_mfma_f32_16x16x32_bf16 for the store kernel: 16 bytes per (limb L, output tile
+//                      J < 8, k-step a < 4, lane) at index ((L * 8 + J) * 4 + a) * 64 + lane, holding
+//                      R_l[32 a + 8 (lane / 16) + e][dense_out_channel(J, lane % 16)], e = 0..7.
+constexpr int kDenseD = 128;
+constexpr size_t kDenseRtOffset = (size_t)kDenseD * kDenseD * 4;
+constexpr size_t kDenseLimbOffset = 2 * kDenseRtOffset;
+constexpr size_t kDenseBytes = kDenseLimbOffset + (size_t)3 * 8 * 4 * 64 * 16;
+// output channel of row m (0..15) of output tile J (0..7): tiles 2 a' and 2 a' + 1 together give lane
+// (token, rg) the eight contiguous channels 32 a' + 8 rg .. + 7, the layout the store kernel quantises from
+__host__ __device__ inline int dense_out_channel(int J, int m) { return 32 * (J >> 1) + 8 * (m >> 2) + 4 * (J & 1) + (m & 3); }
+
 // 1/sqrt(h) for the supported Hadamard orders (correctly rounded constants).
 __device__ __forceinline__ float had_norm(int h) {
   return h == 16 ? 0.25f : h == 32 ? 0.17677669529663687f : h == 64 ? 0.125f

@@ -384,6 +384,15 @@ __global__ __launch_bounds__(NT) void decode_merge_kernel(DecodeParams p) {
     for (int k = 1; k < NG; ++k) num += red[k][c];
     o = num / den;
   }
+  if (D == 128 && p.dense_v) {        // block-uniform: the learned rotation's transpose first (App. A.3)
+    float* x = red[0];
+    __syncthreads();                  // every read of red[][] above is done
+    if (g == 0) x[c] = o;
+    __syncthreads();
+    if (wave == 0) wave_lds_matvec128<1>(x, p.dense + kDenseD * kDenseD, lane);
+    __syncthreads();
+    o = x[c];
+  }
   if (p.rot_v) {                      // block-uniform
     float* x = red[0];
     __syncthreads();                  // every read of red[][] above is done
@@ -486,6 +495,9 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
   p.rot_v = !kv16 && c->had_block > 1 && (c->rotate_mask & SAW_ROT_V);
   for (int i = 0; i < 4; ++i) p.signs.w[i] = kv16 ? 0u : c->sign_bits[i];
   p.has_signs = (p.signs.w[0] | p.signs.w[1] | p.signs.w[2] | p.signs.w[3]) != 0;
+  p.dense = kv16 ? nullptr : (const float*)c->dense_rot;
+  p.dense_k = p.dense && (c->rotate_mask & SAW_ROT_K);
+  p.dense_v = p.dense && (c->rotate_mask & SAW_ROT_V);
   p.num_splits = plan.num_splits;
   p.chunk_tokens = plan.chunk_tokens;
   p.bound = plan.bound;

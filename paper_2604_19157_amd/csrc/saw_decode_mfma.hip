@@ -50,7 +50,9 @@ constexpr float kLazyTau = 8.0f;               // reference max may lag the true
 // HP (two 64-channel heads per row, see the kernel): `qraw[j]`, j < G, is channel `lane` of the j-th
 // query head of the pair; its row gets the 64 values in the half of its own kv head and zeros in
 // the other half, so that the 128-channel products below are the 64-channel ones.
-template <int G, int NH, bool HP>
+// DN: a learned rotation R_l follows the Hadamard (App. A.3); a compile-time flag, so that the kernels
+// of caches without one carry none of its code.
+template <int G, int NH, bool HP, bool DN>
 __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&qraw)[2 * G], int lane,
                                           float* __restrict__ qs, u32x4 (&a_q)[4],
                                           float (&qsum)[NH], float& qmul_out) {
@@ -80,6 +82,10 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   if (p.rot_k) {
     wave_lds_fwht128<G>(qs, min(p.had_block, 64), lane);
     qmul *= had_norm(p.had_block);
+  }
+  // learned rotation after the Hadamard (App. A.3: q^ = (q H_b) R_l)
+  if constexpr (DN) {
+    if (p.dense_k) wave_lds_matvec128<G>(qs, p.dense, lane);
   }
   const bool is_lo = row16 >= LO;
   const int qhead = row16 - (is_lo ? LO : 0);
@@ -134,7 +140,7 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
 //   scr   LDS scratch of 272 floats (16-byte aligned), distinct from qrot
 // HP: the 128 values are the new vectors of two neighbouring 64-channel kv heads (lanes 0-31 hold
 // the first head's channels), quantised and stored per head; `kvh` counts pairs.
-template <int G, int NH, bool HP>
+template <int G, int NH, bool HP, bool DN>
 __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int lane, int L, int pid,
                                              uint32_t wk, uint32_t wv,
                                              const float* __restrict__ qrot, float qmul,
@@ -151,7 +157,8 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
   const int64_t vec = ((int64_t)pid * p.n_kv_heads + head) * 16 + slot;
   // K and V go through every step together (index 0: K, 1: V): one two-vector transform instead of
   // two single ones, and reductions that overlap each other
-  const bool rot[2] = {p.rot_k != 0, p.rot_v != 0};
+  const bool rot[2] = {p.rot_k != 0, p.rot_v != 0};                                // block Hadamard
+  const bool dns[2] = {DN && p.dense_k != 0, DN && p.dense_v != 0};                  // learned rotation after it
   float x[2][2];
   if (p.kv_new_dtype == SAW_BF16) { widen2<SAW_BF16>(wk, x[0][0], x[0][1]); widen2<SAW_BF16>(wv, x[1][0], x[1][1]); }
   else                            { widen2<SAW_F16>(wk, x[0][0], x[0][1]);  widen2<SAW_F16>(wv, x[1][0], x[1][1]); }
@@ -164,13 +171,18 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
       }
     }
   }
-  if (rot[0] || rot[1]) {
+  if (rot[0] || rot[1] || dns[0] || dns[1]) {
     *(f32x2*)(yb + 2 * lane) = f32x2{x[0][0], x[0][1]};
     *(f32x2*)(yb + D + 2 * lane) = f32x2{x[1][0], x[1][1]};
     wave_sync();
     if (rot[0] && rot[1]) wave_lds_fwht128<2>(yb, p.had_block, lane);
     else if (rot[0]) wave_lds_fwht128<1>(yb, p.had_block, lane);
-    else wave_lds_fwht128<1>(yb + D, p.had_block, lane);
+    else if (rot[1]) wave_lds_fwht128<1>(yb + D, p.had_block, lane);
+    if constexpr (DN) {                                    // k^ = (k H_b) R_l, the same for V (App. A.3)
+      if (dns[0] && dns[1]) wave_lds_matvec128<2>(yb, p.dense, lane);
+      else if (dns[0]) wave_lds_matvec128<1>(yb, p.dense, lane);
+      else if (dns[1]) wave_lds_matvec128<1>(yb + D, p.dense, lane);
+    }
     const f32x2 yk = *(const f32x2*)(yb + 2 * lane), yv = *(const f32x2*)(yb + D + 2 * lane);
     x[0][0] = yk.x; x[0][1] = yk.y; x[1][0] = yv.x; x[1][1] = yv.y;
     wave_sync();                                             // yb is rewritten below
@@ -287,13 +299,14 @@ enum SegMode : int { kSegSplitKV = 0, kSegAlone = 1, kSegShare = 2 };
 // the spread of the lengths).  Four wavefronts over three sequences put 4/3 wavefronts on a (sequence,
 // kv head) item, which fills the chip when there are 1025 to 1536 items - too many for four
 // wavefronts per pair, and with two per pair a quarter to a half of the slots would stay empty.
-template <int G, int NW, bool PAIR, bool HP = false, int PK = 2>
+template <int G, int NW, bool PAIR, bool HP = false, int PK = 2, bool DN = false>
 // (a launch of this kernel puts at most 8 wavefronts on a compute unit, 2 per SIMD: let the
 // register allocator use the 256 registers that leaves each of them)
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void decode_int4_mfma_kernel(DecodeParams p) {
   static_assert(!PAIR || NW == 2 || NW == 4, "a pair block has two or four wavefronts");
   static_assert(!HP || G >= 2, "a head pair has at least one query head per kv head");
+  static_assert(!(HP && DN), "the learned rotation is built for head_dim 128");
   constexpr int D = 128;                       // channels of a row (a head, or a pair of 64-channel heads)
   constexpr int DH = HP ? 64 : 128;            // channels of one head
   constexpr int GK = HP ? G / 2 : G;           // query heads per kv head
@@ -602,7 +615,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       // randomised Hadamard: q diag(sigma) first (element lane + 64 j is channel lane + 64 (j & 1))
       if (p.rot_k && p.has_signs) qraw[j] = apply_sign(p.signs, HP ? lane : lane + 64 * (j & 1), qraw[j]);
     }
-    prepare_q<G, NH, HP>(p, qraw, lane, qrows, a_q, qsum, qmul);
+    prepare_q<G, NH, HP, DN>(p, qraw, lane, qrows, a_q, qsum, qmul);
   }
 
   f32x4 oacc[8];
@@ -612,7 +625,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
   if (takes_new)
-    append_token<G, NH, HP>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
+    append_token<G, NH, HP, DN>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
                             ascr, oacc, m_ref, lsum);
 
   // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
@@ -929,8 +942,11 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     fb[idx] = v / l0;
   }
   wave_sync();
-  // rotate back once for V (App. A.4), write the output
+  // rotate back once for V (App. A.4; a learned rotation's transpose first, App. A.3), write the output
   float onorm = 1.0f;
+  if constexpr (DN) {
+    if (p.dense_v) wave_lds_matvec128<G>(fb, p.dense + kDenseD * kDenseD, lane);
+  }
   if (p.rot_v) {
     wave_lds_fwht128<G>(fb, p.had_block, lane);
     onorm = had_norm(p.had_block);
@@ -960,25 +976,25 @@ void decode_int4_mfma_kernel(DecodeParams p) {
 #undef SAW_SEG
 #undef SAW_SEQ
 
-template <int G, bool HP>
+template <int G, bool HP, bool DN>
 static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_t st) {
   if constexpr (!(HP && G == 8)) {       // (two such blocks of head pairs with eight query rows would not fit LDS)
     if (p.pair == 4 && p.pair_seqs == 3) {
-      decode_int4_mfma_kernel<G, 4, true, HP, 3><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
+      decode_int4_mfma_kernel<G, 4, true, HP, 3, DN><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
       return;
     }
   }
   if (p.pair == 4) {
-    decode_int4_mfma_kernel<G, 4, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(256), 0, st>>>(p);
+    decode_int4_mfma_kernel<G, 4, true, HP, 2, DN><<<dim3(1, grid.y, (B + 1) / 2), dim3(256), 0, st>>>(p);
     return;
   }
   if (p.pair) {
-    decode_int4_mfma_kernel<G, 2, true, HP><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
+    decode_int4_mfma_kernel<G, 2, true, HP, 2, DN><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
     return;
   }
-  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false, HP><<<grid, dim3(256), 0, st>>>(p);
-  else if (nw == 2) decode_int4_mfma_kernel<G, 2, false, HP><<<grid, dim3(128), 0, st>>>(p);
-  else decode_int4_mfma_kernel<G, 1, false, HP><<<grid, dim3(64), 0, st>>>(p);
+  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false, HP, 2, DN><<<grid, dim3(256), 0, st>>>(p);
+  else if (nw == 2) decode_int4_mfma_kernel<G, 2, false, HP, 2, DN><<<grid, dim3(128), 0, st>>>(p);
+  else decode_int4_mfma_kernel<G, 1, false, HP, 2, DN><<<grid, dim3(64), 0, st>>>(p);
 }
 
 // `G`: query heads per kv head.  `nw`: wavefronts per (sequence, kv head, partition) block: 1, 2 or
@@ -987,18 +1003,28 @@ static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_
 int launch_decode_int4_mfma(const DecodeParams& p, int G, int B, int nw, bool head_pairs, dim3 grid, hipStream_t st) {
   if (head_pairs) {
     switch (G) {
-      case 1: launch_g<2, true>(p, B, nw, grid, st); break;
-      case 2: launch_g<4, true>(p, B, nw, grid, st); break;
-      case 4: launch_g<8, true>(p, B, nw, grid, st); break;
+      case 1: launch_g<2, true, false>(p, B, nw, grid, st); break;
+      case 2: launch_g<4, true, false>(p, B, nw, grid, st); break;
+      case 4: launch_g<8, true, false>(p, B, nw, grid, st); break;
+      default: return SAW_EINVAL;
+    }
+    return SAW_OK;
+  }
+  if (p.dense) {                        // a learned rotation after the Hadamard: the kernels that carry its code
+    switch (G) {
+      case 1: launch_g<1, false, true>(p, B, nw, grid, st); break;
+      case 2: launch_g<2, false, true>(p, B, nw, grid, st); break;
+      case 4: launch_g<4, false, true>(p, B, nw, grid, st); break;
+      case 8: launch_g<8, false, true>(p, B, nw, grid, st); break;
       default: return SAW_EINVAL;
     }
     return SAW_OK;
   }
   switch (G) {
-    case 1: launch_g<1, false>(p, B, nw, grid, st); break;
-    case 2: launch_g<2, false>(p, B, nw, grid, st); break;
-    case 4: launch_g<4, false>(p, B, nw, grid, st); break;
-    case 8: launch_g<8, false>(p, B, nw, grid, st); break;
+    case 1: launch_g<1, false, false>(p, B, nw, grid, st); break;
+    case 2: launch_g<2, false, false>(p, B, nw, grid, st); break;
+    case 4: launch_g<4, false, false>(p, B, nw, grid, st); break;
+    case 8: launch_g<8, false, false>(p, B, nw, grid, st); break;
     default: return SAW_EINVAL;
   }
   return SAW_OK;

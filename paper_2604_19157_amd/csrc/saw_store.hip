@@ -53,6 +53,8 @@ struct DequantParams {
   int32_t had_block;
   int32_t unrot[2];
   SignBits signs;
+  const float* dense_t;   // transpose of a learned rotation R_l (App. A.3), fp32 [128][128] row-major; null: none
+  int32_t undense[2];     // multiply K / V by R_l^T before the Hadamard's inverse
 };
 
 template <int D>
@@ -79,6 +81,28 @@ __global__ __launch_bounds__(256) void dequant_pages_kernel(DequantParams p) {
   float e[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) e[i] = sz.x * ((float)((w >> (4 * i)) & 15u) - sz.y);
+  if (D == 128 && p.undense[which]) {          // block-uniform: x^ R_l^T first (the inverse of a rotation is its transpose)
+    __shared__ __attribute__((aligned(16))) float xs[VPB][D];
+    float* const row = xs[tid / LPV];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) row[8 * sub + i] = e[i];
+    __syncthreads();
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll 4
+    for (int k = 0; k < D; ++k) {
+      const float xk = row[k];
+      const float4 r0 = *(const float4*)(p.dense_t + k * D + 8 * sub);
+      const float4 r1 = *(const float4*)(p.dense_t + k * D + 8 * sub + 4);
+      acc[0] = fmaf(xk, r0.x, acc[0]); acc[1] = fmaf(xk, r0.y, acc[1]);
+      acc[2] = fmaf(xk, r0.z, acc[2]); acc[3] = fmaf(xk, r0.w, acc[3]);
+      acc[4] = fmaf(xk, r1.x, acc[4]); acc[5] = fmaf(xk, r1.y, acc[5]);
+      acc[6] = fmaf(xk, r1.z, acc[6]); acc[7] = fmaf(xk, r1.w, acc[7]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = acc[i];
+  }
   if (p.unrot[which]) {
     fwht<LPV>(e, sub, p.had_block);
     const float norm = had_norm(p.had_block);
@@ -126,16 +150,23 @@ __global__ __launch_bounds__(256) void kv16_store_kernel(Kv16StoreParams p) {
 // ---------------------------------------------------------------------------------------
 // host launchers (called from saw_api.hip)
 // the store kernel itself lives in saw_store_mfma.hip
-int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
-                      const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
-                      const int32_t* append_lens, int32_t append_bound, hipStream_t st);
+int launch_store_mfma(const saw_cache_t* c, const void* const* K, const void* const* V, int n_layers, int dt,
+                      int64_t T, int64_t stride, const int32_t* pt, int32_t n_seqs, int32_t max_pages,
+                      const int32_t* slots, const int32_t* append_lens, int32_t append_bound, hipStream_t st);
 
 // `slots` null: token t is appended to sequence t at position append_lens[t] (skipped when that
 // exceeds append_bound).
 int launch_store(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
                  const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
                  const int32_t* append_lens, int32_t append_bound, hipStream_t st) {
-  return launch_store_mfma(c, K, V, dt, T, stride, pt, n_seqs, max_pages, slots, append_lens, append_bound, st);
+  return launch_store_mfma(c, &K, &V, 1, dt, T, stride, pt, n_seqs, max_pages, slots, append_lens, append_bound, st);
+}
+
+// Several layers' stores in one launch: `c`, `K`, `V` are host arrays of n_layers entries.
+int launch_store_layers(const saw_cache_t* c, const void* const* K, const void* const* V, int n_layers, int dt,
+                        int64_t T, int64_t stride, const int32_t* pt, int32_t n_seqs, int32_t max_pages,
+                        const int32_t* slots, hipStream_t st) {
+  return launch_store_mfma(c, K, V, n_layers, dt, T, stride, pt, n_seqs, max_pages, slots, nullptr, 0, st);
 }
 
 int launch_dequant(const saw_cache_t* c, const int32_t* pt, int32_t max_pages, int32_t seq,
@@ -151,6 +182,9 @@ int launch_dequant(const saw_cache_t* c, const int32_t* pt, int32_t max_pages, i
   p.unrot[0] = unrotate && (c->had_block > 1) && (c->rotate_mask & SAW_ROT_K);
   p.unrot[1] = unrotate && (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
   for (int i = 0; i < 4; ++i) p.signs.w[i] = c->sign_bits[i];
+  p.dense_t = c->dense_rot ? (const float*)((const uint8_t*)c->dense_rot + kDenseRtOffset) : nullptr;
+  p.undense[0] = unrotate && c->dense_rot && (c->rotate_mask & SAW_ROT_K);
+  p.undense[1] = unrotate && c->dense_rot && (c->rotate_mask & SAW_ROT_V);
   const int D = c->head_dim;
   const int vpb = 256 / (D / 8);
   const int64_t n_vec = (int64_t)p.n_tokens * c->n_kv_heads;

@@ -28,10 +28,17 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct StoreMfmaParams {
+// One launch can serve several layers (grid.z): the layers share the slots, the page table and the
+// cache shape, and differ in their pools, their inputs and their learned rotation.
+constexpr int kMaxStoreLayers = 32;
+struct StoreLayerPtrs {
   uint8_t* codes[2];
   float* meta[2];
   const void* in[2];
+  const void* dense_limbs;      // learned rotation R_l (App. A.3) as bf16 limb operands, see saw_common.h; or null
+};
+struct StoreMfmaParams {
+  StoreLayerPtrs layer[kMaxStoreLayers];
   const int32_t* page_table;
   const int32_t* slots;         // [T][2] (sequence, position), or null:
   const int32_t* append_lens;   // then token t goes to sequence t at position append_lens[t],
@@ -43,6 +50,9 @@ struct StoreMfmaParams {
   int32_t rot[2];
   int32_t has_signs;            // any bit of `signs` set
   SignBits signs;               // diagonal in front of the Hadamard matrix (rotated tensors only)
+  int32_t dense_on[2];          // R_l follows the Hadamard for K / for V
+  int32_t kblocks;              // blocks that cover the (K|V, head) combinations of one token group
+  int32_t kinds_fastest;        // block order: see launch_store_mfma
 };
 
 template <int DT>
@@ -66,8 +76,16 @@ __device__ __forceinline__ float dppf(float v) {
 // and their code tiles and metadata are contiguous in the cache), so that loads, staging and the
 // matrix products run exactly as for head_dim 128; only the min/max, the scales and the addresses
 // are per head.
-template <int D, int DT, int XS, int HP = 1>
+// DENSE (D = 128, one head per wavefront): a learned per-layer rotation follows the Hadamard, y = (x H_blk) R_l
+// (App. A.3).  The Hadamard output of a lane - eight channels of each 32-channel group of one token - is
+// already the B operand of a v_mfma_f32_16x16x32_bf16 over that group, so it is split into three bf16 limbs
+// in registers (hi + mid + lo = the fp32 value to 24 bits) and multiplied by the three limbs of R_l, which
+// arrive as ready-made A operands from the prepared buffer (224 KiB, cache-resident): the six limb products
+// that matter (everything down to 2^-24 of the result), smallest first, accumulated in fp32.  The rows of the
+// A operands are ordered so that the result lands in the very lane layout the quantiser below expects.
+template <int D, int DT, int XS, int HP = 1, bool DENSE = false>
 __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaParams p) {
+  static_assert(!DENSE || (D == 128 && HP == 1), "the learned rotation is built for head_dim 128");
   constexpr int DH = D / HP;             // channels of one head (D itself unless HP = 2: then 64)
   constexpr int ROWB = D * 2;            // bytes of one token's head vector (or head pair)
   constexpr int XC = ROWB / 16;          // 16-byte chunks per vector (16 | 8)
@@ -79,13 +97,16 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   const int n16 = lane & 15, rg = lane >> 4;
   const int n_heads_w = p.n_kv_heads / HP;                    // heads (or head pairs) a tensor has
   const int n_kinds = 2 * n_heads_w;                          // (K|V, head or head pair) combinations
-  const int kind_raw = blockIdx.y * 4 + __builtin_amdgcn_readfirstlane(wave);
+  const int kb_id = p.kinds_fastest ? (int)(blockIdx.x % p.kblocks) : (int)blockIdx.y;
+  const int64_t tb_id = p.kinds_fastest ? (int64_t)(blockIdx.x / p.kblocks) : (int64_t)blockIdx.x;
+  const int kind_raw = kb_id * 4 + __builtin_amdgcn_readfirstlane(wave);
   const bool wave_live = kind_raw < n_kinds;                  // wave-uniform
   const int kind = wave_live ? kind_raw : 0;                  // an idle wavefront shadows kind 0 and stores nothing
   const int which = kind >= n_heads_w ? 1 : 0;
   const int head = (kind - which * n_heads_w) * HP;           // (first) head of this wavefront
-  const int64_t t0 = (int64_t)blockIdx.x * 16;
+  const int64_t t0 = tb_id * 16;
   const bool rot = p.rot[which] != 0;
+  const StoreLayerPtrs& lp = p.layer[blockIdx.z];
 
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][16 * ROWB];
   uint8_t* const stage = stage_all[wave];
@@ -98,7 +119,7 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     const int tok = off / ROWB, x = (off % ROWB) / 16;
     const int64_t t = min(t0 + tok, p.T - 1);                  // tokens past the end shadow the last one; never stored
     // (the input is read once and the cache written once: both are marked streaming, "nt")
-    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)p.in[which] + t * p.token_stride + head * DH + 8 * x));
+    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)lp.in[which] + t * p.token_stride + head * DH + 8 * x));
   }
   // this lane's token (column n16 of the tile) and where it goes
   const int64_t t_mine = t0 + n16;
@@ -184,6 +205,54 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
         y[8 * a + 16 + i] = u - v;
       }
   }
+  if constexpr (DENSE) {
+    if (p.dense_on[which]) {                                    // wavefront-uniform
+      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+      typedef float f32x2_t __attribute__((ext_vector_type(2)));
+      u32x4 bh[NA], bm[NA], bl[NA];                             // limbs of y as B operands, one per k-step (32 channels)
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        uint32_t wh[4], wm[4], wl[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float y0 = y[8 * a + 2 * e], y1 = y[8 * a + 2 * e + 1];
+          wh[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{y0, y1}, bf16x2_t));
+          const float r0 = y0 - __uint_as_float(wh[e] << 16), r1 = y1 - __uint_as_float(wh[e] & 0xffff0000u);
+          wm[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{r0, r1}, bf16x2_t));
+          const float q0 = r0 - __uint_as_float(wm[e] << 16), q1 = r1 - __uint_as_float(wm[e] & 0xffff0000u);
+          wl[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{q0, q1}, bf16x2_t));
+        }
+        bh[a] = u32x4{wh[0], wh[1], wh[2], wh[3]};
+        bm[a] = u32x4{wm[0], wm[1], wm[2], wm[3]};
+        bl[a] = u32x4{wl[0], wl[1], wl[2], wl[3]};
+      }
+      const u32x4* const A = (const u32x4*)lp.dense_limbs + lane;
+#pragma unroll
+      for (int J = 0; J < 8; ++J) {
+        u32x4 ah[NA], am[NA], al[NA];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          ah[a] = A[((0 * 8 + J) * 4 + a) * 64];
+          am[a] = A[((1 * 8 + J) * 4 + a) * 64];
+          al[a] = A[((2 * 8 + J) * 4 + a) * 64];
+        }
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#define SAW_LIMB_PRODUCT(RA, YB)                                                                     \
+  _Pragma("unroll") for (int a = 0; a < NA; ++a)                                                     \
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, RA[a]), __builtin_bit_cast(bf16x8, YB[a]), acc, 0, 0, 0);
+        SAW_LIMB_PRODUCT(al, bh)
+        SAW_LIMB_PRODUCT(ah, bl)
+        SAW_LIMB_PRODUCT(am, bm)
+        SAW_LIMB_PRODUCT(am, bh)
+        SAW_LIMB_PRODUCT(ah, bm)
+        SAW_LIMB_PRODUCT(ah, bh)
+#undef SAW_LIMB_PRODUCT
+        // tile J holds channels 32 (J / 2) + 8 rg + 4 (J % 2) + 0..3 of token n16
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[8 * (J >> 1) + 4 * (J & 1) + i] = acc[i];
+      }
+    }
+  }
   const float norm = rot ? had_norm(p.had_block) : 1.0f;
 
   // ---- token-wise min / max per head: in-lane, then the four rows holding the same token ----
@@ -248,10 +317,10 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (lane < 16 * (D / 2) / 16)
-      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(p.codes[which] + vec0 * (DH / 2) + 16 * lane));
+      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(lp.codes[which] + vec0 * (DH / 2) + 16 * lane));
 #pragma unroll
     for (int hh = 0; hh < HP; ++hh)
-      if (rg == hh) *(float2*)(p.meta[which] + (vec0 + 16 * hh + n16) * 2) = make_float2(s_store[hh], z_store[hh]);
+      if (rg == hh) *(float2*)(lp.meta[which] + (vec0 + 16 * hh + n16) * 2) = make_float2(s_store[hh], z_store[hh]);
     return;
   }
   if (!ok) return;
@@ -259,19 +328,26 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   for (int hh = 0; hh < HP; ++hh) {
     const int64_t vec = ((int64_t)page * p.n_kv_heads + head + hh) * 16 + (slot.y & 15);
 #pragma unroll
-    for (int a = NAH * hh; a < NAH * (hh + 1); ++a) ((uint32_t*)(p.codes[which] + vec * (DH / 2)))[4 * (a % NAH) + rg] = packed[a];
-    if (rg == hh) *(float2*)(p.meta[which] + vec * 2) = make_float2(s_store[hh], z_store[hh]);
+    for (int a = NAH * hh; a < NAH * (hh + 1); ++a) ((uint32_t*)(lp.codes[which] + vec * (DH / 2)))[4 * (a % NAH) + rg] = packed[a];
+    if (rg == hh) *(float2*)(lp.meta[which] + vec * 2) = make_float2(s_store[hh], z_store[hh]);
   }
 }
 
-int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt, int64_t T, int64_t stride,
+// `c`, `K`, `V`: n_layers cache descriptors and input pointers (host arrays); the layers agree in shape,
+// Hadamard block, mask and signs (checked by the caller).
+int launch_store_mfma(const saw_cache_t* c, const void* const* K, const void* const* V, int n_layers, int dt,
+                      int64_t T, int64_t stride,
                       const int32_t* pt, int32_t n_seqs, int32_t max_pages, const int32_t* slots,
                       const int32_t* append_lens, int32_t append_bound,
                       hipStream_t st) {
   StoreMfmaParams p;
-  p.codes[0] = c->k_codes; p.codes[1] = c->v_codes;
-  p.meta[0] = c->k_meta;   p.meta[1] = c->v_meta;
-  p.in[0] = K; p.in[1] = V;
+  for (int l = 0; l < n_layers; ++l) {
+    StoreLayerPtrs& lp = p.layer[l];
+    lp.codes[0] = c[l].k_codes; lp.codes[1] = c[l].v_codes;
+    lp.meta[0] = c[l].k_meta;   lp.meta[1] = c[l].v_meta;
+    lp.in[0] = K[l]; lp.in[1] = V[l];
+    lp.dense_limbs = c[l].dense_rot ? (const uint8_t*)c[l].dense_rot + kDenseLimbOffset : nullptr;
+  }
   p.page_table = pt; p.slots = slots; p.append_lens = append_lens; p.append_bound = append_bound; p.T = T; p.token_stride = stride;
   p.n_seqs = n_seqs; p.max_pages = max_pages; p.num_pages = c->num_pages; p.n_kv_heads = c->n_kv_heads;
   p.had_block = c->had_block;
@@ -279,13 +355,25 @@ int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt
   p.rot[1] = (c->had_block > 1) && (c->rotate_mask & SAW_ROT_V);
   for (int i = 0; i < 4; ++i) p.signs.w[i] = c->sign_bits[i];
   p.has_signs = (c->sign_bits[0] | c->sign_bits[1] | c->sign_bits[2] | c->sign_bits[3]) != 0;
+  p.dense_on[0] = c->dense_rot && (c->rotate_mask & SAW_ROT_K);
+  p.dense_on[1] = c->dense_rot && (c->rotate_mask & SAW_ROT_V);
   const int D = c->head_dim;
   const int64_t tblocks = (T + 15) / 16;
   if (tblocks > 0x7fffffffLL) return SAW_EINVAL;
   const bool pair64 = D == 64 && (c->n_kv_heads % 2) == 0;      // two 64-channel heads per wavefront
   const int kblocks = (2 * (c->n_kv_heads / (pair64 ? 2 : 1)) + 3) / 4;
   if (kblocks > 65535) return SAW_EINVAL;
-  dim3 grid((unsigned)tblocks, kblocks), block(256);
+  dim3 grid((unsigned)tblocks, kblocks, n_layers), block(256);
+  // Block order.  With many (K|V, head) combinations per token (a token's K row of 4 KB or more: the MHA
+  // shape with 32 heads of 64) the blocks of one token group run next to each other, so that blocks in
+  // flight together read neighbouring pieces of the same input rows: 76.3 -> 69.7 us on the 32k-token MHA
+  // prefill.  With 2 KB rows (8 heads of 128) the token groups are the fastest index: 34.0 against 34.7 us.
+  p.kblocks = kblocks;
+  p.kinds_fastest = 0;
+  if (kblocks >= 8 && tblocks * kblocks < 0x7fffffffLL) {
+    p.kinds_fastest = 1;
+    grid = dim3((unsigned)(tblocks * kblocks), 1, n_layers);
+  }
   const int h = c->had_block;
   int xs = -1;                                                  // static stage count when K and V agree
   if (p.rot[0] == p.rot[1]) xs = !p.rot[0] ? 0 : (h >= 128 ? 2 : (h >= 64 ? 1 : 0));
@@ -302,7 +390,11 @@ int launch_store_mfma(const saw_cache_t* c, const void* K, const void* V, int dt
     case 1: case 2: rotate_quant_store_mfma_kernel<128, TT, 1, 2><<<grid, block, 0, st>>>(p); break;   \
     default: rotate_quant_store_mfma_kernel<128, TT, -1, 2><<<grid, block, 0, st>>>(p); break;         \
   }
-  if (pair64 && dt == SAW_BF16) { SAW_LAUNCH_PAIR(SAW_BF16) }
+  if (p.dense_on[0] || p.dense_on[1]) {                         // head_dim 128 (checked by the caller)
+    if (dt == SAW_BF16) rotate_quant_store_mfma_kernel<128, SAW_BF16, -1, 1, true><<<grid, block, 0, st>>>(p);
+    else rotate_quant_store_mfma_kernel<128, SAW_F16, -1, 1, true><<<grid, block, 0, st>>>(p);
+  }
+  else if (pair64 && dt == SAW_BF16) { SAW_LAUNCH_PAIR(SAW_BF16) }
   else if (pair64) { SAW_LAUNCH_PAIR(SAW_F16) }
   else if (D == 128 && dt == SAW_BF16) { SAW_LAUNCH(128, SAW_BF16) }
   else if (D == 128) { SAW_LAUNCH(128, SAW_F16) }

@@ -173,4 +173,45 @@ __device__ __forceinline__ void wave_lds_fwht128(float* x, int h, int lane) {
   }
 }
 
+// In-place x <- x M for NV vectors of 128 floats in LDS, run by one wavefront: out[v][j] =
+// sum_i x[v][i] M[i][j] with M a global fp32 [128][128] row-major matrix (the learned rotation of
+// App. A.3 or its transpose).  Lane j computes columns j and j + 64 of every vector (coalesced rows
+// of M, broadcast reads of x) with four partial sums per output (i mod 4), so that the rounding error
+// stays near that of a pairwise sum.
+template <int NV>
+__device__ __forceinline__ void wave_lds_matvec128(float* x, const float* __restrict__ M, int lane) {
+  float acc[NV][2][4];
+#pragma unroll
+  for (int v = 0; v < NV; ++v)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[v][c][u] = 0.f;
+#pragma unroll 4
+  for (int i0 = 0; i0 < 128; i0 += 4) {
+    float m0[4], m1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      m0[u] = M[(i0 + u) * 128 + lane];
+      m1[u] = M[(i0 + u) * 128 + 64 + lane];
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const f32x4 xv = *(const f32x4*)(x + v * 128 + i0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc[v][0][u] = fmaf(xv[u], m0[u], acc[v][0][u]);
+        acc[v][1][u] = fmaf(xv[u], m1[u], acc[v][1][u]);
+      }
+    }
+  }
+  wave_sync();                                               // every read of x is done
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    x[v * 128 + lane] = (acc[v][0][0] + acc[v][0][1]) + (acc[v][0][2] + acc[v][0][3]);
+    x[v * 128 + 64 + lane] = (acc[v][1][0] + acc[v][1][1]) + (acc[v][1][2] + acc[v][1][3]);
+  }
+  wave_sync();
+}
+
 }  // namespace saw

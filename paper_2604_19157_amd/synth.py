@@ -37,6 +37,7 @@ class Workload:
     v_chan_scale: np.ndarray        # [Hkv][d] float32
     rotate_mask: int = 3
     signs: np.ndarray | None = None     # [d] of +1 / -1: diagonal in front of the Hadamard matrix (None: plain)
+    dense: np.ndarray | None = None     # [d][d] float64 holding float32 values: a learned rotation's stand-in (None: none)
     extra: dict = field(default_factory=dict)
 
     @property
@@ -137,12 +138,21 @@ def make_workload(name: str, rep: int = 0, **over) -> Workload:
     return Workload(name=name, seed=seed, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_size=P,
                     had_block=h, dtype=dtype, seq_lens=seq_lens, page_table=pt, num_pages=num_pages,
                     k_chan_scale=ks, v_chan_scale=vs, rotate_mask=over.get("rotate_mask", 3),
-                    signs=random_signs(d, over["sign_seed"]) if over.get("sign_seed") is not None else None)
+                    signs=random_signs(d, over["sign_seed"]) if over.get("sign_seed") is not None else None,
+                    dense=random_orthogonal(d, over["dense_seed"]) if over.get("dense_seed") is not None else None)
 
 
 def random_signs(d: int, seed: int) -> np.ndarray:
     """d values of +1 / -1, half of them negative on average (the diagonal of a randomised Hadamard)."""
     return np.where(np.random.default_rng(int(seed)).random(d) < 0.5, -1.0, 1.0)
+
+
+def random_orthogonal(d: int, seed: int) -> np.ndarray:
+    """A seeded random orthogonal d x d matrix (QR of a Gaussian matrix, column signs fixed), rounded to
+    float32 and returned as float64, so that a float32 copy on the device holds exactly these values.
+    It stands in for a calibrated per-layer rotation, which this repository has no data to compute."""
+    Q, Rr = np.linalg.qr(np.random.default_rng(int(seed)).standard_normal((d, d)))
+    return (Q * np.sign(np.diag(Rr))).astype(np.float32).astype(np.float64)
 
 
 def _gen(seed: int, device) -> torch.Generator:

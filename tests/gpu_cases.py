@@ -12,7 +12,7 @@ from paper_2604_19157_amd import synth
 
 def fill_caches(w, saw, dev="cuda", chunk=4096, order_rng=None, with_ref=True):
     """Store every token of every sequence of `w`; returns (gpu cache, oracle cache, per-vector records)."""
-    cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, device=dev, signs=w.signs)
+    cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, device=dev, signs=w.signs, dense=w.dense)
     ref = O.new_cache(w.num_pages, w.n_kv_heads, w.page_size, w.head_dim) if with_ref else None
     pt = torch.from_numpy(w.page_table).to(dev)
     recs = []
@@ -28,7 +28,7 @@ def fill_caches(w, saw, dev="cuda", chunk=4096, order_rng=None, with_ref=True):
             saw.rotate_quant_store(cache, K.to(dev), V.to(dev), pt, torch.from_numpy(sl).to(dev))
             if with_ref:
                 r = O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), w.page_table, sl,
-                                         w.had_block, w.rotate_mask, return_prerounding=True, signs=w.signs)
+                                         w.had_block, w.rotate_mask, return_prerounding=True, signs=w.signs, dense=w.dense)
                 recs.append(r)
     torch.cuda.synchronize()
     return cache, ref, recs, pt
@@ -43,14 +43,14 @@ def oracle_fill(w, chunk=4096, seqs=None):
             p1 = min(L, p0 + chunk)
             K, V = synth.gen_kv(w, b, p0, p1)
             O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), w.page_table,
-                                 synth.slots_for(b, p0, p1), w.had_block, w.rotate_mask, signs=w.signs)
+                                 synth.slots_for(b, p0, p1), w.had_block, w.rotate_mask, signs=w.signs, dense=w.dense)
     return ref
 
 
 def upload_cache(ref, w, saw, dev="cuda", into=None, pages=None):
     """Copy an oracle cache's bytes into a device cache (a new one, or rows `pages` of `into`)."""
     cache = into if into is not None else saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block,
-                                                    w.rotate_mask, device=dev, signs=w.signs)
+                                                    w.rotate_mask, device=dev, signs=w.signs, dense=w.dense)
     for k in ("k_codes", "v_codes", "k_meta", "v_meta"):
         dst = getattr(cache, k)
         if pages is None:

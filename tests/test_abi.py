@@ -179,3 +179,39 @@ def test_rank_order_never_puts_an_empty_sequence_ahead_of_a_non_empty_one(saw):
         # the bound does not change the order as long as it clamps nothing
         if bound == 0 or bound > max(lens):
             assert order == saw.decode_rank_order(lens, max(lens) + 1 if max(lens) else 1)
+
+
+def test_store_layers_and_dense_rotation_reject_bad_arguments(saw):
+    L = saw.lib()
+    P = ctypes.c_void_p
+    n = 3
+    sts = (saw.SawCacheStruct * n)(*[_struct(saw) for _ in range(n)])
+    ptrs = (ctypes.c_void_p * n)(16, 16, 16)
+
+    def call(sts=sts, K=ptrs, V=ptrs, n=n, dt=1, T=4, stride=256, pt=16, slots=16):
+        return L.saw_rotate_quant_store_layers(sts, K, V, n, dt, T, stride, P(pt), 1, 4, P(slots), P(0))
+
+    assert call(T=0) == 0
+    assert call(n=0) == -1
+    mixed = (saw.SawCacheStruct * n)(_struct(saw), _struct(saw, had_block=64), _struct(saw))
+    assert call(sts=mixed) == -1                                      # layers must agree in the Hadamard block
+    mixed = (saw.SawCacheStruct * n)(_struct(saw), _struct(saw, num_pages=5), _struct(saw))
+    assert call(sts=mixed) == -1
+    mixed = (saw.SawCacheStruct * n)(_struct(saw), _struct(saw, dense_rot=16), _struct(saw))
+    assert call(sts=mixed) == -1                                      # a learned rotation for all layers or for none
+    assert call(K=(ctypes.c_void_p * n)(16, 0, 16)) == -2
+    assert call(K=(ctypes.c_void_p * n)(16, 8, 16)) == -1             # misaligned
+    assert call(slots=4) == -1
+    # learned rotation: head_dim 128 only, aligned buffers, big enough
+    assert L.saw_dense_rotation_bytes(128) == 224 * 1024 and L.saw_dense_rotation_bytes(64) == 0
+    assert L.saw_prepare_dense_rotation(P(16), 64, P(16), 1 << 20, P(0)) == -1
+    assert L.saw_prepare_dense_rotation(P(16), 128, P(16), 1000, P(0)) == -1
+    assert L.saw_prepare_dense_rotation(P(0), 128, P(16), 1 << 20, P(0)) == -2
+    assert L.saw_prepare_dense_rotation(P(16), 128, P(8), 1 << 20, P(0)) == -1
+    st = _struct(saw, head_dim=64, had_block=64, dense_rot=16)
+    assert L.saw_rotate_quant_store(ctypes.byref(st), P(16), P(16), 1, 4, 128, P(16), 1, 4, P(16), P(0)) == -1
+    st = _struct(saw, dense_rot=8)                                    # misaligned prepared buffer
+    assert L.saw_rotate_quant_store(ctypes.byref(st), P(16), P(16), 1, 4, 256, P(16), 1, 4, P(16), P(0)) == -1
+    # flatten cannot rotate a learned rotation back
+    st = _struct(saw, dense_rot=16)
+    assert L.saw_flatten_dequant(ctypes.byref(st), P(16), 4, 0, 0, 8, 1, 2, P(16), P(16), 256, P(0)) == -1

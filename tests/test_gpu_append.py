@@ -60,9 +60,9 @@ def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None):
     # oracle: store the new tokens (into the mapped table: an unmapped token is still attended to), then decode
     slots = np.stack([np.arange(B, dtype=np.int32), w.seq_lens.astype(np.int32)], 1)
     rec = O.rotate_quant_store(ref, Kn.float().numpy(), Vn.float().numpy(), w.page_table, slots, w.had_block,
-                               w.rotate_mask, return_prerounding=True, signs=w.signs)
+                               w.rotate_mask, return_prerounding=True, signs=w.signs, dense=w.dense)
     o_ref = O.paged_decode_attn(ref, q.float().numpy(), w.page_table, w.seq_lens + 1, w.had_block, w.rotate_mask,
-                                signs=w.signs)
+                                signs=w.signs, dense=w.dense)
 
     # (1) the appended token's bytes
     page, slot = rec["page"], rec["slot"]

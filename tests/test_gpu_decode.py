@@ -41,7 +41,7 @@ def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_
     o = o.float().cpu().numpy()
     qn = q.float().numpy()
     o_ref = O.paged_decode_attn(ref, qn, w.page_table, w.seq_lens, w.had_block, w.rotate_mask,
-                                sm_scale=sm_scale if sm_scale > 0 else None, signs=w.signs)
+                                sm_scale=sm_scale if sm_scale > 0 else None, signs=w.signs, dense=w.dense)
     err = parity.attn_error(o, o_ref)
     msg = f"[{w.name} B={w.batch} Hq={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} h={w.had_block} mask={w.rotate_mask} splits={num_splits}] err={err:.2e}"
     if end_to_end:

@@ -43,7 +43,7 @@ def _case(saw, w, unrotate, dtype, ranges=None):
                 continue
             k, v = saw.flatten_dequant(cache, pt, b, p0, p1, unrotate=unrotate, out_dtype=dtype)
             kr, vr = O.dequant_pages(ref, w.page_table, b, p0, p1, w.had_block, w.rotate_mask, unrotate=unrotate,
-                                     signs=w.signs)
+                                     signs=w.signs, dense=w.dense)
             tag = f"[{w.name} h={w.had_block} d={w.head_dim} mask={w.rotate_mask} unrot={unrotate} {dtype} seq {b} [{p0},{p1})]"
             _check(k, kr, dtype, tag + " K")
             _check(v, vr, dtype, tag + " V")

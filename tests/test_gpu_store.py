@@ -140,7 +140,7 @@ def test_dequant_pages(saw, name, kw, unrotate):
         for (p0, p1) in [(0, L), (5, min(L, 37)), (L - 1, L)]:
             k, v = saw.dequant_pages(cache, pt, b, p0, p1, unrotate=unrotate)
             kr, vr = O.dequant_pages(got, w.page_table, b, p0, p1, w.had_block, w.rotate_mask, unrotate=unrotate,
-                                     signs=w.signs)
+                                     signs=w.signs, dense=w.dense)
             for a, r in ((k, kr), (v, vr)):
                 a = a.cpu().numpy().astype(np.float64)
                 assert np.abs(a - r).max() <= 2e-6 * np.abs(r).max()
@@ -150,3 +150,83 @@ def test_dequant_pages(saw, name, kw, unrotate):
         k, v = saw.dequant_pages(cache, pt, 0, 0, int(w.seq_lens[0]), unrotate=True)
         s = got["k_meta"][..., 0].max()
         assert (k.cpu() - K.float()).abs().max() <= 0.51 * s * (w.head_dim ** 0.5)
+
+
+@pytest.mark.parametrize("n_layers,dense", [(3, False), (35, False), (2, True)])
+def test_store_layers_in_one_launch(saw, n_layers, dense):
+    """saw_rotate_quant_store_layers: every layer's cache holds exactly the bytes a per-layer call writes, and
+    (first and last layer) the oracle's codes under the store criterion.  35 layers go out as two launches.
+    With a learned rotation every layer has its own matrix."""
+    w = synth.make_workload("tiny", batch=2, seq_lens=[37, 16], had_block=64)
+    pt = torch.from_numpy(w.page_table).cuda()
+    Rs = [synth.random_orthogonal(128, 50 + l) if dense else None for l in range(n_layers)]
+    mk = lambda l: saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, dense=Rs[l])
+    multi = [mk(l) for l in range(n_layers)]
+    single = [mk(l) for l in range(n_layers)]
+    for b in range(w.batch):
+        L = int(w.seq_lens[b])
+        sl = torch.from_numpy(synth.slots_for(b, 0, L)).cuda()
+        KV = [synth.gen_kv(w, b + 100 * l, 0, L, device="cuda") for l in range(n_layers)]
+        saw.rotate_quant_store_layers(multi, [k for k, _ in KV], [v for _, v in KV], pt, sl)
+        for l in range(n_layers):
+            saw.rotate_quant_store(single[l], KV[l][0], KV[l][1], pt, sl)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        for k in ("k_codes", "v_codes", "k_meta", "v_meta"):
+            assert torch.equal(getattr(multi[l], k), getattr(single[l], k)), (l, k)
+    for l in (0, n_layers - 1):
+        ref = O.new_cache(w.num_pages, w.n_kv_heads, w.page_size, w.head_dim)
+        recs = []
+        for b in range(w.batch):
+            L = int(w.seq_lens[b])
+            K, V = synth.gen_kv(w, b + 100 * l, 0, L, device="cuda")
+            recs.append(O.rotate_quant_store(ref, K.float().cpu().numpy(), V.float().cpu().numpy(), w.page_table,
+                                             synth.slots_for(b, 0, L), w.had_block, w.rotate_mask,
+                                             return_prerounding=True, dense=Rs[l]))
+        res = gc.compare_store(gc.cache_to_numpy(multi[l], w), ref, recs)
+        parity.assert_store_ok(res)
+        assert res["untouched_ok"]
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_plain_store_on_the_vector_alu_matches_the_oracle(saw, dtype):
+    """The lean plain INT4 store that bench.py uses as a comparator: no rotation whatever the descriptor says,
+    codes under the store criterion, ragged token counts, tokens in arbitrary order."""
+    w = synth.make_workload("tiny", batch=3, seq_lens=[37, 16, 100], had_block=64, dtype=dtype)
+    cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask)
+    ref = O.new_cache(w.num_pages, w.n_kv_heads, w.page_size, w.head_dim)
+    pt = torch.from_numpy(w.page_table).cuda()
+    recs = []
+    rng = np.random.default_rng(3)
+    for b in range(w.batch):
+        L = int(w.seq_lens[b])
+        K, V = synth.gen_kv(w, b, 0, L)
+        sl = synth.slots_for(b, 0, L)
+        perm = rng.permutation(L)
+        K, V, sl = K[perm].contiguous(), V[perm].contiguous(), sl[perm]
+        saw.plain_quant_store_valu(cache, K.cuda(), V.cuda(), pt, torch.from_numpy(sl).cuda())
+        recs.append(O.rotate_quant_store(ref, K.float().numpy(), V.float().numpy(), w.page_table, sl, 1, 0,
+                                         return_prerounding=True))
+    torch.cuda.synchronize()
+    res = gc.compare_store(gc.cache_to_numpy(cache, w), ref, recs)
+    parity.assert_store_ok(res)
+    assert res["untouched_ok"]
+
+
+def test_read_probe_reads_every_listed_tile_once(saw):
+    """The read-only probe behind bench.py's streaming ceiling: the XOR of the words it hands back equals the
+    XOR of every dword of the listed pages' K/V code tiles and (scale, zero) pairs (a multiple of four pages:
+    nothing is read twice), whatever the page order."""
+    w = synth.make_workload("tiny", batch=2, ctx=200)
+    cache, _, _, _ = gc.fill_caches(w, saw, with_ref=False)
+    pages = np.concatenate([w.page_table[b, :12] for b in range(2)]).astype(np.int32)      # 24 pages
+    sink = torch.zeros(2048, dtype=torch.int32, device="cuda")
+    n = saw.read_probe(cache, torch.from_numpy(pages).cuda(), sink)
+    torch.cuda.synchronize()
+    assert n == 24 * w.n_kv_heads * 2304
+    want = 0
+    for t in (cache.k_codes, cache.v_codes, cache.k_meta, cache.v_meta):
+        a = t.cpu().numpy()[pages].reshape(-1).view(np.uint32)
+        want ^= int(np.bitwise_xor.reduce(a))
+    got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+    assert got == want
