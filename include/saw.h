@@ -210,6 +210,36 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
                           saw_stream_t stream);
 
 /*
+ * Optional hints for the decode calls.  `order`: a device array of B int32, a permutation of 0..B-1 that
+ * lists the sequences longest first (ties in any order; sequences without cached tokens LAST - the
+ * schedule of a large batch relies on that).  A serving engine knows its lengths on the host and can keep
+ * this order at no cost; with it the kernels of a large batch skip their own length ranking (the first
+ * microseconds of every wavefront).  Entries outside [0, B) are clamped; an order that is not a permutation
+ * or not sorted gives unbalanced work or wrong rows, never an out-of-bounds access.  The order is only
+ * read where the launch needs one (one partition per sequence and more than 256 (sequence, kv head)
+ * items); hints == NULL or order == NULL: the kernels rank the sequences themselves, which is what
+ * saw_paged_decode_attn / saw_append_decode_attn do.  Everything else as in those calls.
+ */
+typedef struct saw_decode_hints {
+  const int32_t* order;
+} saw_decode_hints_t;
+
+int saw_paged_decode_attn_hinted(const saw_cache_t* cache, const void* q, int32_t q_dtype,
+                                 int32_t B, int32_t n_q_heads,
+                                 const int32_t* page_table, int32_t max_pages_per_seq,
+                                 const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                                 void* out, int32_t out_dtype,
+                                 void* workspace, size_t workspace_bytes, int32_t num_splits,
+                                 const saw_decode_hints_t* hints, saw_stream_t stream);
+
+int saw_append_decode_attn_hinted(const saw_cache_t* cache, const void* K_new, const void* V_new,
+                                  int32_t kv_dtype, const void* q, int32_t q_dtype, int32_t B,
+                                  int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                                  const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                                  int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                  const saw_decode_hints_t* hints, saw_stream_t stream);
+
+/*
  * saw_paged_decode_attn without a workspace argument, for callers that cannot allocate device
  * memory or carry a workspace around: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same kernels, same arguments and same results as saw_paged_decode_attn;

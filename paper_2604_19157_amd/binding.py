@@ -28,6 +28,10 @@ class SawCacheStruct(ctypes.Structure):
                 ("sign_bits", ctypes.c_uint32 * 4), ("dense_rot", ctypes.c_void_p)]
 
 
+class SawHints(ctypes.Structure):
+    _fields_ = [("order", ctypes.c_void_p)]
+
+
 class SawError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -63,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.saw_decode_rank_order.argtypes = [ctypes.POINTER(i32), i32, i32, ctypes.POINTER(i32)]
         L.saw_paged_decode_attn.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, vp]
         L.saw_paged_decode_attn_static.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, i32, vp]
+        hp = ctypes.POINTER(SawHints)
+        L.saw_paged_decode_attn_hinted.argtypes = [cp, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, i32, hp, vp]
+        L.saw_append_decode_attn_hinted.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz,
+                                                    hp, vp]
         L.saw_dequant_pages.argtypes = [cp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.saw_append_decode_attn.argtypes = [cp, vp, vp, i32, vp, i32, i32, i32, vp, i32, vp, i32, f32, vp, i32, vp, sz, vp]
         L.saw_flatten_dequant.argtypes = [cp, vp, i32, i32, i32, i32, i32, i32, vp, vp, ctypes.c_int64, vp]
@@ -211,8 +219,9 @@ def decode_rank_order(seq_lens, max_seq_len=0):
 
 
 def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,
-                      out_dtype=torch.float32, workspace=None, num_splits=0):
-    """saw_paged_decode_attn: q ``[B][Hq][d]``; returns ``out [B][Hq][d]``."""
+                      out_dtype=torch.float32, workspace=None, num_splits=0, order=None):
+    """saw_paged_decode_attn: q ``[B][Hq][d]``; returns ``out [B][Hq][d]``.  With ``order`` (int32 device
+    tensor, the sequences longest first) the call is saw_paged_decode_attn_hinted."""
     B, Hq, d = q.shape
     assert q.is_contiguous() and page_table.is_contiguous() and seq_lens.dtype == torch.int32
     bound = max_seq_len if max_seq_len > 0 else page_table.shape[1] * cache.page_size
@@ -222,6 +231,14 @@ def paged_decode_attn(cache: Cache, q, page_table, seq_lens, max_seq_len=0, sm_s
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     st = cache.struct()
+    if order is not None:
+        assert order.dtype == torch.int32 and order.numel() == B and order.is_contiguous()
+        hints = SawHints(order.data_ptr())
+        _check(lib().saw_paged_decode_attn_hinted(ctypes.byref(st), _ptr(q), _DT[q.dtype], B, Hq, _ptr(page_table),
+                                                  page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
+                                                  _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
+                                                  num_splits, ctypes.byref(hints), _stream()), "saw_paged_decode_attn_hinted")
+        return out
     _check(lib().saw_paged_decode_attn(ctypes.byref(st), _ptr(q), _DT[q.dtype], B, Hq, _ptr(page_table),
                                        page_table.shape[1], _ptr(seq_lens), max_seq_len, float(sm_scale),
                                        _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(),
@@ -243,7 +260,7 @@ def paged_decode_attn_static(cache: Cache, q, page_table, seq_lens, out, max_seq
 
 
 def append_decode_attn(cache: Cache, K_new, V_new, q, page_table, seq_lens, max_seq_len=0, sm_scale=0.0, out=None,
-                       out_dtype=torch.float32, workspace=None):
+                       out_dtype=torch.float32, workspace=None, order=None):
     """saw_append_decode_attn: K_new, V_new ``[B][Hkv][d]`` (token b -> sequence b at position
     seq_lens[b]), q ``[B][Hq][d]``; stores the tokens and returns ``out [B][Hq][d]`` of the attention
     over seq_lens[b] + 1 tokens.  seq_lens (tokens cached before the call) is not modified."""
@@ -258,6 +275,15 @@ def append_decode_attn(cache: Cache, K_new, V_new, q, page_table, seq_lens, max_
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     st = cache.struct()
+    if order is not None:
+        assert order.dtype == torch.int32 and order.numel() == B and order.is_contiguous()
+        hints = SawHints(order.data_ptr())
+        _check(lib().saw_append_decode_attn_hinted(ctypes.byref(st), _ptr(K_new), _ptr(V_new), _DT[K_new.dtype], _ptr(q),
+                                                   _DT[q.dtype], B, Hq, _ptr(page_table), page_table.shape[1], _ptr(seq_lens),
+                                                   max_seq_len, float(sm_scale), _ptr(out), _DT[out.dtype], _ptr(workspace),
+                                                   workspace.numel(), ctypes.byref(hints), _stream()),
+               "saw_append_decode_attn_hinted")
+        return out
     _check(lib().saw_append_decode_attn(ctypes.byref(st), _ptr(K_new), _ptr(V_new), _DT[K_new.dtype], _ptr(q),
                                         _DT[q.dtype], B, Hq, _ptr(page_table), page_table.shape[1], _ptr(seq_lens),
                                         max_seq_len, float(sm_scale), _ptr(out), _DT[out.dtype], _ptr(workspace),

@@ -32,7 +32,7 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
                const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
                const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
                const SplitPlan& plan, const void* k_new, const void* v_new, int kv_new_dtype, int len_bias,
-               hipStream_t st);
+               const int32_t* order, hipStream_t st);
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -264,7 +264,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
                          const void* q, int32_t q_dtype, int32_t B, int32_t Hq, const int32_t* pt,
                          int32_t max_pages, const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
                          void* out, int32_t out_dtype, void* ws, size_t ws_bytes, int32_t num_splits,
-                         saw_stream_t stream) {
+                         const saw_decode_hints_t* hints, saw_stream_t stream) {
   if (!c) return SAW_ENULL;
   if (!shape_ok(c)) return SAW_EINVAL;
   if (!kv16 && !block_ok(c)) return SAW_EINVAL;
@@ -287,7 +287,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   const size_t need = partial_bytes(B, Hq, plan.num_splits, c->head_dim);
   if (ws_bytes < need) return SAW_EWORKSPACE;
   return run_decode(c, kv16, kp, vp, kv_dtype, q, q_dtype, B, Hq, pt, max_pages, seq_lens, sm_scale, out,
-                    out_dtype, ws, plan, nullptr, nullptr, 0, 0, (hipStream_t)stream);
+                    out_dtype, ws, plan, nullptr, nullptr, 0, 0, hints ? hints->order : nullptr, (hipStream_t)stream);
 }
 
 int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, int32_t B,
@@ -298,7 +298,18 @@ int saw_paged_decode_attn(const saw_cache_t* c, const void* q, int32_t q_dtype, 
   if (!c) return SAW_ENULL;
   return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
                        max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
-                       workspace_bytes, num_splits, stream);
+                       workspace_bytes, num_splits, nullptr, stream);
+}
+
+int saw_paged_decode_attn_hinted(const saw_cache_t* c, const void* q, int32_t q_dtype, int32_t B,
+                                 int32_t n_q_heads, const int32_t* page_table, int32_t max_pages_per_seq,
+                                 const int32_t* seq_lens, int32_t max_seq_len, float sm_scale, void* out,
+                                 int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                 int32_t num_splits, const saw_decode_hints_t* hints, saw_stream_t stream) {
+  if (!c) return SAW_ENULL;
+  return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
+                       max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
+                       workspace_bytes, num_splits, hints, stream);
 }
 
 // The device address of `scratch` on the current device, resolved once per device with that device
@@ -336,14 +347,14 @@ int saw_paged_decode_attn_static(const saw_cache_t* c, const void* q, int32_t q_
   // written by the decode pass of the same call)
   return decode_common(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, n_q_heads, page_table,
                        max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, ws,
-                       (size_t)SAW_STATIC_SCRATCH_BYTES, num_splits, stream);
+                       (size_t)SAW_STATIC_SCRATCH_BYTES, num_splits, nullptr, stream);
 }
 
-int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
-                           const void* q, int32_t q_dtype, int32_t B, int32_t Hq,
-                           const int32_t* page_table, int32_t max_pages, const int32_t* seq_lens,
-                           int32_t max_seq_len, float sm_scale, void* out, int32_t out_dtype,
-                           void* ws, size_t ws_bytes, saw_stream_t stream) {
+static int append_common(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
+                         const void* q, int32_t q_dtype, int32_t B, int32_t Hq,
+                         const int32_t* page_table, int32_t max_pages, const int32_t* seq_lens,
+                         int32_t max_seq_len, float sm_scale, void* out, int32_t out_dtype,
+                         void* ws, size_t ws_bytes, const saw_decode_hints_t* hints, saw_stream_t stream) {
   if (!c) return SAW_ENULL;
   if (!shape_ok(c) || !block_ok(c)) return SAW_EINVAL;
   if (kv_dtype != SAW_F16 && kv_dtype != SAW_BF16) return SAW_EINVAL;
@@ -375,7 +386,8 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
     // the cached range is [0, seq_lens[b]), bounded by max_seq_len as given
     plan.bound = (int)(after - 1);
     return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
-                      sm_scale, out, out_dtype, ws, plan, K_new, V_new, kv_dtype, 0, (hipStream_t)stream);
+                      sm_scale, out, out_dtype, ws, plan, K_new, V_new, kv_dtype, 0, hints ? hints->order : nullptr,
+                      (hipStream_t)stream);
   }
   // head_dim 64 outside the head-pair kernel: two launches from the same call: append (token b -> sequence b at seq_lens[b]),
   // then decode over seq_lens[b] + 1 tokens
@@ -383,7 +395,26 @@ int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* 
                               max_pages, nullptr, seq_lens, (int32_t)(after - 1), (hipStream_t)stream);
   if (rc != SAW_OK) return rc;
   return run_decode(c, false, c->k_codes, c->v_codes, 0, q, q_dtype, B, Hq, page_table, max_pages, seq_lens,
-                    sm_scale, out, out_dtype, ws, plan, nullptr, nullptr, 0, 1, (hipStream_t)stream);
+                    sm_scale, out, out_dtype, ws, plan, nullptr, nullptr, 0, 1, hints ? hints->order : nullptr,
+                    (hipStream_t)stream);
+}
+
+int saw_append_decode_attn(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
+                           const void* q, int32_t q_dtype, int32_t B, int32_t Hq,
+                           const int32_t* page_table, int32_t max_pages, const int32_t* seq_lens,
+                           int32_t max_seq_len, float sm_scale, void* out, int32_t out_dtype,
+                           void* ws, size_t ws_bytes, saw_stream_t stream) {
+  return append_common(c, K_new, V_new, kv_dtype, q, q_dtype, B, Hq, page_table, max_pages, seq_lens, max_seq_len,
+                       sm_scale, out, out_dtype, ws, ws_bytes, nullptr, stream);
+}
+
+int saw_append_decode_attn_hinted(const saw_cache_t* c, const void* K_new, const void* V_new, int32_t kv_dtype,
+                                  const void* q, int32_t q_dtype, int32_t B, int32_t Hq,
+                                  const int32_t* page_table, int32_t max_pages, const int32_t* seq_lens,
+                                  int32_t max_seq_len, float sm_scale, void* out, int32_t out_dtype,
+                                  void* ws, size_t ws_bytes, const saw_decode_hints_t* hints, saw_stream_t stream) {
+  return append_common(c, K_new, V_new, kv_dtype, q, q_dtype, B, Hq, page_table, max_pages, seq_lens, max_seq_len,
+                       sm_scale, out, out_dtype, ws, ws_bytes, hints, stream);
 }
 
 int saw_dequant_pages(const saw_cache_t* c, const int32_t* page_table, int32_t max_pages_per_seq,
@@ -443,7 +474,7 @@ int saw_kv16_paged_decode_attn(const saw_cache_t* c, const void* k_pages, const 
                                int32_t num_splits, saw_stream_t stream) {
   return decode_common(c, true, k_pages, v_pages, dtype, q, q_dtype, B, n_q_heads, page_table,
                        max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, out_dtype, workspace,
-                       workspace_bytes, num_splits, stream);
+                       workspace_bytes, num_splits, nullptr, stream);
 }
 
 }  // extern "C"

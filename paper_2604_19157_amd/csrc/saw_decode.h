@@ -27,6 +27,7 @@ struct DecodeParams {
   int32_t sorted;           // matrix-core path, one block per (sequence, kv head): block z takes the sequence of length rank z
   int32_t pair;             // matrix-core path: blocks of this many wavefronts (2 or 4) over (long, short) sequence pairs; 0: off
   int32_t pair_seqs;        // matrix-core path, pair mode: sequences per block, 2 or (with pair == 4) 3
+  const int32_t* order;     // matrix-core INT4 path: the caller's longest-first order of the sequences, or null (ranked in the kernel)
   int32_t batch;
   int32_t waves_per_item;   // matrix-core path: wavefronts sharing one partition (1, 2 or 4)
   const float* dense;       // learned rotation R_l (App. A.3): fp32 [128][128], its transpose right behind it; null: none

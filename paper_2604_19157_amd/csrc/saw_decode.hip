@@ -471,8 +471,9 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
                const void* q, int q_dtype, int B, int Hq, const int32_t* pt, int max_pages,
                const int32_t* seq_lens, float sm_scale, void* out, int out_dtype, void* ws,
                const SplitPlan& plan, const void* k_new, const void* v_new, int kv_new_dtype, int len_bias,
-               hipStream_t st) {
+               const int32_t* order, hipStream_t st) {
   DecodeParams p;
+  p.order = kv16 ? nullptr : order;
   p.k_codes = (const uint8_t*)k_pages;
   p.v_codes = (const uint8_t*)v_pages;
   p.k_meta = c->k_meta;

@@ -127,30 +127,33 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
   qmul_out = qmul;
 }
 
+constexpr int kMetaBytesOf(bool hp) { return hp ? 2048 : 1024; }   // one batch's (scale, zero) pairs: K, then V
+
 // The decode step's own token (fused append, Sec. 4.1's "new KV entries are rotated, quantised
 // and written" folded into the attention launch): rotate, quantise and store the new K and V
 // vectors of (sequence b, kv head kvh) at position L exactly as the store kernel would (Sec. 3
-// eqs. 1-3, App. A.1), and start the softmax state from that token: its logit against the rotated
-// query is the reference maximum, its weight 1 is the running sum, its dequantised V row the
-// accumulator.  The cached tokens [0, L) are then streamed as usual, so nothing this launch
-// writes is read back by it.  One wavefront, two channels per lane.
+// eqs. 1-3, App. A.1), and place its codes and (scale, zero) pairs in LDS as token 0 of page 0 of a
+// batch, in the layout the transfers produce.  The caller then runs one more batch in which only that
+// token is valid, so the new token goes through the very code path of the cached ones (same q~ limbs,
+// same softmax update) and nothing this launch writes to the cache is read back by it.  All of this
+// happens at the END of the range that starts the sequence, when every transfer of the range has
+// landed: at the start of a launch all wavefronts of the chip run their prologues at once and are
+// bound by instruction issue, while later the vector ALU has slack under the memory traffic.
+// One wavefront, two channels per lane.
 //   pid, wk, wv  page id of position L and this lane's two channels of the new K and V vectors,
-//         loaded by the caller early enough that nothing here waits for memory
-//   qrot  LDS, [G][128]: the (rotated) query rows before scaling; qmul their scale
-//   scr   LDS scratch of 272 floats (16-byte aligned), distinct from qrot
+//         loaded by the caller at the start of the range
+//   scr   LDS scratch of 256 floats (16-byte aligned) that no buffer below overlaps
+//   kdst, vdst, mdst  the K buffer, a V buffer and its metadata buffer
 // HP: the 128 values are the new vectors of two neighbouring 64-channel kv heads (lanes 0-31 hold
 // the first head's channels), quantised and stored per head; `kvh` counts pairs.
-template <int G, int NH, bool HP, bool DN>
+template <int G, bool HP, bool DN>
 __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int lane, int L, int pid,
-                                             uint32_t wk, uint32_t wv,
-                                             const float* __restrict__ qrot, float qmul,
-                                             float* __restrict__ scr, f32x4 (&oacc)[8],
-                                             float (&m_ref)[NH], float (&lsum)[NH]) {
+                                             uint32_t wk, uint32_t wv, float* __restrict__ scr,
+                                             uint8_t* __restrict__ kdst, uint8_t* __restrict__ vdst,
+                                             uint8_t* __restrict__ mdst) {
   constexpr int D = 128;
   constexpr int DH = HP ? 64 : 128;  // channels of one head
-  const int row16 = lane & 15, grp = lane >> 4;
-  float* const yb = scr;            // [2][128]: K and V for the rotation, then [128] the dequantised V row
-  float* const lg = scr + 256;      // [G]: logits of the new token
+  float* const yb = scr;            // [2][128]: K and V for the rotation
   const int slot = L & 15;
   const bool place = pid >= 0 && pid < p.num_pages;          // otherwise attended to but not stored
   const int head = HP ? 2 * kvh + (lane >> 5) : kvh;         // kv head of this lane's two channels
@@ -185,7 +188,7 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     }
     const f32x2 yk = *(const f32x2*)(yb + 2 * lane), yv = *(const f32x2*)(yb + D + 2 * lane);
     x[0][0] = yk.x; x[0][1] = yk.y; x[1][0] = yv.x; x[1][1] = yv.y;
-    wave_sync();                                             // yb is rewritten below
+    wave_sync();
   }
   // min and max over each head's values (128: all lanes, 64: half of them): reductions of
   // (max, -min) pairs, rows first (DPP)
@@ -204,7 +207,6 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
       nmn[w] = max_xor32(nmn[w]);
     }
   }
-  float d[2][2];
 #pragma unroll
   for (int w = 0; w < 2; ++w) {
     const float norm = rot[w] ? had_norm(p.had_block) : 1.0f;
@@ -224,36 +226,19 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     }
     const float c0 = __builtin_amdgcn_fmed3f(rintf(x[w][0] * inv) + zq, 0.0f, 15.0f);
     const float c1 = __builtin_amdgcn_fmed3f(rintf(x[w][1] * inv) + zq, 0.0f, 15.0f);
+    const uint8_t byte = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
+    const bool meta_lane = (lane & (DH / 2 - 1)) == 0;        // lane 0 (and lane 32 for the pair's second head)
     if (place) {
       uint8_t* codes = const_cast<uint8_t*>(w ? p.v_codes : p.k_codes);
       float* meta = const_cast<float*>(w ? p.v_meta : p.k_meta);
-      codes[vec * (DH / 2) + (lane & (DH / 2 - 1))] = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
-      if ((lane & (DH / 2 - 1)) == 0) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
+      codes[vec * (DH / 2) + (lane & (DH / 2 - 1))] = byte;
+      if (meta_lane) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
     }
-    d[w][0] = s_store * (c0 - z_store);
-    d[w][1] = s_store * (c1 - z_store);
-  }
-  // the new token's logits against the rotated query rows, and its dequantised V row
-  *(f32x2*)(yb + 2 * lane) = f32x2{d[1][0], d[1][1]};
-#pragma unroll
-  for (int j = 0; j < G; ++j) {
-    const f32x2 qq = *(const f32x2*)(qrot + j * D + 2 * lane);
-    float part = fmaf(qq.x, d[0][0], qq.y * d[0][1]);
-    part = row_allsum(part);
-    part = add_xor16(part);
-    part = add_xor32(part);
-    if (lane == 0) lg[j] = part * qmul;
-  }
-  wave_sync();
-  const int head0 = (G > 4) ? 4 * (grp & 1) : 0;
-  const bool writer = (G > 4) ? (grp < 2) : (grp == 0);
-  const bool counts = (G > 4) ? (lane == 0 || lane == 16) : (lane == 0);   // one lane per head group holds the weight
-#pragma unroll
-  for (int i = 0; i < NH; ++i) {
-    m_ref[i] = lg[head0 + i];
-    lsum[i] = counts ? 1.0f : 0.0f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) oacc[c][i] = (writer && i < G) ? yb[16 * c + row16] : 0.0f;
+    // token 0 of page 0 of the batch: its 64 code bytes are the first 64 bytes of the tile (chunk Q of
+    // token 0 sits at chunk position Q), its pairs the first of the metadata block (head pair: one per head)
+    (w ? vdst : kdst)[lane] = byte;
+    if (meta_lane)
+      *(f32x2*)(mdst + (w ? kMetaBytesOf(HP) / 2 : 0) + (HP ? 128 * (lane >> 5) : 0)) = f32x2{s_store, z_store};
   }
   wave_sync();
 }
@@ -357,7 +342,6 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     const int B = p.batch;
     if (threadIdx.x < 4) done_cnt[threadIdx.x] = 0;
     __syncthreads();                                    // nothing in flight yet: a plain barrier is fine here
-    const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
     // the block's sequences by length rank, longest first; rank >= B: no such sequence
     int rk[K], nbk[K], stk[K];
     bool present[K];
@@ -369,12 +353,27 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       rk[0] = blockIdx.z; rk[1] = 2 * n3 - 1 - rk[0]; rk[K - 1] = 2 * n3 + rk[0];
       present[0] = true; present[1] = rk[1] < B; present[K - 1] = rk[K - 1] < B;
     }
+    if (p.order) {
+      // the caller supplied the longest-first order: two dependent loads per sequence instead of the ranking
+      int oi[K], raw[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      bk[k] = present[k] ? seq_of_rank(lane, lc, rk[k]) : 0;
-      lk[k] = present[k] ? lc.lens[bk[k]] : 0;
-      nbk[k] = (lk[k] + 63) >> 6;
+      for (int k = 0; k < K; ++k) oi[k] = present[k] ? p.order[rk[k]] : 0;
+#pragma unroll
+      for (int k = 0; k < K; ++k) bk[k] = min(max(oi[k], 0), B - 1);
+#pragma unroll
+      for (int k = 0; k < K; ++k) raw[k] = present[k] ? p.seq_lens[bk[k]] : 0;
+#pragma unroll
+      for (int k = 0; k < K; ++k) lk[k] = present[k] ? max(min(raw[k] + p.len_bias, p.bound), 0) : 0;
+    } else {
+      const LenClasses lc = build_len_classes(p, B, lane, (int*)kbuf);
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        bk[k] = present[k] ? seq_of_rank(lane, lc, rk[k]) : 0;
+        lk[k] = present[k] ? lc.lens[bk[k]] : 0;
+      }
     }
+#pragma unroll
+    for (int k = 0; k < K; ++k) nbk[k] = (lk[k] + 63) >> 6;
     // Shares of the sequences' batches laid end to end: wavefront w takes [T w / NW, T (w+1) / NW).
     // A wavefront that gets the end of one sequence and the start of the next pays another
     // prologue, about the time of two or three batches: that cost sits in front of every sequence
@@ -429,8 +428,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     // one block per (sequence, kv head), more blocks than fit the chip at once: blocks are dispatched
     // in index order as earlier ones finish, so taking the sequences longest first leaves the
     // shortest for the end of the launch
-    const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
-    bk[0] = seq_of_rank(lane, lc, blockIdx.z);
+    if (p.order) {
+      bk[0] = min(max(p.order[blockIdx.z], 0), p.batch - 1);
+    } else {
+      const LenClasses lc = build_len_classes(p, p.batch, lane, (int*)kbuf);
+      bk[0] = seq_of_rank(lane, lc, blockIdx.z);
+    }
     wave_sync();
   }
 
@@ -597,9 +600,6 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // query scratch: up to G = 4 in the P buffer (no transfer ever targets it), else the second V
   // buffer for the rows (first written by the second batch's transfers, which leave after this)
   float* const qrows = (G <= 4) ? (float*)pbuf : (float*)vbuf_b;
-  // fused append scratch (272 floats): the second V buffer is idle until the first batch's body
-  // requests the second batch; with G = 8 it holds the query rows and the P buffer is free instead
-  float* const ascr = (G <= 4) ? (float*)vbuf_b : (float*)pbuf;
   u32x4 a_q[4];
   float qsum[NH];
   float qmul;
@@ -624,19 +624,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   float m_ref[NH], lsum[NH], zs[NH];
 #pragma unroll
   for (int i = 0; i < NH; ++i) { m_ref[i] = -INFINITY; lsum[i] = 0.f; zs[i] = 0.f; }
-  if (takes_new)
-    append_token<G, NH, HP, DN>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, qrows, qmul,
-                            ascr, oacc, m_ref, lsum);
 
-  // One batch.  On entry the transfers of batch bi (V into vcur, K into kb, metadata) are the
-  // only ones this wavefront has in flight.
+  // One batch, whose first token is position tok0 of the sequence.  On entry the transfers of batch bi
+  // (V into vcur, K into kb, metadata) are the only ones this wavefront has in flight.
   // The buffers come in as __restrict__ parameters: after inlining that gives the LDS accesses
   // and the LDS-DMA transfers distinct alias scopes, so the compiler's own wait-count insertion
   // does not drain the prefetch before reading a buffer no transfer is writing.  Correctness
   // does not rest on that analysis: the explicit vmcnt(0) below covers everything batch bi needs.
-  auto body = [&](const int bi, uint8_t* __restrict__ const kb, uint8_t* __restrict__ const vcur,
+  auto body = [&](const int bi, const int tok0, uint8_t* __restrict__ const kb, uint8_t* __restrict__ const vcur,
                   uint8_t* __restrict__ const vnext, uint8_t* __restrict__ const pb,
-                  uint8_t* __restrict__ const mcur, uint8_t* __restrict__ const mnext) {
+                  uint8_t* __restrict__ const mcur, uint8_t* __restrict__ const mnext) __attribute__((always_inline)) {
     // (issued through the builtin, not inline asm, so that the compiler's wait-count pass sees it
     // and stops guarding earlier loads, e.g. the q~ operands, with waits of its own further down)
     __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): batch bi has landed (codes in LDS, metadata)
@@ -697,7 +694,6 @@ void decode_int4_mfma_kernel(DecodeParams p) {
       }
     }
     // ---- softmax with a lazily updated reference maximum ----
-    const int tok0 = t_begin + 64 * bi;
     float lg[NS][NH];
     bool valid[NS];
     bool need = false;
@@ -772,8 +768,8 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   };
   for (int bi = first_batch; bi < nb; bi += 2 * STEP) {
-    body(bi, kbuf, vbuf_a, vbuf_b, pbuf, mbuf_a, mbuf_b);
-    if (bi + STEP < nb) body(bi + STEP, kbuf, vbuf_b, vbuf_a, pbuf, mbuf_b, mbuf_a);
+    body(bi, t_begin + 64 * bi, kbuf, vbuf_a, vbuf_b, pbuf, mbuf_a, mbuf_b);
+    if (bi + STEP < nb) body(bi + STEP, t_begin + 64 * (bi + STEP), kbuf, vbuf_b, vbuf_a, pbuf, mbuf_b, mbuf_a);
   }
 
   // A wavefront without a batch of its own (first_batch >= nb) still has the prologue's transfers of
@@ -781,6 +777,16 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // have landed first: without this wait a transfer can arrive after the scratch has been written
   // and overwrite it.
   __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+
+  // Fused append: the step's new token is quantised and stored now, placed in the (idle) buffers as
+  // token 0 of a batch, and attended to by one more pass of the batch code in which only that token is
+  // valid (tok0 = t_end - 1: only position tok0 + 0 lies below t_end; the batch index is past the range,
+  // so nothing is requested).
+  if (takes_new) {
+    append_token<G, HP, DN>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (float*)vbuf_b, kbuf, vbuf_a, mbuf_a);
+    body(0x3fffffff, t_end - 1, kbuf, vbuf_a, vbuf_b, pbuf, mbuf_a, mbuf_b);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // (the new token's stores to the cache)
+  }
 
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
   if (!PAIR && NW > 1) {

@@ -36,7 +36,7 @@ def _new_tokens(w):
     return torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
 
 
-def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None):
+def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None, order=None):
     """`unmapped`: sequences whose new token's page is taken out of the page table (attended, not stored).
     `max_seq_len`: the host-side bound handed to the call (None: the longest sequence; 0: the default)."""
     B = w.batch
@@ -52,7 +52,8 @@ def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None):
     out = torch.full((B, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
     before = gc.cache_to_numpy(cache, w)
     saw.append_decode_attn(cache, Kn.cuda(), Vn.cuda(), q.cuda(), pt, lens,
-                           max_seq_len=int(w.seq_lens.max()) if max_seq_len is None else max_seq_len, out=out)
+                           max_seq_len=int(w.seq_lens.max()) if max_seq_len is None else max_seq_len, out=out,
+                           order=None if order is None else torch.from_numpy(np.asarray(order, np.int32)).cuda())
     torch.cuda.synchronize()
     assert torch.equal(lens.cpu(), torch.from_numpy(w.seq_lens))              # lengths are the caller's to advance
     got = gc.cache_to_numpy(cache, w)
@@ -112,6 +113,16 @@ def test_large_ragged_batch_pair_mode(saw, B, Hkv):
     lens[:6] = [0, 329, 1, 16, 15, 64]                       # empty, page boundaries, batch boundary
     w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv)
     _case(saw, w)
+
+
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (150, 8), (200, 8), (300, 8)])
+def test_caller_supplied_order(saw, B, Hkv):
+    """saw_append_decode_attn_hinted: the same step with the longest-first order supplied by the caller."""
+    rng = np.random.default_rng(B + 2)
+    lens = rng.integers(0, 330, size=B)
+    lens[:6] = [0, 329, 1, 16, 15, 64]
+    w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv)
+    _case(saw, w, order=np.argsort(-lens, kind="stable"))
 
 
 @pytest.mark.parametrize("h,mask", [(1, 3), (16, 3), (32, 3), (64, 3), (128, 3), (64, 1), (64, 2)])

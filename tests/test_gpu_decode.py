@@ -20,7 +20,7 @@ def saw():
 
 
 def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_dtype=None, end_to_end=True,
-                 max_seq_len=None):
+                 max_seq_len=None, order=None):
     """Criterion: both sides attend over the SAME bytes, the ones the oracle's store wrote (uploaded to
     the device cache), so the decode kernel is compared with the oracle independently of the store.
     `max_seq_len`: the host-side bound handed to the call (None: the longest sequence; 0: the call's
@@ -34,6 +34,8 @@ def _decode_case(saw, w, num_splits=0, out_dtype=torch.float32, sm_scale=0.0, q_
     sl = torch.from_numpy(w.seq_lens).cuda()
     kw = dict(max_seq_len=int(w.seq_lens.max()) if max_seq_len is None else max_seq_len, sm_scale=sm_scale,
               out_dtype=out_dtype, num_splits=num_splits)
+    if order is not None:               # the caller's longest-first order (saw_paged_decode_attn_hinted)
+        kw["order"] = torch.from_numpy(np.asarray(order, np.int32)).cuda()
     # the output starts as NaN: a row the path never writes fails the comparison
     o = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=out_dtype, device="cuda")
     saw.paged_decode_attn(cache, q.cuda(), pt, sl, out=o, **kw)
@@ -233,6 +235,27 @@ def test_random_shapes(saw, seed):
     kw, splits = _random_case(seed)
     w = synth.make_workload("highconc", **kw)
     _decode_case(saw, w, num_splits=splits, end_to_end=False)
+
+
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (150, 8), (191, 8), (200, 8), (255, 8), (300, 8), (383, 4)])
+def test_caller_supplied_order(saw, B, Hkv):
+    """saw_paged_decode_attn_hinted: the longest-first order comes from the caller (a stable host sort of the
+    lengths, empty sequences last) and the kernels skip their own ranking: pair blocks of two and of four,
+    blocks over three sequences, and the longest-first single-wavefront order."""
+    rng = np.random.default_rng(B + 1)
+    lens = rng.integers(0, 330, size=B)
+    lens[rng.integers(0, B, size=B // 5)] = 64
+    lens[:3] = [0, 329, 1]
+    w = synth.make_workload("highconc", batch=B, seq_lens=lens, n_q_heads=4 * Hkv, n_kv_heads=Hkv)
+    order = np.argsort(-lens, kind="stable")
+    o, _ = _decode_case(saw, w, num_splits=1, end_to_end=False, order=order)
+    assert not o[lens == 0].any()
+    # entries outside [0, B) are clamped: nothing out of bounds, whatever the rows hold
+    cache = gc.upload_cache(gc.oracle_fill(w), w, saw)
+    bad = torch.from_numpy(np.where(np.arange(B) % 7 == 0, 10 ** 6, order).astype(np.int32)).cuda()
+    saw.paged_decode_attn(cache, synth.gen_q(w).cuda(), torch.from_numpy(w.page_table).cuda(),
+                          torch.from_numpy(w.seq_lens).cuda(), max_seq_len=int(lens.max()), num_splits=1, order=bad)
+    torch.cuda.synchronize()
 
 
 LOOSE_WIDTH = 2048          # page-table columns of a table sized for 32768-token contexts

@@ -107,17 +107,18 @@ def test_decode_full_size(saw, name, n_sample, out_dtype, over):
     assert (np.abs(o[nonempty]).max(axis=(1, 2)) > 0).all()
 
 
-@pytest.mark.parametrize("name,over", [("highconc", {}), ("llama8b", {}),
-                                       ("highconc", dict(head_dim=64, had_block=64))])
-def test_append_decode_full_size(saw, name, over):
+@pytest.mark.parametrize("name,over,hint", [("highconc", {}, True), ("highconc", {}, False), ("llama8b", {}, False),
+                                            ("highconc", dict(head_dim=64, had_block=64), True)])
+def test_append_decode_full_size(saw, name, over, hint):
     """The step bench.py times: saw_append_decode_attn on the whole workload in the bench's launch shape
     (bf16 K/V/q, fp32 output, the bound at the longest sequence).  Every sequence's output against the oracle
     (2e-3; a sequence whose new token took a code the boundary rule exempts: the loose composed bound), every
-    appended token's codes and metadata under the store criterion, nothing else in the cache changed."""
+    appended token's codes and metadata under the store criterion, nothing else in the cache changed.
+    `hint`: with the caller's longest-first order, as bench.py calls it (saw_append_decode_attn_hinted)."""
     import test_gpu_append as TA
     w = synth.make_workload(name, **over)
     print(f"[{name} {over}] B={w.batch} tokens={w.total_tokens}", flush=True)
-    TA._case(saw, w)
+    TA._case(saw, w, order=np.argsort(-w.seq_lens, kind="stable") if hint else None)
 
 
 @pytest.mark.parametrize("name", ["prefill", "prefill_mha"])
