@@ -551,6 +551,14 @@ int run_decode(const saw_cache_t* c, bool kv16, const void* k_pages, const void*
     else if ((int64_t)B * items >= 1152 && blocks <= 1024) p.pair = 2;   // (whatever the plan's wavefronts per item)
     else if (plan.waves_per_item == 1 && (int64_t)B * items > 256) {
       if (blocks <= 1024) p.pair = 2;
+      else if ((int64_t)B * items <= 2304 && blocks3 <= 1024 && !(c->head_dim == 64 && G == 4)) {
+        // just above 2048 items: blocks of two wavefronts over THREE sequences keep everything resident
+        // (equal lengths, where the longest-first order has nothing to reorder and the last 32 items ran
+        // alone: 260 x 8 sequences of 2304 tokens 165 -> 135 us; ragged batches 137-148 us either way up
+        // to 288 x 8; from 320 x 8 on the longest-first order is ahead: 155 against 166 us)
+        p.pair = 2;
+        p.pair_seqs = 3;
+      }
       else p.sorted = 1;
     }
   }

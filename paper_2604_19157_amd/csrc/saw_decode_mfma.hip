@@ -313,8 +313,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // per-object ones and then orders every LDS access behind every transfer).
   constexpr int kRecFloats = G * 128 + 2 * G;                   // a record: accumulator rows, then (max, sum) per row
   constexpr int K = PAIR ? PK : 1;                              // sequences of a pair-mode block
-  static_assert(PK == 2 || (PK == 3 && NW == 4), "three sequences per block go with four wavefronts");
-  constexpr int kSpareBytes = (PAIR && NW > 2) ? (K - 1) * kRecFloats * 4 : 0;
+  static_assert(PK == 2 || PK == 3, "a block takes two or three sequences");
+  // (a wavefront can hold the head of a shared sequence and, after it, an earlier sequence of the block
+  // only when the block has more than two wavefronts or more than two sequences: then that record
+  // needs a slot outside the wavefront's own buffers)
+  constexpr bool kSpare = PAIR && (NW > 2 || K > 2);
+  constexpr int kSpareBytes = kSpare ? (K - 1) * kRecFloats * 4 : 0;
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[NW * kWaveLds + 16 + kSpareBytes];
   uint8_t* const kbuf = lds_all + wave * kWaveLds;
   uint8_t* const vbuf_a = kbuf + 4 * kTileBytes;
@@ -863,7 +867,7 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // block's spare slot when this wavefront still has its share of the long sequence to stream.
   float* const fb = (float*)vbuf_a;
   // (a shared range that is not this wavefront's last is the start of sequence sq >= 1)
-  const bool to_spare = PAIR && NW > 2 && emode == kSegShare && seg != nseg - 1;
+  const bool to_spare = kSpare && emode == kSegShare && seg != nseg - 1;
   float* const rec = to_spare ? spare_rec + (sq - 1) * kRecFloats : fb;
   float* const ml = rec + G * D;
   wave_sync();
@@ -987,6 +991,10 @@ static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_
   if constexpr (!(HP && G == 8)) {       // (two such blocks of head pairs with eight query rows would not fit LDS)
     if (p.pair == 4 && p.pair_seqs == 3) {
       decode_int4_mfma_kernel<G, 4, true, HP, 3, DN><<<dim3(1, grid.y, (B + 2) / 3), dim3(256), 0, st>>>(p);
+      return;
+    }
+    if (p.pair == 2 && p.pair_seqs == 3) {
+      decode_int4_mfma_kernel<G, 2, true, HP, 3, DN><<<dim3(1, grid.y, (B + 2) / 3), dim3(128), 0, st>>>(p);
       return;
     }
   }

@@ -106,7 +106,7 @@ def test_small_batch_one_launch(saw):
     _case(saw, synth.make_workload("tiny"))
 
 
-@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (150, 8), (191, 8), (200, 8), (300, 8)])
+@pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (150, 8), (191, 8), (200, 8), (300, 8), (260, 8), (288, 8)])
 def test_large_ragged_batch_pair_mode(saw, B, Hkv):
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)

@@ -91,12 +91,13 @@ def test_ragged_lengths_with_empty_and_single(saw):
 
 
 @pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (300, 2), (65, 8), (130, 8), (162, 8), (191, 8), (383, 4),
-                                   (200, 8), (255, 8), (300, 8)])
+                                   (200, 8), (255, 8), (300, 8), (257, 8), (260, 8), (288, 8), (575, 4)])
 def test_many_sequences_balanced_item_order(saw, B, Hkv):
     """More (sequence, kv head) items than compute units: the kernel pairs long with short sequences
     (everything resident at once: blocks of four wavefronts per pair from 576 to 1024 items, the first
     four cases, blocks of four over three sequences up to 1536 items, the next four, blocks of two up to
-    2048 items) or, beyond that, takes them longest first.  Every sequence is
+    2048 items, blocks of two over three sequences up to 2304 items, the last four) or, beyond that, takes
+    them longest first.  Every sequence is
     compared, so an item served twice or never shows up; lengths include empty sequences and many ties."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, 330, size=B)
@@ -283,6 +284,18 @@ def test_empty_sequences_under_a_loose_bound(saw, lens, Hkv):
                             table_width=8192)
     o, _ = _decode_case(saw, w, end_to_end=False, max_seq_len=0)
     assert not o[np.asarray(lens) == 0].any()
+
+
+@pytest.mark.parametrize("lens", [[0] * 260, [1] * 270, [64] * 200 + [0] * 60, [200] * 3 + [1] * 257, [300, 10, 5] * 90,
+                                  [129] * 90 + [64] * 90 + [0] * 90, list(range(288)), [128] * 259,
+                                  [64 * (i % 4) for i in range(277)], [257] * 130 + [3] * 130, [40, 200, 200] * 88])
+def test_blocks_of_two_over_three_sequences(saw, lens):
+    """2049..2304 items: a block of two wavefronts takes three sequences laid end to end; the one cut between
+    the two shares falls in any of them (a wavefront that holds the head of a shared sequence and an earlier
+    sequence after it leaves that record in the block's spare slot), in a gap, or nowhere (empty sequences)."""
+    w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens)
+    _decode_case(saw, w, end_to_end=False)
+    _decode_case(saw, w, end_to_end=False, order=np.argsort(-np.asarray(lens), kind="stable"))
 
 
 @pytest.mark.parametrize("lens", [[0] * 150, [1] * 150, [64] * 100 + [0] * 50, [200] * 3 + [1] * 147,
