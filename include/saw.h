@@ -29,7 +29,7 @@
  *     is physical page page_table[b][i]; logical position p sits in logical page
  *     p / page_size at slot p % page_size.
  *   - Query head j reads kv head j / (n_q_heads / n_kv_heads).
- *   - Alignment: code pools, K/V inputs, read-back outputs and workspaces 16 bytes; the metadata
+ *   - Alignment: code pools, K/V inputs, attention and read-back outputs and workspaces 16 bytes; the metadata
  *     pools 8 bytes for the store and 16 bytes for the decode calls (which fetch the pairs with
  *     16-byte transfers); anything else is SAW_EINVAL.
  *   - Supported: page_size 16; head_dim 64 or 128; had_block 1 (no rotation), 16, 32,

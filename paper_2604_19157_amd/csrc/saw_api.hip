@@ -278,7 +278,7 @@ static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const 
   if (!(G == 1 || G == 2 || G == 4 || G == 8)) return SAW_EINVAL;
   if (!kp || !vp || !q || !pt || !seq_lens || !out || !ws) return SAW_ENULL;
   if (!kv16 && (!c->k_meta || !c->v_meta)) return SAW_ENULL;
-  if (!aligned16(kp) || !aligned16(vp) || !aligned16(ws)) return SAW_EINVAL;
+  if (!aligned16(kp) || !aligned16(vp) || !aligned16(ws) || !aligned16(out)) return SAW_EINVAL;
   // (the INT4 kernels fetch the (scale, zero) pairs with 16-byte transfers)
   if (!kv16 && (!aligned16(c->k_meta) || !aligned16(c->v_meta))) return SAW_EINVAL;
   if (!isfinite(sm_scale)) return SAW_EINVAL;
@@ -368,7 +368,7 @@ static int append_common(const saw_cache_t* c, const void* K_new, const void* V_
       !seq_lens || !out || !ws)
     return SAW_ENULL;
   if (!aligned16(K_new) || !aligned16(V_new) || !aligned16(c->k_codes) || !aligned16(c->v_codes) ||
-      !aligned16(ws) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
+      !aligned16(ws) || !aligned16(out) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
     return SAW_EINVAL;
   if (!isfinite(sm_scale) || max_seq_len < 0) return SAW_EINVAL;
   // the plan covers the lengths after the append (max_seq_len + 1 tokens)

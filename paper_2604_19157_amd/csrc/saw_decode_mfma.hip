@@ -129,10 +129,32 @@ __device__ __forceinline__ void prepare_q(const DecodeParams& p, const float (&q
 
 constexpr int kMetaBytesOf(bool hp) { return hp ? 2048 : 1024; }   // one batch's (scale, zero) pairs: K, then V
 
+// (what append_token leaves for append_store: this lane's code byte and (scale, zero) pair of K and of V,
+// the token's vector index in the pools, and whether its page is mapped)
+struct NewToken {
+  uint32_t byte[2];
+  f32x2 meta[2];
+  int64_t vec;
+  bool place;
+};
+// The stores of the new token to the cache pools.  They are issued after the batch that attends to the
+// token (which needs nothing from memory), so that no part of the step waits for them.
+template <bool HP>
+__device__ __forceinline__ void append_store(const DecodeParams& p, int lane, const NewToken& nt) {
+  constexpr int DH = HP ? 64 : 128;
+  if (!nt.place) return;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    uint8_t* codes = const_cast<uint8_t*>(w ? p.v_codes : p.k_codes);
+    float* meta = const_cast<float*>(w ? p.v_meta : p.k_meta);
+    codes[nt.vec * (DH / 2) + (lane & (DH / 2 - 1))] = (uint8_t)nt.byte[w];
+    if ((lane & (DH / 2 - 1)) == 0) *(f32x2*)(meta + nt.vec * 2) = nt.meta[w];
+  }
+}
 // The decode step's own token (fused append, Sec. 4.1's "new KV entries are rotated, quantised
-// and written" folded into the attention launch): rotate, quantise and store the new K and V
-// vectors of (sequence b, kv head kvh) at position L exactly as the store kernel would (Sec. 3
-// eqs. 1-3, App. A.1), and place its codes and (scale, zero) pairs in LDS as token 0 of page 0 of a
+// and written" folded into the attention launch): rotate and quantise the new K and V vectors of
+// (sequence b, kv head kvh) for position L exactly as the store kernel would (Sec. 3 eqs. 1-3,
+// App. A.1; append_store writes them to the pools), and place its codes and (scale, zero) pairs in LDS as token 0 of page 0 of a
 // batch, in the layout the transfers produce.  The caller then runs one more batch in which only that
 // token is valid, so the new token goes through the very code path of the cached ones (same q~ limbs,
 // same softmax update) and nothing this launch writes to the cache is read back by it.  All of this
@@ -150,14 +172,14 @@ template <int G, bool HP, bool DN>
 __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int lane, int L, int pid,
                                              uint32_t wk, uint32_t wv, float* __restrict__ scr,
                                              uint8_t* __restrict__ kdst, uint8_t* __restrict__ vdst,
-                                             uint8_t* __restrict__ mdst) {
+                                             uint8_t* __restrict__ mdst, NewToken& nt) {
   constexpr int D = 128;
   constexpr int DH = HP ? 64 : 128;  // channels of one head
   float* const yb = scr;            // [2][128]: K and V for the rotation
   const int slot = L & 15;
-  const bool place = pid >= 0 && pid < p.num_pages;          // otherwise attended to but not stored
+  nt.place = pid >= 0 && pid < p.num_pages;                  // otherwise attended to but not stored
   const int head = HP ? 2 * kvh + (lane >> 5) : kvh;         // kv head of this lane's two channels
-  const int64_t vec = ((int64_t)pid * p.n_kv_heads + head) * 16 + slot;
+  nt.vec = ((int64_t)pid * p.n_kv_heads + head) * 16 + slot;
   // K and V go through every step together (index 0: K, 1: V): one two-vector transform instead of
   // two single ones, and reductions that overlap each other
   const bool rot[2] = {p.rot_k != 0, p.rot_v != 0};                                // block Hadamard
@@ -228,12 +250,8 @@ __device__ __forceinline__ void append_token(const DecodeParams& p, int kvh, int
     const float c1 = __builtin_amdgcn_fmed3f(rintf(x[w][1] * inv) + zq, 0.0f, 15.0f);
     const uint8_t byte = (uint8_t)((uint32_t)c0 | ((uint32_t)c1 << 4));
     const bool meta_lane = (lane & (DH / 2 - 1)) == 0;        // lane 0 (and lane 32 for the pair's second head)
-    if (place) {
-      uint8_t* codes = const_cast<uint8_t*>(w ? p.v_codes : p.k_codes);
-      float* meta = const_cast<float*>(w ? p.v_meta : p.k_meta);
-      codes[vec * (DH / 2) + (lane & (DH / 2 - 1))] = byte;
-      if (meta_lane) *(f32x2*)(meta + vec * 2) = f32x2{s_store, z_store};
-    }
+    nt.byte[w] = byte;
+    nt.meta[w] = f32x2{s_store, z_store};
     // token 0 of page 0 of the batch: its 64 code bytes are the first 64 bytes of the tile (chunk Q of
     // token 0 sits at chunk position Q), its pairs the first of the metadata block (head pair: one per head)
     (w ? vdst : kdst)[lane] = byte;
@@ -787,9 +805,10 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   // valid (tok0 = t_end - 1: only position tok0 + 0 lies below t_end; the batch index is past the range,
   // so nothing is requested).
   if (takes_new) {
-    append_token<G, HP, DN>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (float*)vbuf_b, kbuf, vbuf_a, mbuf_a);
+    NewToken nt;
+    append_token<G, HP, DN>(p, kvh, lane, seq_len_b, new_pid, new_wk, new_wv, (float*)vbuf_b, kbuf, vbuf_a, mbuf_a, nt);
     body(0x3fffffff, t_end - 1, kbuf, vbuf_a, vbuf_b, pbuf, mbuf_a, mbuf_b);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                    // (the new token's stores to the cache)
+    append_store<HP>(p, lane, nt);                         // (nobody waits for these: see append_store)
   }
 
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
@@ -927,29 +946,45 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     }
   }
   wave_sync();
-  // combine and normalise into this wavefront's buffer (element by element: a record that lives
-  // there is read before it is overwritten, and its (max, sum) pairs sit behind the rows)
-  for (int idx = lane; idx < G * D; idx += 64) {
-    const int h = idx >> 7;
-    float v = recs[0][idx], l0 = recs[0][G * D + 2 * h + 1];
-    if (PAIR && nrec > 1) {
-      float mm = recs[0][G * D + 2 * h];
+  // combine and normalise into this wavefront's buffer.  The weight of record r for head h, the
+  // denominator already divided in, is the same in every lane and is worked out first (the (max, sum)
+  // pairs sit behind the rows of a record and are read before anything is overwritten); then element by
+  // element, in place where the record lives in this buffer.
+  float wgt[NW][G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    float mr[NW], lr[NW];
+#pragma unroll
+    for (int r = 0; r < NW; ++r) {
+      mr[r] = (r < nrec) ? recs[r][G * D + 2 * h] : -INFINITY;
+      lr[r] = (r < nrec) ? recs[r][G * D + 2 * h + 1] : 0.f;
+    }
+    float mm = mr[0];
+#pragma unroll
+    for (int r = 1; r < NW; ++r) mm = fmaxf(mm, mr[r]);
+    float den = 0.f;
+#pragma unroll
+    for (int r = 0; r < NW; ++r) {
+      wgt[r][h] = (PAIR && nrec > 1) ? ((r < nrec) ? fast_exp2(mr[r] - mm) : 0.f) : (r == 0 ? 1.f : 0.f);
+      den = fmaf(wgt[r][h], lr[r], den);
+    }
+    const float inv = __builtin_amdgcn_rcpf(den);
+#pragma unroll
+    for (int r = 0; r < NW; ++r) wgt[r][h] *= inv;
+  }
+  wave_sync();
+#pragma unroll
+  for (int it = 0; it < G * D / 64; ++it) {
+    const int idx = lane + 64 * it;
+    constexpr int kPerHead = D / 64;                          // iterations per head
+    const int h = it / kPerHead;                              // compile-time after unrolling
+    float v = wgt[0][h] * recs[0][idx];
+    if (PAIR) {
 #pragma unroll
       for (int r = 1; r < NW; ++r)
-        if (r < nrec) mm = fmaxf(mm, recs[r][G * D + 2 * h]);
-      const float a0 = fast_exp2(recs[0][G * D + 2 * h] - mm);
-      v *= a0;
-      l0 *= a0;
-#pragma unroll
-      for (int r = 1; r < NW; ++r) {
-        if (r < nrec) {
-          const float ar = fast_exp2(recs[r][G * D + 2 * h] - mm);
-          v = fmaf(ar, recs[r][idx], v);
-          l0 = fmaf(ar, recs[r][G * D + 2 * h + 1], l0);
-        }
-      }
+        if (r < nrec) v = fmaf(wgt[r][h], recs[r][idx], v);
     }
-    fb[idx] = v / l0;
+    fb[idx] = v;
   }
   wave_sync();
   // rotate back once for V (App. A.4; a learned rotation's transpose first, App. A.3), write the output
@@ -962,14 +997,39 @@ void decode_int4_mfma_kernel(DecodeParams p) {
     onorm = had_norm(p.had_block);
   }
   const int64_t obase = ((int64_t)b * p.n_q_heads + kvh * G) * DH;
-  for (int i = lane; i < G * D; i += 64) {
-    float o = fb[i] * onorm;
-    if (p.rot_v && p.has_signs) o = apply_sign(p.signs, i & (DH - 1), o);      // (o~ H_blk) diag(sigma) = o~ R^T
-    if (HP) {                                    // a row's own 64 channels; the other half is cross terms
-      const int h = i >> 7, c = i & 127;
+  if (HP) {
+    for (int i = lane; i < G * D; i += 64) {
+      float o = fb[i] * onorm;
+      if (p.rot_v && p.has_signs) o = apply_sign(p.signs, i & (DH - 1), o);    // (o~ H_blk) diag(sigma) = o~ R^T
+      const int h = i >> 7, c = i & 127;           // a row's own 64 channels; the other half is cross terms
       if ((c >> 6) == h / GK) store_elem(p.out, p.out_dtype, obase + h * 64 + (c & 63), o);
-    } else {
-      store_elem(p.out, p.out_dtype, obase + i, o);
+    }
+  } else {
+    // four consecutive channels per lane: 16-byte (fp32) or 8-byte (16-bit) stores, whole rows per instruction
+#pragma unroll
+    for (int it = 0; it < (G * D + 255) / 256; ++it) {
+      const int i = 4 * (lane + 64 * it);
+      if (G * D % 256 != 0 && i >= G * D) break;             // (one query head: 32 lanes hold its row)
+      const f32x4 o4 = *(const f32x4*)(fb + i);
+      float o[4] = {o4.x * onorm, o4.y * onorm, o4.z * onorm, o4.w * onorm};
+      if (p.rot_v && p.has_signs) {                                            // (o~ H_blk) diag(sigma) = o~ R^T
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = apply_sign(p.signs, (i + e) & (DH - 1), o[e]);
+      }
+      if (p.out_dtype == SAW_F32) {
+        *(f32x4*)((float*)p.out + obase + i) = f32x4{o[0], o[1], o[2], o[3]};
+      } else {
+        uint32_t w0, w1;
+        if (p.out_dtype == SAW_BF16) {
+          w0 = f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+          w1 = f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+        } else {
+          w0 = f32_to_f16(o[0]) | ((uint32_t)f32_to_f16(o[1]) << 16);
+          w1 = f32_to_f16(o[2]) | ((uint32_t)f32_to_f16(o[3]) << 16);
+        }
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        *(u32x2_t*)((uint16_t*)p.out + obase + i) = u32x2_t{w0, w1};
+      }
     }
   }
   wave_sync();                                   // the next range's prologue reuses these buffers
