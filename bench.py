@@ -330,11 +330,13 @@ def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, with_appen
     ws = torch.empty(saw.decode_workspace_bytes(cache, w.batch, w.n_q_heads, max_len), dtype=torch.uint8, device=dev)
     splits, chunk = saw.decode_plan(cache, w.batch, max_len)
     turn = [0]
+    # the caller's longest-first order, as in the headline step (only read by the large-batch launch shapes)
+    order = torch.from_numpy(np.argsort(-lens, kind="stable").astype(np.int32)).to(dev) if w.batch > 1 else None
 
     def call():
         c = copies[turn[0] % len(copies)]
         turn[0] += 1
-        saw.paged_decode_attn(c, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws)
+        saw.paged_decode_attn(c, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws, order=order)
 
     res16 = None
     if with_kv16:
@@ -357,7 +359,7 @@ def other_decode(saw, dev, name, iters=32, warmup=8, with_kv16=False, with_appen
         def call_step():
             c = copies[turn[0] % len(copies)]
             turn[0] += 1
-            saw.append_decode_attn(c, newK, newV, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws2)
+            saw.append_decode_attn(c, newK, newV, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws2, order=order)
 
         step_us = time_calls(call_step, iters, warmup, settle=OTHER_SETTLE_S)[0]
     overhead = 2 * w.batch * w.n_q_heads * splits * (w.head_dim + 2) * 4 if splits > 1 else 0
