@@ -104,7 +104,10 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   const int kind = wave_live ? kind_raw : 0;                  // an idle wavefront shadows kind 0 and stores nothing
   const int which = kind >= n_heads_w ? 1 : 0;
   const int head = (kind - which * n_heads_w) * HP;           // (first) head of this wavefront
-  const int64_t t0 = tb_id * 16;
+  // DENSE: a wavefront takes NT = 2 consecutive 16-token tiles, so that one set of limb operands of R_l
+  // (96 KB per wavefront through L1) serves twice the tokens.
+  constexpr int NT = DENSE ? 2 : 1;
+  const int64_t t0 = tb_id * (16 * NT);
   const bool rot = p.rot[which] != 0;
   const StoreLayerPtrs& lp = p.layer[blockIdx.z];
 
@@ -112,21 +115,25 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
   uint8_t* const stage = stage_all[wave];
 
   // ---- issue the tile loads (coalesced: each 16-lane row reads 256 contiguous bytes) ----
-  u32x4 ld[NLD];
+  u32x4 ld[NT][NLD];
+  int2 slot[NT];
 #pragma unroll
-  for (int r = 0; r < NLD; ++r) {
-    const int off = r * 1024 + 16 * lane;                      // byte offset in the dense 16 x D tile
-    const int tok = off / ROWB, x = (off % ROWB) / 16;
-    const int64_t t = min(t0 + tok, p.T - 1);                  // tokens past the end shadow the last one; never stored
-    // (the input is read once and the cache written once: both are marked streaming, "nt")
-    ld[r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)lp.in[which] + t * p.token_stride + head * DH + 8 * x));
+  for (int tile = 0; tile < NT; ++tile) {
+#pragma unroll
+    for (int r = 0; r < NLD; ++r) {
+      const int off = r * 1024 + 16 * lane;                    // byte offset in the dense 16 x D tile
+      const int tok = off / ROWB, x = (off % ROWB) / 16;
+      const int64_t t = min(t0 + 16 * tile + tok, p.T - 1);    // tokens past the end shadow the last one; never stored
+      // (the input is read once and the cache written once: both are marked streaming, "nt")
+      ld[tile][r] = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)lp.in[which] + t * p.token_stride + head * DH + 8 * x));
+    }
+    // this lane's token (column n16 of the tile) and where it goes
+    const int64_t t_mine = t0 + 16 * tile + n16;
+    slot[tile] = make_int2(-1, -1);
+    if (wave_live && t_mine < p.T)
+      slot[tile] = p.slots ? *(const int2*)(p.slots + 2 * t_mine) : make_int2((int)t_mine, p.append_lens[t_mine]);
+    if (!p.slots && slot[tile].y > p.append_bound) slot[tile] = make_int2(-1, -1);
   }
-  // this lane's token (column n16 of the tile) and where it goes
-  const int64_t t_mine = t0 + n16;
-  int2 slot = make_int2(-1, -1);
-  if (wave_live && t_mine < p.T)
-    slot = p.slots ? *(const int2*)(p.slots + 2 * t_mine) : make_int2((int)t_mine, p.append_lens[t_mine]);
-  if (!p.slots && slot.y > p.append_bound) slot = make_int2(-1, -1);
 
   // ---- the +/-1 matrix: A[m][k], m = output row, k = input channel (low five bits) ----
   // MFMA #1 row m -> output channel (low five bits) 8*(m/4) + m%4, MFMA #2 row m -> that + 4,
@@ -153,78 +160,90 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
     ha2 = u32x4{e2[0] | (e2[1] << 16), e2[2] | (e2[3] << 16), e2[4] | (e2[5] << 16), e2[6] | (e2[7] << 16)};
   }
 
-  // ---- through LDS into the B-operand layout: column = token, k-group rg = chunk 4a + rg ----
-  // chunk x of token tok sits at chunk position x ^ ((tok / RP) & (XC-1)): both the row-wise
-  // writes and the column-wise reads below touch every bank once.
-  // Randomised Hadamard: x . diag(sigma) is a sign flip of the 16-bit inputs (exact), applied here
-  // because a lane's chunk index (lane % (ROWB / 16)) is the same for all of its loads: one mask.
+  // Randomised Hadamard: x . diag(sigma) is a sign flip of the 16-bit inputs (exact), applied at the
+  // staging step because a lane's chunk index (lane % (ROWB / 16)) is the same for all of its loads: one mask.
   u32x4 sflip = u32x4{0u, 0u, 0u, 0u};
   if (p.has_signs && rot) {                                     // wavefront-uniform
     uint32_t sx[4];
     sign_pairs(p.signs, (8 * (lane % (ROWB / 16))) % DH, sx);
     sflip = u32x4{sx[0], sx[1], sx[2], sx[3]};
   }
+
+  float y[NT][NV];                                              // y[.][8a + i]: channel 32a + 8rg + i of token n16
 #pragma unroll
-  for (int r = 0; r < NLD; ++r) {
-    const int off = r * 1024 + 16 * lane;
-    const int tok = off / ROWB, x = (off % ROWB) / 16;
-    *(u32x4*)(stage + tok * ROWB + 16 * (x ^ ((tok / RP) & (XC - 1)))) = ld[r] ^ sflip;
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  float y[NV];                                                  // y[8a + i]: channel 32a + 8rg + i of token n16
+  for (int tile = 0; tile < NT; ++tile) {
+    // ---- through LDS into the B-operand layout: column = token, k-group rg = chunk 4a + rg ----
+    // chunk x of token tok sits at chunk position x ^ ((tok / RP) & (XC-1)): both the row-wise
+    // writes and the column-wise reads below touch every bank once.
 #pragma unroll
-  for (int a = 0; a < NA; ++a) {
-    const int x = 4 * a + rg;
-    const u32x4 bv = *(const u32x4*)(stage + n16 * ROWB + 16 * (x ^ ((n16 / RP) & (XC - 1))));
-    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
-    const f32x4 d1 = mfma_pm1<DT>(ha1, bv, zero);
-    const f32x4 d2 = mfma_pm1<DT>(ha2, bv, zero);
+    for (int r = 0; r < NLD; ++r) {
+      const int off = r * 1024 + 16 * lane;
+      const int tok = off / ROWB, x = (off % ROWB) / 16;
+      *(u32x4*)(stage + tok * ROWB + 16 * (x ^ ((tok / RP) & (XC - 1)))) = ld[tile][r] ^ sflip;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { y[8 * a + i] = d1[i]; y[8 * a + 4 + i] = d2[i]; }
-  }
-  // ---- orders 64 / 128: butterflies across the 32-channel groups, now register to register ----
-  if (XS >= 1 || (XS < 0 && rot && p.had_block >= 64)) {
+    for (int a = 0; a < NA; ++a) {
+      const int x = 4 * a + rg;
+      const u32x4 bv = *(const u32x4*)(stage + n16 * ROWB + 16 * (x ^ ((n16 / RP) & (XC - 1))));
+      const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+      const f32x4 d1 = mfma_pm1<DT>(ha1, bv, zero);
+      const f32x4 d2 = mfma_pm1<DT>(ha2, bv, zero);
 #pragma unroll
-    for (int a = 0; a < NA; a += 2)
+      for (int i = 0; i < 4; ++i) { y[tile][8 * a + i] = d1[i]; y[tile][8 * a + 4 + i] = d2[i]; }
+    }
+    if (NT > 1) {                                               // the next tile's staging overwrites what was just read
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // ---- orders 64 / 128: butterflies across the 32-channel groups, now register to register ----
+    if (XS >= 1 || (XS < 0 && rot && p.had_block >= 64)) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float u = y[8 * a + i], v = y[8 * a + 8 + i];
-        y[8 * a + i] = u + v;
-        y[8 * a + 8 + i] = u - v;
-      }
-  }
-  if (D == 128 && (XS >= 2 || (XS < 0 && rot && p.had_block >= 128))) {
+      for (int a = 0; a < NA; a += 2)
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int i = 0; i < 8; ++i) {
+          const float u = y[tile][8 * a + i], v = y[tile][8 * a + 8 + i];
+          y[tile][8 * a + i] = u + v;
+          y[tile][8 * a + 8 + i] = u - v;
+        }
+    }
+    if (D == 128 && (XS >= 2 || (XS < 0 && rot && p.had_block >= 128))) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float u = y[8 * a + i], v = y[8 * a + 16 + i];
-        y[8 * a + i] = u + v;
-        y[8 * a + 16 + i] = u - v;
-      }
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float u = y[tile][8 * a + i], v = y[tile][8 * a + 16 + i];
+          y[tile][8 * a + i] = u + v;
+          y[tile][8 * a + 16 + i] = u - v;
+        }
+    }
   }
   if constexpr (DENSE) {
     if (p.dense_on[which]) {                                    // wavefront-uniform
       typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
       typedef float f32x2_t __attribute__((ext_vector_type(2)));
-      u32x4 bh[NA], bm[NA], bl[NA];                             // limbs of y as B operands, one per k-step (32 channels)
+      u32x4 bh[NT][NA], bm[NT][NA], bl[NT][NA];                 // limbs of y as B operands, one per k-step (32 channels)
 #pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        uint32_t wh[4], wm[4], wl[4];
+      for (int tile = 0; tile < NT; ++tile) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float y0 = y[8 * a + 2 * e], y1 = y[8 * a + 2 * e + 1];
-          wh[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{y0, y1}, bf16x2_t));
-          const float r0 = y0 - __uint_as_float(wh[e] << 16), r1 = y1 - __uint_as_float(wh[e] & 0xffff0000u);
-          wm[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{r0, r1}, bf16x2_t));
-          const float q0 = r0 - __uint_as_float(wm[e] << 16), q1 = r1 - __uint_as_float(wm[e] & 0xffff0000u);
-          wl[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{q0, q1}, bf16x2_t));
+        for (int a = 0; a < NA; ++a) {
+          uint32_t wh[4], wm[4], wl[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float y0 = y[tile][8 * a + 2 * e], y1 = y[tile][8 * a + 2 * e + 1];
+            wh[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{y0, y1}, bf16x2_t));
+            const float r0 = y0 - __uint_as_float(wh[e] << 16), r1 = y1 - __uint_as_float(wh[e] & 0xffff0000u);
+            wm[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{r0, r1}, bf16x2_t));
+            const float q0 = r0 - __uint_as_float(wm[e] << 16), q1 = r1 - __uint_as_float(wm[e] & 0xffff0000u);
+            wl[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{q0, q1}, bf16x2_t));
+          }
+          bh[tile][a] = u32x4{wh[0], wh[1], wh[2], wh[3]};
+          bm[tile][a] = u32x4{wm[0], wm[1], wm[2], wm[3]};
+          bl[tile][a] = u32x4{wl[0], wl[1], wl[2], wl[3]};
         }
-        bh[a] = u32x4{wh[0], wh[1], wh[2], wh[3]};
-        bm[a] = u32x4{wm[0], wm[1], wm[2], wm[3]};
-        bl[a] = u32x4{wl[0], wl[1], wl[2], wl[3]};
       }
       const u32x4* const A = (const u32x4*)lp.dense_limbs + lane;
 #pragma unroll
@@ -236,100 +255,111 @@ __global__ __launch_bounds__(256) void rotate_quant_store_mfma_kernel(StoreMfmaP
           am[a] = A[((1 * 8 + J) * 4 + a) * 64];
           al[a] = A[((2 * 8 + J) * 4 + a) * 64];
         }
-        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tile = 0; tile < NT; ++tile) {
+          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #define SAW_LIMB_PRODUCT(RA, YB)                                                                     \
   _Pragma("unroll") for (int a = 0; a < NA; ++a)                                                     \
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, RA[a]), __builtin_bit_cast(bf16x8, YB[a]), acc, 0, 0, 0);
-        SAW_LIMB_PRODUCT(al, bh)
-        SAW_LIMB_PRODUCT(ah, bl)
-        SAW_LIMB_PRODUCT(am, bm)
-        SAW_LIMB_PRODUCT(am, bh)
-        SAW_LIMB_PRODUCT(ah, bm)
-        SAW_LIMB_PRODUCT(ah, bh)
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, RA[a]), __builtin_bit_cast(bf16x8, YB[tile][a]), acc, 0, 0, 0);
+          SAW_LIMB_PRODUCT(al, bh)
+          SAW_LIMB_PRODUCT(ah, bl)
+          SAW_LIMB_PRODUCT(am, bm)
+          SAW_LIMB_PRODUCT(am, bh)
+          SAW_LIMB_PRODUCT(ah, bm)
+          SAW_LIMB_PRODUCT(ah, bh)
 #undef SAW_LIMB_PRODUCT
-        // tile J holds channels 32 (J / 2) + 8 rg + 4 (J % 2) + 0..3 of token n16
+          // tile J holds channels 32 (J / 2) + 8 rg + 4 (J % 2) + 0..3 of token n16
 #pragma unroll
-        for (int i = 0; i < 4; ++i) y[8 * (J >> 1) + 4 * (J & 1) + i] = acc[i];
+          for (int i = 0; i < 4; ++i) y[tile][8 * (J >> 1) + 4 * (J & 1) + i] = acc[i];
+        }
       }
     }
   }
   const float norm = rot ? had_norm(p.had_block) : 1.0f;
-
-  // ---- token-wise min / max per head: in-lane, then the four rows holding the same token ----
-  constexpr int NVH = NV / HP;                                // this lane's values of one head
-  float s_store[HP], z_store[HP];
-  uint32_t packed[NA];
-#pragma unroll
-  for (int hh = 0; hh < HP; ++hh) {
-    float mn = y[NVH * hh], mx = y[NVH * hh];
-#pragma unroll
-    for (int i = 1; i < NVH; ++i) { mn = fminf(mn, y[NVH * hh + i]); mx = fmaxf(mx, y[NVH * hh + i]); }
-    mn = fminf(mn, __shfl_xor(mn, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mn = fminf(mn, __shfl_xor(mn, 32, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-
-    // ---- scale / zero (App. A.1), quantise, pack ----
-    const float range = mx - mn;
-    float inv, zq;
-    if (range > 0.0f) {
-      inv = 15.0f / range;
-      s_store[hh] = range * (norm * (1.0f / 15.0f));
-      zq = rintf(-mn * inv);
-      z_store[hh] = zq;
-    } else {  // constant vector
-      inv = 0.0f;
-      zq = 0.0f;
-      s_store[hh] = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
-      z_store[hh] = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
-    }
-#pragma unroll
-    for (int a = (NA / HP) * hh; a < (NA / HP) * (hh + 1); ++a) {
-      uint32_t w = 0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float c = rintf(y[8 * a + i] * inv) + zq;
-        c = __builtin_amdgcn_fmed3f(c, 0.0f, 15.0f);
-        w |= ((uint32_t)c) << (4 * i);
-      }
-      packed[a] = w;                                            // dword 4 (a % (NA / HP)) + rg of the token's code row of head hh
-    }
-  }
   if (!wave_live) return;
 
-  // ---- paged placement ----
-  int32_t page = -1;
-  const bool slot_ok = slot.x >= 0 && slot.x < p.n_seqs && slot.y >= 0 && (slot.y >> 4) < p.max_pages;
-  if (slot_ok) page = p.page_table[(int64_t)slot.x * p.max_pages + (slot.y >> 4)];
-  const bool ok = slot_ok && page >= 0 && page < p.num_pages;
-  // fast path: the 16 tokens are the 16 slots of one page, in order
-  const int seq0 = __builtin_amdgcn_readfirstlane(slot.x);
-  const int pos0 = __builtin_amdgcn_readfirstlane(slot.y);
-  const bool aligned = __all(ok && slot.x == seq0 && slot.y == pos0 + n16) && ((pos0 & 15) == 0);
-  constexpr int NAH = NA / HP;                                // 32-channel groups of one head
-  if (aligned) {
-    const int page0 = __builtin_amdgcn_readfirstlane(page);
-    const int64_t vec0 = ((int64_t)page0 * p.n_kv_heads + head) * 16;
-    // transpose the code dwords through LDS so that every lane writes 16 contiguous bytes
-    // (a head pair's two tiles follow each other in the cache, so they leave as one run)
-    uint32_t* const ob = (uint32_t*)stage;                     // [head of the pair][token][DH/8 dwords]
 #pragma unroll
-    for (int a = 0; a < NA; ++a) ob[(a / NAH) * (16 * DH / 8) + n16 * (DH / 8) + 4 * (a % NAH) + rg] = packed[a];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (lane < 16 * (D / 2) / 16)
-      __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(lp.codes[which] + vec0 * (DH / 2) + 16 * lane));
+  for (int tile = 0; tile < NT; ++tile) {
+    // ---- token-wise min / max per head: in-lane, then the four rows holding the same token ----
+    constexpr int NVH = NV / HP;                                // this lane's values of one head
+    float s_store[HP], z_store[HP];
+    uint32_t packed[NA];
 #pragma unroll
-    for (int hh = 0; hh < HP; ++hh)
-      if (rg == hh) *(float2*)(lp.meta[which] + (vec0 + 16 * hh + n16) * 2) = make_float2(s_store[hh], z_store[hh]);
-    return;
-  }
-  if (!ok) return;
+    for (int hh = 0; hh < HP; ++hh) {
+      float mn = y[tile][NVH * hh], mx = y[tile][NVH * hh];
 #pragma unroll
-  for (int hh = 0; hh < HP; ++hh) {
-    const int64_t vec = ((int64_t)page * p.n_kv_heads + head + hh) * 16 + (slot.y & 15);
+      for (int i = 1; i < NVH; ++i) { mn = fminf(mn, y[tile][NVH * hh + i]); mx = fmaxf(mx, y[tile][NVH * hh + i]); }
+      mn = fminf(mn, __shfl_xor(mn, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mn = fminf(mn, __shfl_xor(mn, 32, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+      // ---- scale / zero (App. A.1), quantise, pack ----
+      const float range = mx - mn;
+      float inv, zq;
+      if (range > 0.0f) {
+        inv = 15.0f / range;
+        s_store[hh] = range * (norm * (1.0f / 15.0f));
+        zq = rintf(-mn * inv);
+        z_store[hh] = zq;
+      } else {  // constant vector
+        inv = 0.0f;
+        zq = 0.0f;
+        s_store[hh] = (mn != 0.0f) ? fabsf(mn) * norm : 1.0f;
+        z_store[hh] = (mn > 0.0f) ? -1.0f : ((mn < 0.0f) ? 1.0f : 0.0f);
+      }
 #pragma unroll
-    for (int a = NAH * hh; a < NAH * (hh + 1); ++a) ((uint32_t*)(lp.codes[which] + vec * (DH / 2)))[4 * (a % NAH) + rg] = packed[a];
-    if (rg == hh) *(float2*)(lp.meta[which] + vec * 2) = make_float2(s_store[hh], z_store[hh]);
+      for (int a = (NA / HP) * hh; a < (NA / HP) * (hh + 1); ++a) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float c = rintf(y[tile][8 * a + i] * inv) + zq;
+          c = __builtin_amdgcn_fmed3f(c, 0.0f, 15.0f);
+          w |= ((uint32_t)c) << (4 * i);
+        }
+        packed[a] = w;                                          // dword 4 (a % (NA / HP)) + rg of the token's code row of head hh
+      }
+    }
+
+    // ---- paged placement ----
+    const int2 sl = slot[tile];
+    int32_t page = -1;
+    const bool slot_ok = sl.x >= 0 && sl.x < p.n_seqs && sl.y >= 0 && (sl.y >> 4) < p.max_pages;
+    if (slot_ok) page = p.page_table[(int64_t)sl.x * p.max_pages + (sl.y >> 4)];
+    const bool ok = slot_ok && page >= 0 && page < p.num_pages;
+    // fast path: the 16 tokens are the 16 slots of one page, in order
+    const int seq0 = __builtin_amdgcn_readfirstlane(sl.x);
+    const int pos0 = __builtin_amdgcn_readfirstlane(sl.y);
+    const bool aligned = __all(ok && sl.x == seq0 && sl.y == pos0 + n16) && ((pos0 & 15) == 0);
+    constexpr int NAH = NA / HP;                                // 32-channel groups of one head
+    if (aligned) {                                              // wavefront-uniform
+      const int page0 = __builtin_amdgcn_readfirstlane(page);
+      const int64_t vec0 = ((int64_t)page0 * p.n_kv_heads + head) * 16;
+      // transpose the code dwords through LDS so that every lane writes 16 contiguous bytes
+      // (a head pair's two tiles follow each other in the cache, so they leave as one run)
+      uint32_t* const ob = (uint32_t*)stage;                   // [head of the pair][token][DH/8 dwords]
+#pragma unroll
+      for (int a = 0; a < NA; ++a) ob[(a / NAH) * (16 * DH / 8) + n16 * (DH / 8) + 4 * (a % NAH) + rg] = packed[a];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      if (lane < 16 * (D / 2) / 16)
+        __builtin_nontemporal_store(*(const u32x4*)(stage + 16 * lane), (u32x4*)(lp.codes[which] + vec0 * (DH / 2) + 16 * lane));
+#pragma unroll
+      for (int hh = 0; hh < HP; ++hh)
+        if (rg == hh) *(float2*)(lp.meta[which] + (vec0 + 16 * hh + n16) * 2) = make_float2(s_store[hh], z_store[hh]);
+      if (NT > 1) {                                             // the next tile's transposition reuses the buffer
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    } else if (ok) {
+#pragma unroll
+      for (int hh = 0; hh < HP; ++hh) {
+        const int64_t vec = ((int64_t)page * p.n_kv_heads + head + hh) * 16 + (sl.y & 15);
+#pragma unroll
+        for (int a = NAH * hh; a < NAH * (hh + 1); ++a) ((uint32_t*)(lp.codes[which] + vec * (DH / 2)))[4 * (a % NAH) + rg] = packed[a];
+        if (rg == hh) *(float2*)(lp.meta[which] + vec * 2) = make_float2(s_store[hh], z_store[hh]);
+      }
+    }
   }
 }
 
@@ -358,7 +388,8 @@ int launch_store_mfma(const saw_cache_t* c, const void* const* K, const void* co
   p.dense_on[0] = c->dense_rot && (c->rotate_mask & SAW_ROT_K);
   p.dense_on[1] = c->dense_rot && (c->rotate_mask & SAW_ROT_V);
   const int D = c->head_dim;
-  const int64_t tblocks = (T + 15) / 16;
+  const int tile_tokens = (p.dense_on[0] || p.dense_on[1]) ? 32 : 16;   // tokens per wavefront (the DENSE kernel takes two tiles)
+  const int64_t tblocks = (T + tile_tokens - 1) / tile_tokens;
   if (tblocks > 0x7fffffffLL) return SAW_EINVAL;
   const bool pair64 = D == 64 && (c->n_kv_heads % 2) == 0;      // two 64-channel heads per wavefront
   const int kblocks = (2 * (c->n_kv_heads / (pair64 ? 2 : 1)) + 3) / 4;
