@@ -79,6 +79,11 @@ static bool make_plan(const saw_cache_t* c, int B, int max_pages, int max_seq_le
     const int64_t max_by_min_chunk = (units + 3) / 4;      // partitions of >= 256 tokens
     if (s > max_by_min_chunk) s = max_by_min_chunk;
     if (!kv16 && items >= 512 && B <= 1024) s = 1;
+    // Very many partitions (a single long sequence): a quarter of them, each shared by four wavefronts
+    // that fold their states in LDS, leaves the merge pass a quarter of the partial records to write
+    // and read - as long as every wavefront keeps its 512 tokens (131072 tokens x 8 kv heads: 256
+    // partitions 40.0 us, 64 partitions of four wavefronts 37.8 us).
+    if (!kv16 && s > 64 && units / (s / 4) >= 32) s /= 4;
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
     S = (int)s;
