@@ -29,7 +29,7 @@ struct DecodeParams {
   int32_t pair_seqs;        // matrix-core path, pair mode: sequences per block, 2 or (with pair == 4) 3
   const int32_t* order;     // matrix-core INT4 path: the caller's longest-first order of the sequences, or null (ranked in the kernel)
   int32_t batch;
-  int32_t waves_per_item;   // matrix-core path: wavefronts sharing one partition (1, 2 or 4)
+  int32_t waves_per_item;   // matrix-core path: wavefronts sharing one partition (1, 2, 4 or 8)
   const float* dense;       // learned rotation R_l (App. A.3): fp32 [128][128], its transpose right behind it; null: none
   int32_t dense_k, dense_v; // R_l applies to K and the query / to V and the output
   int32_t has_signs;        // any bit of `signs` set

@@ -812,38 +812,71 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   }
 
   // ---- fold the wavefronts of the block together (wavefront 0 keeps the result) ----
+  // Every wavefront leaves its state in its own buffers; then all of them work on the fold together:
+  // each works out the common reference maximum and the NW weights per head, combines its own slice of
+  // the accumulator tiles over all wavefronts into wavefront 0's copy, and wavefront 0 combines the
+  // sums.  Two block barriers whatever NW is, instead of one pass per wavefront by wavefront 0 alone.
   if (!PAIR && NW > 1) {
+    static_assert(8 % NW == 0, "the accumulator tiles are dealt out evenly");
+    constexpr int CPW = 8 / NW;                             // accumulator tiles per wavefront
     float* const st = (float*)kbuf;                         // this wavefront's state: [j][lane]
-    if (wave > 0) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c)
+    for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st[(4 * c + i) * 64 + lane] = oacc[c][i];
+      for (int i = 0; i < 4; ++i) st[(4 * c + i) * 64 + lane] = oacc[c][i];
+#pragma unroll
+    for (int i = 0; i < NH; ++i) {
+      st[(32 + i) * 64 + lane] = m_ref[i];
+      st[(36 + i) * 64 + lane] = lsum[i];
+      st[(40 + i) * 64 + lane] = zs[i];
+    }
+    __syncthreads();
+    float aw[NW][NH];
+#pragma unroll
+    for (int i = 0; i < NH; ++i) {
+      float mw[NW];
+      float mm = -INFINITY;                                 // (wavefront 0 always has a batch: the maximum is finite)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        mw[w] = ((const float*)(lds_all + w * kWaveLds))[(32 + i) * 64 + lane];
+        mm = fmaxf(mm, mw[w]);
+      }
+#pragma unroll
+      for (int w = 0; w < NW; ++w) aw[w][i] = fast_exp2(mw[w] - mm);   // 0 for a wavefront that had no batch
+      m_ref[i] = mm;
+    }
+    float* const st0 = (float*)lds_all;                     // wavefront 0's state
+#pragma unroll
+    for (int cc = 0; cc < CPW; ++cc) {
+      const int c = wave * CPW + cc;
 #pragma unroll
       for (int i = 0; i < NH; ++i) {
-        st[(32 + i) * 64 + lane] = m_ref[i];
-        st[(36 + i) * 64 + lane] = lsum[i];
-        st[(40 + i) * 64 + lane] = zs[i];
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v = fmaf(aw[w][i], ((const float*)(lds_all + w * kWaveLds))[(4 * c + i) * 64 + lane], v);
+        st0[(4 * c + i) * 64 + lane] = v;                   // (only this wavefront touches tile c of that copy now)
+      }
+    }
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        float l = 0.f, z = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const float* so = (const float*)(lds_all + w * kWaveLds);
+          l = fmaf(aw[w][i], so[(36 + i) * 64 + lane], l);
+          z = fmaf(aw[w][i], so[(40 + i) * 64 + lane], z);
+        }
+        lsum[i] = l;
+        zs[i] = z;
       }
     }
     __syncthreads();
     if (wave > 0) return;
-#pragma unroll 1
-    for (int w = 1; w < NW; ++w) {
-      const float* so = (const float*)(lds_all + w * kWaveLds);
 #pragma unroll
-      for (int i = 0; i < NH; ++i) {
-        const float mo = so[(32 + i) * 64 + lane];
-        const float mnew = fmaxf(m_ref[i], mo);             // wavefront 0 always has a batch: finite
-        const float a0 = fast_exp2(m_ref[i] - mnew);
-        const float a1 = fast_exp2(mo - mnew);              // 0 for a wavefront that had no batch
-        lsum[i] = a0 * lsum[i] + a1 * so[(36 + i) * 64 + lane];
-        zs[i] = a0 * zs[i] + a1 * so[(40 + i) * 64 + lane];
+    for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) oacc[c][i] = a0 * oacc[c][i] + a1 * so[(4 * c + i) * 64 + lane];
-        m_ref[i] = mnew;
-      }
-    }
+      for (int i = 0; i < NH; ++i) oacc[c][i] = st[(4 * c + i) * 64 + lane];
   }
 
   // ---- epilogue: reduce the per-lane sums, fold hi + lo rows ----
@@ -1066,7 +1099,8 @@ static void launch_g(const DecodeParams& p, int B, int nw, dim3 grid, hipStream_
     decode_int4_mfma_kernel<G, 2, true, HP, 2, DN><<<dim3(1, grid.y, (B + 1) / 2), dim3(128), 0, st>>>(p);
     return;
   }
-  if (nw >= 4) decode_int4_mfma_kernel<G, 4, false, HP, 2, DN><<<grid, dim3(256), 0, st>>>(p);
+  if (nw >= 8) decode_int4_mfma_kernel<G, 8, false, HP, 2, DN><<<grid, dim3(512), 0, st>>>(p);
+  else if (nw >= 4) decode_int4_mfma_kernel<G, 4, false, HP, 2, DN><<<grid, dim3(256), 0, st>>>(p);
   else if (nw == 2) decode_int4_mfma_kernel<G, 2, false, HP, 2, DN><<<grid, dim3(128), 0, st>>>(p);
   else decode_int4_mfma_kernel<G, 1, false, HP, 2, DN><<<grid, dim3(64), 0, st>>>(p);
 }

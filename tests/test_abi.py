@@ -125,7 +125,11 @@ def test_plan_keeps_one_partition_from_512_items_on(saw):
     need = L.saw_decode_workspace_bytes(ctypes.byref(st), 64, 32, 4096, 0)
     assert need > 64 * 32 * 1 * 130 * 4                              # more than the one partition: the 16-bit call's
     st64 = _struct(saw, n_kv_heads=8, head_dim=64, had_block=64)
-    assert plan(st64, 128, 4096)[0] == 1 and plan(st64, 64, 4096)[0] > 1
+    assert plan(st64, 128, 4096)[0] == 1 and plan(st64, 64, 8192)[0] > 1
+    # small batches of short contexts: one partition (a block of eight wavefronts per item), up to five batches per
+    # wavefront, or eight when the blocks fill most of the chip; longer contexts go back to partitions
+    assert plan(st, 4, 2304)[0] == 1 and plan(st, 32, 4096)[0] == 1 and plan(st64, 64, 4096)[0] == 1
+    assert plan(st, 16, 4096)[0] > 1 and plan(st, 1, 8192)[0] > 1 and plan(st, 4, 2600)[0] > 1
     st64odd = _struct(saw, n_kv_heads=7, head_dim=64, had_block=64)
     assert plan(st64odd, 74, 4096)[0] == 1 and plan(st64odd, 73, 4096)[0] > 1
 

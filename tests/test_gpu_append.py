@@ -102,8 +102,17 @@ def _case(saw, w, out_dtype=torch.float32, unmapped=(), max_seq_len=None, order=
 
 
 def test_small_batch_one_launch(saw):
-    """B*Hkv <= 256: one wavefront per (sequence, kv head), fused in the kernel."""
+    """Small batches of short contexts: one block of eight wavefronts per (sequence, kv head), the whole step
+    in one launch: lengths that leave wavefronts of a block without a batch, empty sequences, ragged tails."""
     _case(saw, synth.make_workload("tiny"))
+    for lens in ([0, 1, 63, 64, 65, 500], [2304] * 4 + [0, 7], [1000, 1024, 512, 3, 130, 129, 128, 127]):
+        w = synth.make_workload("tiny", batch=len(lens), seq_lens=lens)
+        cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask)
+        assert saw.decode_plan(cache, w.batch, max(lens) + 1)[0] == 1
+        _case(saw, w)
+    _case(saw, synth.make_workload("longctx1", batch=3, seq_lens=[300, 0, 2000], had_block=64))      # G = 8
+    _case(saw, synth.make_workload("highconc", batch=5, seq_lens=[90, 0, 300, 64, 1], n_q_heads=8, n_kv_heads=4,
+                                   head_dim=64, had_block=64))                                           # head pairs
 
 
 @pytest.mark.parametrize("B,Hkv", [(70, 8), (129, 4), (150, 8), (191, 8), (200, 8), (300, 8), (260, 8), (288, 8)])
@@ -154,11 +163,12 @@ def test_several_partitions_with_lengths_on_partition_boundaries(saw):
     """The append inside the split-KV path: the partition that starts a sequence carries the new token
     and the merge takes exactly the partitions that ran -- also when the cached length is zero, sits
     exactly on a partition boundary, or one past it."""
-    w0 = synth.make_workload("tiny", batch=6, seq_lens=[0, 1, 192, 193, 384, 513])
+    longest = 2700                       # (long enough that the plan takes partitions, not one block of eight wavefronts)
+    w0 = synth.make_workload("tiny", batch=8, seq_lens=[0, 1, 192, 193, 384, 513, 700, longest])
     cache = saw.Cache(w0.num_pages, w0.n_kv_heads, w0.head_dim, w0.had_block, w0.rotate_mask)
-    splits, chunk = saw.decode_plan(cache, w0.batch, int(w0.seq_lens.max()) + 1)
+    splits, chunk = saw.decode_plan(cache, w0.batch, longest + 1)
     assert splits > 1
-    lens = [0, 1, chunk - 1, chunk, chunk + 1, 2 * chunk, min(2 * chunk + 1, 513)]
+    lens = [0, 1, chunk - 1, chunk, chunk + 1, 2 * chunk, 2 * chunk + 1, longest]
     w = synth.make_workload("tiny", batch=len(lens), seq_lens=lens)
     _case(saw, w)
     _case(saw, synth.make_workload("longctx1", batch=2, seq_lens=[700, 0], had_block=64))     # G = 8

@@ -108,6 +108,21 @@ def test_many_sequences_balanced_item_order(saw, B, Hkv):
     _decode_case(saw, w, num_splits=0, end_to_end=False)
 
 
+@pytest.mark.parametrize("lens,kw", [([0, 1, 63, 64, 65, 500], {}), ([2304] * 4 + [0, 7], {}), ([2500] * 30, {}),
+                                     ([1000, 1024, 512, 3, 130, 129, 128, 127] * 4, {}),
+                                     ([300, 0, 2000], dict(n_q_heads=64)),
+                                     ([90, 0, 300, 64, 1], dict(n_q_heads=8, n_kv_heads=4, head_dim=64, had_block=64)),
+                                     ([200, 40, 0], dict(dense_seed=3))])
+def test_small_batch_blocks_of_eight(saw, lens, kw):
+    """Small batches of short contexts: the plan takes one partition and one block of eight wavefronts per
+    (sequence, kv head); the wavefronts fold their states in LDS and the call is a single launch."""
+    w = synth.make_workload("tiny", batch=len(lens), seq_lens=lens, **kw)
+    cache = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask)
+    assert saw.decode_plan(cache, w.batch, max(lens))[0] == 1
+    _decode_case(saw, w, end_to_end=False)
+    _decode_case(saw, w, end_to_end=False, out_dtype=torch.bfloat16)
+
+
 def test_batch_beyond_the_ranking_limit(saw):
     """More than 1024 sequences: the in-kernel length ranking is not used (one wavefront per item)."""
     rng = np.random.default_rng(7)

@@ -45,7 +45,7 @@ def _run_both(saw, w, num_splits):
 
 def test_static_scratch_matches_workspace_call_twice_second_smaller(saw):
     # first call: several partitions per sequence, so the scratch holds partial results
-    s1 = _run_both(saw, synth.make_workload("llama8b", batch=5, ctx=(300, 1500)), num_splits=0)
+    s1 = _run_both(saw, synth.make_workload("llama8b", batch=5, ctx=(2600, 4000)), num_splits=0)
     assert s1 > 1
     # second call, smaller in every dimension, partitions again: stale records of the first call lie around it
     s2 = _run_both(saw, synth.make_workload("tiny", batch=2, ctx=(70, 200)), num_splits=3)
