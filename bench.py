@@ -700,6 +700,9 @@ def main():
             "highconc_head_dim64": other_decode(saw, dev, "highconc", head_dim=64, had_block=64, with_append=True),
             # mid-size ragged batch (384 items: partitions + merge) and equal lengths just above 2048 items
             "highconc_48_sequences": other_decode(saw, dev, "highconc", batch=48),
+            # small batch of short contexts: one block of eight wavefronts per (sequence, kv head), one launch
+            "small_32x2304": other_decode(saw, dev, "llama8b", batch=32, ctx=2304, with_append=True),
+            "small_4x2304": other_decode(saw, dev, "llama8b", batch=4, ctx=2304, with_append=True),
             "highconc_260_equal2304": other_decode(saw, dev, "highconc", batch=260, ctx=2304),
         }
         u = ex["other_decode"]["highconc_uniform2304"]["kv16_decode"]
