@@ -268,9 +268,10 @@ int saw_paged_decode_attn_static(const saw_cache_t* cache, const void* q, int32_
  * that of saw_rotate_quant_store(slots = (b, seq_lens[b])) followed by saw_paged_decode_attn
  * over seq_lens[b] + 1 tokens.  With head_dim 128, and with head_dim 64 when n_kv_heads is even
  * and a kv head serves at most 4 query heads, the decode kernel does the append itself: the
- * wavefront that starts a sequence quantises and stores the new token and seeds its softmax state
- * with it, which makes the step ONE kernel launch when there is one partition per sequence (large
- * batches), and the decode and merge kernels otherwise.  For the remaining head_dim 64 shapes the
+ * wavefront that starts a sequence also quantises the new token, attends to it from on-chip memory
+ * (nothing the call writes is read back by it) and stores it, which makes the step ONE kernel launch
+ * when there is one partition per sequence (large batches, and small batches of short contexts), and
+ * the decode and merge kernels otherwise.  For the remaining head_dim 64 shapes the
  * call enqueues the store and the decode kernels back to back.
  *
  *   K_new, V_new device, dense [B][n_kv_heads][head_dim] of kv_dtype (SAW_F16 | SAW_BF16),
