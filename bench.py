@@ -666,6 +666,19 @@ def main():
                                  "decode_only_vs_k_and_v": round(kd / med_d, 4)}
         del ck
         torch.cuda.empty_cache()
+        # learned per-layer rotation after the Hadamard (App. A.3; a seeded random orthogonal matrix stands in for it):
+        # the query, the appended token and the output take one more 128 x 128 product each
+        cl = saw.Cache(w.num_pages, w.n_kv_heads, w.head_dim, w.had_block, w.rotate_mask, device=dev,
+                       dense=synth.random_orthogonal(w.head_dim, 2))
+        fill(w, saw, dev, cl)
+        ld_, lf_ = time_interleaved([lambda: saw.paged_decode_attn(cl, q, pt, seq_lens, max_seq_len=max_len, out=out, workspace=ws,
+                                                                   order=order),
+                                     lambda: saw.append_decode_attn(cl, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0, out=out,
+                                                                    workspace=ws, order=order)], 50, 5)
+        ex["learned_rotation"] = {"decode_only_us": round(ld_, 2), "fused_step_us": round(lf_, 2),
+                                  "decode_only_vs_hadamard_only": round(ld_ / med_d, 4)}
+        del cl
+        torch.cuda.empty_cache()
         progress("read ceiling and K-only done")
         ex["prefill_store_sweep"] = store_sweep(saw, dev)
         progress("store sweep done")
