@@ -22,7 +22,8 @@ def saw():
                                      ("highconc", dict(batch=80, ctx=(1, 200))),      # ... 640: pair blocks of four
                                      ("highconc", dict(batch=200, ctx=(1, 120))),     # ... 1600: pair blocks of two
                                      ("highconc", dict(batch=150, ctx=(1, 150), head_dim=64, had_block=64)),  # head pairs
-                                     ("tiny", dict(batch=3, ctx=(130, 700)))])         # split-KV + merge kernel
+                                     ("tiny", dict(batch=3, ctx=(130, 700))),          # small batch: blocks of eight wavefronts, one launch
+                                     ("tiny", dict(batch=3, ctx=(2600, 3000)))])       # split-KV + merge kernel
 def test_decode_step_replays_from_a_graph(saw, name, kw):
     w = synth.make_workload(name, **kw)
     cache, _, _, pt = gc.fill_caches(w, saw, with_ref=False)
