@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256) void decode_int4_kernel(DecodeParams p) {
   constexpr int TPW = 64 / LPT;        // tokens per wave pass
   constexpr int CPL = D / LPT;         // codes per lane
   constexpr int WPL = CPL / 8;         // dwords per lane
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // (the partition index is rotated by kv head and sequence, so that no XCD serves a fixed set of partitions)
+  const int split = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int t_begin = split * p.chunk_tokens;
@@ -200,7 +201,8 @@ __global__ __launch_bounds__(256) void decode_kv16_kernel(DecodeParams p) {
   constexpr int TPW = 64 / LPT;
   constexpr int CPL = D / LPT;         // elements per lane
   constexpr int WPL = CPL / 2;         // dwords per lane
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // (the partition index is rotated by kv head and sequence, so that no XCD serves a fixed set of partitions)
+  const int split = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int L = min(p.seq_lens[b] + p.len_bias, p.bound);
   const int t_begin = split * p.chunk_tokens;

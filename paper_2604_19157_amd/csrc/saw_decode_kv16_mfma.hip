@@ -71,7 +71,8 @@ __global__ __launch_bounds__(PAIR ? 128 : 64) void decode_kv16_mfma_kernel(Decod
   using namespace kv16;
   constexpr int D = 128;
   constexpr int NWV = PAIR ? 2 : 1;
-  const int split = blockIdx.x, kvh = blockIdx.y;
+  // (the partition index is rotated by kv head and sequence, so that no XCD serves a fixed set of partitions)
+  const int split = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x, kvh = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int row16 = lane & 15, grp = lane >> 4;

@@ -318,7 +318,12 @@ void decode_int4_mfma_kernel(DecodeParams p) {
   constexpr int NH = (G > 4) ? 4 : G;          // heads per lane in the softmax layout
   constexpr int LO = (G > 4) ? 8 : 4;          // first row of the lo limbs of P
   constexpr int STEP = PAIR ? 1 : NW;          // batch stride of a wavefront inside its range
-  const int split = blockIdx.x;
+  // (which partition a block takes is rotated by its kv head and sequence: blocks go to the XCDs round
+  // robin in launch order, and with the partition index as the fastest grid index and a partition count
+  // that shares a factor with 8 every XCD would serve a fixed set of partition indices - of a ragged
+  // batch the later partitions are mostly empty, so some XCDs got most of the work: 33 sequences x 8
+  // partitions 41 us against 28-32 us with 7 or 9 partitions)
+  const int split = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x;
   const int kvh = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
