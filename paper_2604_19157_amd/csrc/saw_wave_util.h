@@ -175,41 +175,50 @@ __device__ __forceinline__ void wave_lds_fwht128(float* x, int h, int lane) {
 
 // In-place x <- x M for NV vectors of 128 floats in LDS, run by one wavefront: out[v][j] =
 // sum_i x[v][i] M[i][j] with M a global fp32 [128][128] row-major matrix (the learned rotation of
-// App. A.3 or its transpose).  Lane j computes columns j and j + 64 of every vector (coalesced rows
-// of M, broadcast reads of x) with four partial sums per output (i mod 4), so that the rounding error
-// stays near that of a pairwise sum.
+// App. A.3 or its transpose).  Lane l takes four consecutive columns 4 (l % 32) .. + 3 and the rows of
+// half l / 32 (rows 64 h .. 64 h + 63): every load is 16 bytes, a load instruction covers two whole rows
+// of M, and the 64 loads of a lane go out in four rounds of 16 (what bounds this routine is the latency
+// of M coming from L2 while every wavefront of the chip asks for it, so few, wide rounds matter).  Two
+// partial sums per output and half (rows of even and odd index), added pairwise at the end, keep the
+// rounding error near that of a pairwise sum.
 template <int NV>
 __device__ __forceinline__ void wave_lds_matvec128(float* x, const float* __restrict__ M, int lane) {
+  const int half = lane >> 5, cq = lane & 31;
   float acc[NV][2][4];
 #pragma unroll
   for (int v = 0; v < NV; ++v)
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int e = 0; e < 2; ++e)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc[v][c][u] = 0.f;
-#pragma unroll 4
-  for (int i0 = 0; i0 < 128; i0 += 4) {
-    float m0[4], m1[4];
+      for (int c = 0; c < 4; ++c) acc[v][e][c] = 0.f;
+  const float* const mbase = M + (64 * half) * 128 + 4 * cq;
+#pragma unroll 1
+  for (int t = 0; t < 4; ++t) {
+    f32x4 m[16];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      m0[u] = M[(i0 + u) * 128 + lane];
-      m1[u] = M[(i0 + u) * 128 + 64 + lane];
-    }
+    for (int u = 0; u < 16; ++u) m[u] = *(const f32x4*)(mbase + (16 * t + u) * 128);
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      const f32x4 xv = *(const f32x4*)(x + v * 128 + i0);
+      const float* xr = x + v * 128 + 64 * half + 16 * t;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        acc[v][0][u] = fmaf(xv[u], m0[u], acc[v][0][u]);
-        acc[v][1][u] = fmaf(xv[u], m1[u], acc[v][1][u]);
+      for (int u4 = 0; u4 < 4; ++u4) {
+        const f32x4 xv = *(const f32x4*)(xr + 4 * u4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int u = 4 * u4 + k;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[v][u & 1][c] = fmaf(xv[k], m[u][c], acc[v][u & 1][c]);
+        }
       }
     }
   }
   wave_sync();                                               // every read of x is done
 #pragma unroll
   for (int v = 0; v < NV; ++v) {
-    x[v * 128 + lane] = (acc[v][0][0] + acc[v][0][1]) + (acc[v][0][2] + acc[v][0][3]);
-    x[v * 128 + 64 + lane] = (acc[v][1][0] + acc[v][1][1]) + (acc[v][1][2] + acc[v][1][3]);
+    f32x4 r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r[c] = add_xor32(acc[v][0][c] + acc[v][1][c]);   // the two halves of the rows
+    if (half == 0) *(f32x4*)(x + v * 128 + 4 * cq) = r;
   }
   wave_sync();
 }
