@@ -502,9 +502,10 @@ def main():
     ws = torch.empty(saw.decode_workspace_bytes(cache, B, w.n_q_heads, max_len, args.num_splits), dtype=torch.uint8, device=dev)
     splits, chunk = saw.decode_plan(cache, B, max_len, args.num_splits)
     fused = args.num_splits == 0
-    # The longest-first order of the batch, as a serving scheduler keeps it: it knows every sequence's length
-    # on the host, so this is a host-side sort outside the step, handed to the call like the page table is.
-    order = None if args.no_order_hint else torch.from_numpy(np.argsort(-lens0, kind="stable").astype(np.int32)).to(dev)
+    # The longest-first order of the batch: computed once per decode step (it depends on the lengths only, so one
+    # order serves the attention calls of all layers of the step), here on the device by saw_decode_order from the
+    # device-resident lengths; handed to the call like the page table is.  Its own cost is in extra.decode_order_us.
+    order = None if args.no_order_hint else saw.decode_order(seq_lens0, max_len0)
 
     def store_step():
         saw.rotate_quant_store(cache, newK, newV, pt, new_slots)
@@ -586,7 +587,8 @@ def main():
                    "tokens_cached": int(lens1.sum()), "splits": splits, "chunk_tokens": chunk,
                    "bytes_per_step": dbytes + sbytes,
                    "call": ("saw_append_decode_attn" if order is None else "saw_append_decode_attn_hinted (the caller hands over the "
-                            "longest-first order of the batch, a host-side sort of the lengths kept outside the step; "
+                            "longest-first order of the batch, computed once per decode step - i.e. once for all layers - by "
+                            "saw_decode_order, outside the timed per-layer step: extra.decode_order_us; "
                             "extra.without_order_hint has the same step with the kernel ranking the sequences itself)")
                            if fused else "saw_rotate_quant_store + saw_paged_decode_attn"},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
@@ -628,6 +630,7 @@ def main():
         ex["unfused_step_ms"] = round(wall_ms(unfused_step), 5)
         ex["fused_step_ms"] = round(wall_ms(fused_step), 5)
         if order is not None:
+            ex["decode_order_us"] = round(time_calls(lambda: saw.decode_order(seq_lens0, max_len0), 50, 5)[0], 2)
             # the same calls without the caller's order: every block ranks the 256 lengths itself first
             a, b = time_interleaved([lambda: saw.append_decode_attn(cache, newK, newV, q, pt, seq_lens0, max_seq_len=max_len0,
                                                                     out=out, workspace=ws),

@@ -220,6 +220,16 @@ int saw_paged_decode_attn(const saw_cache_t* cache, const void* q, int32_t q_dty
  * items); hints == NULL or order == NULL: the kernels rank the sequences themselves, which is what
  * saw_paged_decode_attn / saw_append_decode_attn do.  Everything else as in those calls.
  */
+/*
+ * saw_decode_order computes such an order on the device from the device-resident lengths (exactly
+ * longest first after clamping to max_seq_len, <= 0: no clamp; ties in index order, so empty sequences
+ * come last), without a host read: one small launch per decode step, whose result serves the hinted
+ * call of every layer of the step.  seq_lens, order_out: device, B int32 each; B <= 1024 (larger
+ * batches do not use an order).
+ */
+int saw_decode_order(const int32_t* seq_lens, int32_t B, int32_t max_seq_len, int32_t* order_out,
+                     saw_stream_t stream);
+
 typedef struct saw_decode_hints {
   const int32_t* order;
 } saw_decode_hints_t;

@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.saw_rotate_quant_store.argtypes = [cp, vp, vp, i32, i64, i64, vp, i32, i32, vp, vp]
         L.saw_rotate_quant_store_layers.argtypes = [cp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i64, i64, vp, i32,
                                                     i32, vp, vp]
+        L.saw_decode_order.argtypes = [vp, i32, i32, vp, vp]
         L.saw_read_probe.argtypes = [cp, vp, i64, vp, sz, vp]
         L.saw_plain_quant_store_valu.argtypes = [cp, vp, vp, i32, i64, i64, vp, i32, i32, vp, vp]
         L.saw_decode_workspace_bytes.restype = sz
@@ -171,6 +172,15 @@ def rotate_quant_store_layers(caches, Ks, Vs, page_table, slots):
     _check(lib().saw_rotate_quant_store_layers(sts, kp, vp_, n, _DT[Ks[0].dtype], T, stride, _ptr(page_table),
                                                page_table.shape[0], page_table.shape[1], _ptr(slots), _stream()),
            "saw_rotate_quant_store_layers")
+
+
+def decode_order(seq_lens, max_seq_len=0):
+    """saw_decode_order: the longest-first order of the batch, computed on the device (int32 device tensors)."""
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous()
+    order = torch.empty_like(seq_lens)
+    _check(lib().saw_decode_order(_ptr(seq_lens), seq_lens.numel(), int(max_seq_len), _ptr(order), _stream()),
+           "saw_decode_order")
+    return order
 
 
 def read_probe(cache: Cache, page_ids, sink=None):

@@ -17,6 +17,7 @@ namespace saw {
 int launch_store(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*,
                  int32_t, int32_t, const int32_t*, const int32_t*, int32_t, hipStream_t);
 int launch_prepare_dense(const float*, void*, hipStream_t);
+int launch_decode_order(const int32_t*, int, int, int32_t*, hipStream_t);
 int launch_read_probe(const saw_cache_t*, const int32_t*, int64_t, void*, int32_t, hipStream_t);
 int launch_plain_store_valu(const saw_cache_t*, const void*, const void*, int, int64_t, int64_t, const int32_t*, int32_t,
                             int32_t, const int32_t*, hipStream_t);
@@ -284,6 +285,12 @@ int saw_decode_rank_order(const int32_t* seq_lens_host, int32_t B, int32_t max_s
     for (int b = 0; b < B; ++b)
       if (cls[b] == c) order_out[n++] = b;
   return SAW_OK;
+}
+
+int saw_decode_order(const int32_t* seq_lens, int32_t B, int32_t max_seq_len, int32_t* order_out, saw_stream_t stream) {
+  if (!seq_lens || !order_out) return SAW_ENULL;
+  if (B < 1 || B > 1024) return SAW_EINVAL;
+  return launch_decode_order(seq_lens, B, max_seq_len <= 0 ? 0x7fffffff : max_seq_len, order_out, (hipStream_t)stream);
 }
 
 static int decode_common(const saw_cache_t* c, bool kv16, const void* kp, const void* vp, int kv_dtype,

@@ -65,6 +65,32 @@ __global__ __launch_bounds__(64) void read_probe_kernel(ReadProbeParams p) {
   if (lane == 0) p.sink[blockIdx.x] = r;
 }
 
+// ---------------------------------------------------------------------------------------
+// The longest-first order of a batch, computed on the device (no host read of the lengths): thread i
+// counts the sequences that come before sequence i - longer (after clamping to the bound), or equally
+// long with a lower index - and writes i at that rank.  One block; B <= 1024.  Run once per decode step,
+// the order then serves every layer's hinted decode call.
+__global__ __launch_bounds__(1024) void decode_order_kernel(const int32_t* __restrict__ seq_lens, int B, int bound,
+                                                            int32_t* __restrict__ order) {
+  __shared__ int lens[1024];
+  const int i = threadIdx.x;
+  if (i < B) lens[i] = max(min(seq_lens[i], bound), 0);
+  __syncthreads();
+  if (i >= B) return;
+  const int mine = lens[i];
+  int rank = 0;
+  for (int j = 0; j < B; ++j) {
+    const int l = lens[j];
+    rank += (l > mine || (l == mine && j < i)) ? 1 : 0;
+  }
+  order[rank] = i;
+}
+
+int launch_decode_order(const int32_t* seq_lens, int B, int bound, int32_t* order, hipStream_t st) {
+  decode_order_kernel<<<dim3(1), dim3(1024), 0, st>>>(seq_lens, B, bound, order);
+  return hipGetLastError() == hipSuccess ? SAW_OK : SAW_ELAUNCH;
+}
+
 int launch_read_probe(const saw_cache_t* c, const int32_t* page_ids, int64_t n_pages, void* sink, int32_t n_waves,
                       hipStream_t st) {
   ReadProbeParams p;

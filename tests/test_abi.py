@@ -222,6 +222,9 @@ def test_store_layers_and_dense_rotation_reject_bad_arguments(saw):
     assert L.saw_rotate_quant_store(ctypes.byref(st), P(16), P(16), 1, 4, 128, P(16), 1, 4, P(16), P(0)) == -1
     st = _struct(saw, dense_rot=8)                                    # misaligned prepared buffer
     assert L.saw_rotate_quant_store(ctypes.byref(st), P(16), P(16), 1, 4, 256, P(16), 1, 4, P(16), P(0)) == -1
+    # device-side order: pointers and batch size
+    assert L.saw_decode_order(P(0), 4, 0, P(16), P(0)) == -2 and L.saw_decode_order(P(16), 4, 0, P(0), P(0)) == -2
+    assert L.saw_decode_order(P(16), 0, 0, P(16), P(0)) == -1 and L.saw_decode_order(P(16), 1025, 0, P(16), P(0)) == -1
     # flatten cannot rotate a learned rotation back
     st = _struct(saw, dense_rot=16)
     assert L.saw_flatten_dequant(ctypes.byref(st), P(16), 4, 0, 0, 8, 1, 2, P(16), P(16), 256, P(0)) == -1

@@ -274,6 +274,22 @@ def test_caller_supplied_order(saw, B, Hkv):
     torch.cuda.synchronize()
 
 
+def test_device_side_order_matches_a_stable_host_sort(saw):
+    """saw_decode_order: exactly longest first (after clamping), ties by index, empty sequences last; and the
+    hinted decode call accepts it as it is."""
+    rng = np.random.default_rng(9)
+    for B, top, bound in [(1, 5, 0), (7, 3, 0), (256, 4096, 0), (300, 100, 50), (1024, 70, 0)]:
+        lens = rng.integers(0, top + 1, size=B).astype(np.int32)
+        lens[rng.random(B) < 0.2] = 0
+        got = saw.decode_order(torch.from_numpy(lens).cuda(), bound).cpu().numpy()
+        eff = np.minimum(lens, bound) if bound > 0 else lens
+        assert np.array_equal(got, np.argsort(-eff, kind="stable"))
+    lens = rng.integers(0, 330, size=200)
+    w = synth.make_workload("highconc", batch=200, seq_lens=lens)
+    order = saw.decode_order(torch.from_numpy(w.seq_lens).cuda()).cpu().numpy()
+    _decode_case(saw, w, num_splits=1, end_to_end=False, order=order)
+
+
 LOOSE_WIDTH = 2048          # page-table columns of a table sized for 32768-token contexts
 
 
