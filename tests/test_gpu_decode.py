@@ -339,3 +339,26 @@ def test_blocks_of_four_over_three_sequences(saw, lens):
     sequences only."""
     w = synth.make_workload("highconc", batch=len(lens), seq_lens=lens)
     _decode_case(saw, w, end_to_end=False)
+
+
+@pytest.mark.parametrize("seed", range(200, 230))
+def test_schedules_agree(saw, seed):
+    """Whatever launch shape the plan picks (blocks of eight wavefronts, partitions with a merge pass, pair
+    blocks, longest-first order; ranking in the kernel or the caller's order) is only a schedule: on one cache
+    the automatic call, the call forced into three partitions, the call with one partition and the hinted
+    call agree to rounding (1e-4 of the largest output), under a tight and under the default bound."""
+    kw, _ = _random_case(seed)
+    w = synth.make_workload("highconc", **kw)
+    cache, _, _, pt = gc.fill_caches(w, saw, with_ref=False)
+    sl = torch.from_numpy(w.seq_lens).cuda()
+    q = synth.gen_q(w).cuda()
+    for bound in (int(w.seq_lens.max()), 0):
+        ref = saw.paged_decode_attn(cache, q, pt, sl, max_seq_len=bound, num_splits=3)
+        den = float(ref.abs().max()) or 1.0
+        outs = {"auto": saw.paged_decode_attn(cache, q, pt, sl, max_seq_len=bound),
+                "one partition": saw.paged_decode_attn(cache, q, pt, sl, max_seq_len=bound, num_splits=1)}
+        if w.batch <= 1024:
+            outs["caller's order"] = saw.paged_decode_attn(cache, q, pt, sl, max_seq_len=bound, order=saw.decode_order(sl, bound))
+        for name, o in outs.items():
+            assert torch.isfinite(o).all(), name
+            assert float((o - ref).abs().max()) / den < 1e-4, (name, bound, kw["batch"])
